@@ -1,0 +1,151 @@
+"""Pins of the oracle's attention forward and gradient (CPU only)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import entmax_oracle as eo
+
+RNG = np.random.default_rng(99)
+
+
+def rand(*shape, scale=1.0):
+    return RNG.normal(size=shape) * scale
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_forward_is_rowwise_entmax_times_v(alpha, causal):
+    B, H, N, d = 2, 2, 24, 5
+    Q, K, V = rand(B, H, N, d, scale=2), rand(B, H, N, d, scale=2), rand(B, H, N, d)
+    out = eo.attn_fwd(Q, K, V, alpha, causal, tile=8, want_P=True)
+    S = np.einsum("bhrc,bhjc->bhrj", Q, K) / np.sqrt(d)       # Eq. 2
+    for b in range(B):
+        for h in range(H):
+            for r in range(N):
+                nv = r + 1 if causal else N
+                p, tau = eo.entmax(S[b, h, r, :nv], alpha)
+                assert np.abs(out["P"][b, h, r, :nv] - p).max() < 1e-12
+                assert np.all(out["P"][b, h, r, nv:] == 0)
+                assert abs(out["tau"][b, h, r] - tau) < 1e-12
+    assert np.abs(out["O"] - out["P"] @ V).max() < 1e-12
+    assert np.abs(out["P"].sum(-1) - 1).max() < 1e-10
+    # margins: definition, from P's own support and the raw scores
+    X = (alpha - 1) * S - out["tau"][..., None]
+    if causal:
+        X = np.where(np.tril(np.ones((N, N), bool)), X, -np.inf)
+    Mg = X.reshape(B, H, N // 8, 8, N // 8, 8).max(axis=(3, 5))
+    assert np.array_equal(np.isinf(Mg), np.isinf(out["margin"]))
+    fin = np.isfinite(Mg)
+    assert np.abs(Mg[fin] - out["margin"][fin]).max() < 1e-12
+    blk = out["P"].reshape(B, H, N // 8, 8, N // 8, 8).max(axis=(3, 5)) > 0
+    assert np.array_equal(blk, out["margin"] > 0)
+
+
+def test_forward_identity_values_and_first_causal_row():
+    # V = I (d = N): O is P itself; causal row 0 sees one key: p = 1, tau = (alpha-1) s - 1
+    N = 12
+    Q, K = rand(1, 1, N, N), rand(1, 1, N, N)
+    V = np.eye(N)[None, None]
+    for alpha in (1.5, 2.0, 1.3):
+        out = eo.attn_fwd(Q, K, V, alpha, True, tile=4, want_P=True)
+        assert np.abs(out["O"] - out["P"]).max() < 1e-15
+        s00 = Q[0, 0, 0] @ K[0, 0, 0] / np.sqrt(N)
+        assert abs(out["tau"][0, 0, 0] - ((alpha - 1) * s00 - 1)) < 1e-12
+        assert abs(out["O"][0, 0, 0, 0] - 1) < 1e-12
+
+
+def test_forward_softmax_limit():
+    B, H, N, d = 1, 1, 10, 4
+    Q, K, V = rand(B, H, N, d), rand(B, H, N, d), rand(B, H, N, d)
+    S = torch.from_numpy(np.einsum("bhrc,bhjc->bhrj", Q, K) / np.sqrt(d))
+    ref = (torch.softmax(S, -1) @ torch.from_numpy(V)).numpy()
+    errs = [np.abs(eo.attn_fwd(Q, K, V, a, False, want_margin=False)["O"] - ref).max() for a in (1.1, 1.01, 1.001)]
+    assert errs[0] > errs[1] > errs[2] and errs[2] < 2e-3
+
+
+def loss(Q, K, V, dO, alpha, causal):
+    return float((eo.attn_fwd(Q, K, V, alpha, causal, want_margin=False)["O"] * dO).sum())
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_gradient_matches_finite_differences(alpha, causal):
+    B, H, N, d = 1, 2, 9, 4
+    Q, K, V, dO = rand(B, H, N, d, scale=1.5), rand(B, H, N, d, scale=1.5), rand(B, H, N, d), rand(B, H, N, d)
+    g = eo.attn_bwd(Q, K, V, dO, alpha, causal)
+    # the sort-based thresholds are exact; the bisection leaves ~1e-12 of noise in tau, which a
+    # difference quotient amplifies by 1/eps, so general alpha uses a wider stencil
+    eps, tol = (1e-6, 5e-7) if alpha in (1.5, 2.0) else (1e-4, 2e-6)
+    worst = 0.0
+    for name, X in (("dQ", Q), ("dK", K), ("dV", V)):
+        num = np.zeros_like(X)
+        it = np.nditer(X, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = X[idx]
+            X[idx] = old + eps; lp = loss(Q, K, V, dO, alpha, causal)
+            X[idx] = old - eps; lm = loss(Q, K, V, dO, alpha, causal)
+            X[idx] = old
+            num[idx] = (lp - lm) / (2 * eps)
+        err = np.abs(num - g[name]).max()
+        worst = max(worst, err)
+        # piecewise-smooth map: away from support changes central differences agree to O(eps^2)
+        assert err < tol, (name, err)
+
+
+def torch_entmax_attention(Q, K, V, alpha, causal):
+    """Differentiable construction independent of the oracle's backward formula: tau from a
+    sort (alpha in {1.5, 2}), autograd differentiates through the sort-based closed form."""
+    d = Q.shape[-1]
+    S = Q @ K.transpose(-1, -2) / d ** 0.5
+    N = S.shape[-1]
+    if causal:
+        S = S.masked_fill(~torch.tril(torch.ones(N, N, dtype=torch.bool)), -1e30)
+    X = (alpha - 1) * S
+    Xs, _ = torch.sort(X, dim=-1, descending=True)
+    k = torch.arange(1, N + 1, dtype=X.dtype)
+    if alpha == 2.0:
+        t = (Xs.cumsum(-1) - 1) / k
+    else:
+        mean = Xs.cumsum(-1) / k
+        mean_sq = (Xs ** 2).cumsum(-1) / k
+        disc = torch.clamp(mean ** 2 - (mean_sq - 1 / k), min=0)
+        t = mean - torch.sqrt(disc)
+    supp = (Xs > t).sum(-1, keepdim=True)
+    tau = t.gather(-1, supp - 1)
+    Y = torch.clamp(X - tau, min=0)
+    P = Y if alpha == 2.0 else Y ** 2
+    return P @ V, tau.squeeze(-1)
+
+
+@pytest.mark.parametrize("alpha", [1.5, 2.0])
+@pytest.mark.parametrize("causal", [False, True])
+def test_gradient_matches_autograd_through_sort(alpha, causal):
+    B, H, N, d = 2, 2, 33, 8
+    Qn, Kn, Vn, dOn = rand(B, H, N, d, scale=1.5), rand(B, H, N, d, scale=1.5), rand(B, H, N, d), rand(B, H, N, d)
+    Q, K, V = (torch.tensor(a, requires_grad=True) for a in (Qn, Kn, Vn))
+    O, tau = torch_entmax_attention(Q, K, V, alpha, causal)
+    (O * torch.from_numpy(dOn)).sum().backward()
+    fw = eo.attn_fwd(Qn, Kn, Vn, alpha, causal, want_margin=False)
+    assert np.abs(fw["O"] - O.detach().numpy()).max() < 1e-12
+    assert np.abs(fw["tau"] - tau.detach().numpy()).max() < 1e-12
+    g = eo.attn_bwd(Qn, Kn, Vn, dOn, alpha, causal)
+    for name, t in (("dQ", Q), ("dK", K), ("dV", V)):
+        assert np.abs(g[name] - t.grad.numpy()).max() < 1e-11, name
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+def test_gradient_invariants(alpha):
+    B, H, N, d = 1, 1, 40, 6
+    Q, K, V, dO = rand(B, H, N, d, scale=2), rand(B, H, N, d, scale=2), rand(B, H, N, d), rand(B, H, N, d)
+    g = eo.attn_bwd(Q, K, V, dO, alpha, True)
+    # rows of P sum to one -> sum_j dV_j = sum_r dO_r
+    assert np.abs(g["dV"].sum(2) - dO.sum(2)).max() < 1e-10
+    # shifting all scores of a row changes nothing: K -> K + 1 c^T gives the same loss, so
+    # sum_j dK_j must vanish (dS rows sum to zero)
+    assert np.abs(g["dK"].sum(2)).max() < 1e-10
+    # gradients vanish off the support (Sec. 3.3): a key nobody attends to gets dK = dV = 0
+    P = eo.attn_fwd(Q, K, V, alpha, True, want_margin=False, want_P=True)["P"]
+    unused = P[0, 0].max(0) == 0
+    assert unused.any()
+    assert np.all(g["dK"][0, 0, unused] == 0) and np.all(g["dV"][0, 0, unused] == 0)
