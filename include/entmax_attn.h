@@ -1,0 +1,121 @@
+/*
+ * entmax_attn.h - C ABI of the MI355X (gfx950) alpha-entmax attention library.
+ *
+ * The library computes, per (batch, head) and per query row r (AdaSplash-2 paper):
+ *     S = Q K^T / sqrt(d)                                              (Eq. 2)
+ *     P = [(alpha-1) S - tau]_+^{1/(alpha-1)},  sum_j P_rj = 1          (Eq. 3, Eq. 4)
+ *     O = P V                                                          (Eq. 2)
+ * with tau solved per row from an on-chip histogram of the centred scores followed by a
+ * safeguarded Halley/Newton refinement (Sec. 3.1-3.3, Alg. 1), and the gradient of
+ * sum(O * dO) with respect to Q, K, V (Sec. 3.3 "Backward pass", Alg. 2-3).  Key tiles
+ * whose probabilities are all zero are recorded in a bit-packed block mask (App. C.4) and
+ * skipped in the output phase and in both backward kernels.
+ *
+ * Conventions common to every entry point
+ *   - All tensor arguments are DEVICE pointers owned by the caller.  Tensors are
+ *     contiguous [B, H, N, d] with d fastest.  Inputs Q, K, V, dO have the element type
+ *     named by `dtype`; O, dQ, dK, dV, tau are always float32.
+ *   - N must be a positive multiple of 64 and at most 131072; d must be 64 or 128;
+ *     1 < alpha <= 2.
+ *   - Causal masking: key j is visible to query r iff j <= r.
+ *   - The library allocates nothing and never synchronises: all work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  Scratch
+ *     space is the caller's `workspace` (device memory, 256-byte aligned), of at least
+ *     entmax_attn_workspace_bytes(...) bytes.
+ *   - Return value: EA_OK (0) on success.  On any negative code nothing has been
+ *     enqueued, except EA_ERR_HIP where earlier launches of the same call may have been.
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef ENTMAX_ATTN_H
+#define ENTMAX_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { EA_F32 = 0, EA_BF16 = 1 } ea_dtype;
+
+enum {
+    EA_OK = 0,
+    EA_ERR_NULL = -1,       /* a required pointer is NULL */
+    EA_ERR_ALPHA = -2,      /* alpha not finite or outside (1, 2] */
+    EA_ERR_SHAPE = -3,      /* B, H <= 0, N not a positive multiple of 64 or > 131072, d not in {64, 128} */
+    EA_ERR_DTYPE = -4,      /* unknown ea_dtype */
+    EA_ERR_WORKSPACE = -5,  /* workspace NULL, misaligned or too small */
+    EA_ERR_HIP = -6         /* a HIP call failed; see entmax_attn_last_hip_error() */
+};
+
+/* Number of 64-bit counters at the start of the workspace (see entmax_attn_fwd). */
+#define EA_STATS_WORDS 16
+enum {
+    /* units: 64x32 score sub-tiles (64 streamed rows x 32 register-resident rows), the piece one
+     * wavefront computes per MFMA block pair; one matmul on a sub-tile is 2*64*32*d flops */
+    EA_STAT_TAU_TILES = 0,   /* sub-tiles scored by the max, histogram and refinement sweeps (1 matmul each) */
+    EA_STAT_OUT_TILES = 1,   /* sub-tiles scored by the output phase (2 matmuls each where P != 0) */
+    EA_STAT_DELTA_TILES = 2, /* sub-tiles visited by the delta sweep of the backward (2 matmuls each) */
+    EA_STAT_DQ_TILES = 3,    /* sub-tiles visited by the dQ sweep (3 matmuls each) */
+    EA_STAT_DKDV_TILES = 4,  /* sub-tiles visited by the dK/dV kernel (4 matmuls each) */
+    EA_STAT_SWEEPS = 5,      /* sum over work-groups of refinement sweeps run */
+    EA_STAT_MASK_TILES = 6   /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
+};
+
+/* Edge of the square score tiles that one bit of the block mask stands for (64). */
+int entmax_attn_mask_tile(void);
+
+/* Bytes of workspace needed by entmax_attn_fwd (is_bwd == 0) or entmax_attn_bwd
+ * (is_bwd != 0) for this problem; 0 if the shape or dtype is invalid. */
+size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, int causal, int is_bwd);
+
+/*
+ * Forward (Alg. 1): phases max -> histogram -> refinement (+ working mask) -> output.
+ *   Q, K, V     in   [B,H,N,d] of `dtype`
+ *   O           out  [B,H,N,d] float32
+ *   tau         out  [B,H,N]   float32, raw convention: P = [(alpha-1) S - tau]_+^{1/(alpha-1)}
+ *   block_mask  out  [B,H,N/64,ceil(N/64/32)] int32; bit k of word m of row i is set iff some
+ *                    P > 0 (at the returned tau) in the 64x64 tile (i, 32m+k) (App. C.4);
+ *                    bits of tiles above the causal diagonal and padding bits are 0
+ *   iters       out  [B,H,N] int32, may be NULL: number of refinement iterations the row
+ *                    needed; one iteration = one evaluation of f, f', f'' over the true scores
+ *                    followed by one update (Sec. 3.3 Phase 3)
+ * The first EA_STATS_WORDS uint64 of `workspace` are zeroed by the call and then hold the
+ * executed-tile counters of this call (EA_STAT_*), readable after the stream has drained.
+ */
+int entmax_attn_fwd(const void* Q, const void* K, const void* V,
+                    float* O, float* tau, int32_t* block_mask, int32_t* iters,
+                    int B, int H, int N, int d, ea_dtype dtype, float alpha, int causal,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward (Alg. 2-3): delta sweep + dQ kernel over mask rows, dK/dV kernel over mask columns.
+ *   Q, K, V, dO in   [B,H,N,d] of `dtype`
+ *   O           in   accepted for signature parity with Alg. 2-3, not read (may be NULL)
+ *   tau         in   [B,H,N] float32 as returned by the forward
+ *   block_mask  in   as returned by the forward, or NULL: then it is rebuilt from tau with one
+ *                    dense score sweep
+ *   dQ, dK, dV  out  [B,H,N,d] float32, overwritten
+ * Counters as for the forward.
+ */
+int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                    const float* tau, const int32_t* block_mask,
+                    float* dQ, float* dK, float* dV,
+                    int B, int H, int N, int d, ea_dtype dtype, float alpha, int causal,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, human-readable text for a return code. */
+const char* entmax_attn_strerror(int code);
+
+/* hipError_t (as int) of the most recent failing HIP call made by this library on the calling
+ * thread, 0 if none. */
+int entmax_attn_last_hip_error(void);
+
+/* Histogram bins B and work-group query rows used by the threshold kernel (introspection for
+ * tests and the benchmark report). */
+int entmax_attn_histogram_bins(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENTMAX_ATTN_H */

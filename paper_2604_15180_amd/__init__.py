@@ -1,0 +1,8 @@
+"""MI355X-native fused alpha-entmax attention (AdaSplash-2 hot path): thin binding over the
+C ABI in include/entmax_attn.h.  All arithmetic runs in the HIP library; this package only
+marshals arguments.  There is no CPU fallback: without the built library, calls raise."""
+from .binding import (  # noqa: F401
+    EntmaxAttnError, entmax_attn_bwd, entmax_attn_fwd, entmax_attn_histogram_bins,
+    entmax_attn_mask_tile, entmax_attn_strerror, entmax_attn_workspace_bytes, lib, lib_path,
+    read_stats, STAT_NAMES,
+)

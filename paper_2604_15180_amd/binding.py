@@ -1,0 +1,153 @@
+"""ctypes binding of libentmax_attn.so (same names as the C entry points).
+
+PyTorch is used for device memory and the current HIP stream only.  Outputs are allocated
+here; every step of the path runs inside the library's kernels.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libentmax_attn.so")
+_lib = None
+
+EA_F32, EA_BF16 = 0, 1
+EA_STATS_WORDS = 16
+STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
+              "sweeps", "mask_subtiles")
+
+
+class EntmaxAttnError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"entmax_attn error {code}: {text}")
+        self.code = code
+
+
+def lib_path():
+    return _LIB_PATH
+
+
+def lib():
+    """Load the built library (build it first with __graft_entry__.build() or
+    `python -m paper_2604_15180_amd.build`); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is not built; run `python paper_2604_15180_amd/build.py` (needs hipcc). "
+                "There is no fallback path.")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+        L.entmax_attn_mask_tile.restype = ci
+        L.entmax_attn_mask_tile.argtypes = []
+        L.entmax_attn_histogram_bins.restype = ci
+        L.entmax_attn_histogram_bins.argtypes = []
+        L.entmax_attn_last_hip_error.restype = ci
+        L.entmax_attn_last_hip_error.argtypes = []
+        L.entmax_attn_workspace_bytes.restype = sz
+        L.entmax_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci, ci]
+        L.entmax_attn_fwd.restype = ci
+        L.entmax_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+        L.entmax_attn_bwd.restype = ci
+        L.entmax_attn_bwd.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+        L.entmax_attn_strerror.restype = ctypes.c_char_p
+        L.entmax_attn_strerror.argtypes = [ci]
+        _lib = L
+    return _lib
+
+
+def entmax_attn_mask_tile():
+    return int(lib().entmax_attn_mask_tile())
+
+
+def entmax_attn_histogram_bins():
+    return int(lib().entmax_attn_histogram_bins())
+
+
+def entmax_attn_strerror(code):
+    return lib().entmax_attn_strerror(int(code)).decode()
+
+
+def entmax_attn_workspace_bytes(B, H, N, d, dtype, causal, is_bwd):
+    return int(lib().entmax_attn_workspace_bytes(B, H, N, d, _dtype_code(dtype), int(bool(causal)), int(bool(is_bwd))))
+
+
+def _dtype_code(dtype):
+    if dtype in (torch.float32, "f32", EA_F32):
+        return EA_F32
+    if dtype in (torch.bfloat16, "bf16", EA_BF16):
+        return EA_BF16
+    return 99   # the library answers EA_ERR_DTYPE
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _check(rc):
+    if rc != 0:
+        text = entmax_attn_strerror(rc)
+        if rc == -6:
+            text += f" (hipError {lib().entmax_attn_last_hip_error()})"
+        raise EntmaxAttnError(rc, text)
+
+
+def _workspace(nbytes, device):
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def _prep(*tensors):
+    first = tensors[0]
+    for t in tensors:
+        if not t.is_cuda:
+            raise ValueError("entmax_attn: tensors must live on the GPU (there is no CPU path)")
+        if not t.is_contiguous() or t.shape != first.shape or t.dtype != first.dtype:
+            raise ValueError("entmax_attn: Q, K, V, dO must be contiguous [B,H,N,d] of one dtype")
+    return first.shape
+
+
+def entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=False, workspace=None):
+    """-> (O, tau, block_mask) or (O, tau, block_mask, iters).  The workspace used is kept in
+    `entmax_attn_fwd.last_workspace` so that read_stats() can fetch the tile counters."""
+    B, H, N, d = _prep(Q, K, V)
+    dev = Q.device
+    T = N // 64 if N % 64 == 0 else 0
+    O = torch.empty((B, H, N, d), dtype=torch.float32, device=dev)
+    tau = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    mask = torch.empty((B, H, max(T, 1), max((T + 31) // 32, 1)), dtype=torch.int32, device=dev)
+    iters = torch.empty((B, H, N), dtype=torch.int32, device=dev) if want_iters else None
+    nbytes = entmax_attn_workspace_bytes(B, H, N, d, Q.dtype, causal, False)
+    ws = workspace if workspace is not None else _workspace(nbytes, dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    rc = lib().entmax_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(mask), _ptr(iters),
+                               B, H, N, d, _dtype_code(Q.dtype), float(alpha), int(bool(causal)),
+                               _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    _check(rc)
+    entmax_attn_fwd.last_workspace = ws
+    return (O, tau, mask, iters) if want_iters else (O, tau, mask)
+
+
+def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspace=None):
+    """-> (dQ, dK, dV).  block_mask=None makes the library rebuild the mask from tau."""
+    B, H, N, d = _prep(Q, K, V, dO)
+    dev = Q.device
+    dQ = torch.empty((B, H, N, d), dtype=torch.float32, device=dev)
+    dK = torch.empty_like(dQ)
+    dV = torch.empty_like(dQ)
+    nbytes = entmax_attn_workspace_bytes(B, H, N, d, Q.dtype, causal, True)
+    ws = workspace if workspace is not None else _workspace(nbytes, dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    rc = lib().entmax_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
+                               _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, d, _dtype_code(Q.dtype), float(alpha),
+                               int(bool(causal)), _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    _check(rc)
+    entmax_attn_bwd.last_workspace = ws
+    return dQ, dK, dV
+
+
+def read_stats(workspace):
+    """Executed-tile counters of the last call that used `workspace` (synchronises)."""
+    vals = workspace[: EA_STATS_WORDS * 8].view(torch.int64).cpu().tolist()
+    return dict(zip(STAT_NAMES, vals))

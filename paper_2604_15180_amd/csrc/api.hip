@@ -1,0 +1,239 @@
+// Host side of the C ABI declared in include/entmax_attn.h: argument checks, workspace
+// carving, kernel dispatch over (dtype, head dim, alpha mode).  No allocation, no
+// synchronisation: every launch goes to the caller's stream.
+#include "../../include/entmax_attn.h"
+
+#include <math.h>
+
+#include "bwd_kernels.hpp"
+#include "fwd_kernels.hpp"
+
+namespace {
+
+using namespace ea;
+
+constexpr int QB = 1;        // 32*QB query rows per wave, 128*QB per work-group
+constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
+constexpr int MAX_SWEEPS = 12;
+
+thread_local int g_last_hip_error = 0;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Layout {
+    size_t stats, a, b, c, delta, mask, wmask, total;
+};
+
+// element size of the transposed copies
+inline size_t t_elem(ea_dtype t) { return t == EA_BF16 ? 2 : 4; }
+
+Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
+    Layout L{};
+    const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
+    size_t off = 0;
+    L.stats = off; off += align256(EA_STATS_WORDS * 8);
+    L.a = off; off += align256(BH * N * d * t_elem(t));          // V^T
+    L.wmask = off; off += align256(BH * T * W * 4);
+    L.total = off;
+    return L;
+}
+Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
+    Layout L{};
+    const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
+    size_t off = 0;
+    L.stats = off; off += align256(EA_STATS_WORDS * 8);
+    L.a = off; off += align256(BH * N * d * t_elem(t));          // K^T
+    L.b = off; off += align256(BH * N * d * t_elem(t));          // Q^T
+    L.c = off; off += align256(BH * N * d * t_elem(t));          // dO^T
+    L.delta = off; off += align256(BH * N * 4);
+    L.mask = off; off += align256(BH * T * W * 4);               // rebuilt mask (mask == NULL)
+    L.wmask = off; off += align256(BH * T * W * 4);
+    L.total = off;
+    return L;
+}
+
+int check_common(int B, int H, int N, int d, ea_dtype t, float alpha) {
+    if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
+    if (B <= 0 || H <= 0 || N <= 0 || N % 64 != 0 || N > 131072 || (d != 64 && d != 128)) return EA_ERR_SHAPE;
+    if ((long)B * H > 65535) return EA_ERR_SHAPE;
+    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > 2.f) return EA_ERR_ALPHA;
+    return EA_OK;
+}
+
+int alpha_mode(float alpha) {
+    if (alpha == 1.5f) return ALPHA_15;
+    if (alpha == 2.0f) return ALPHA_20;
+    return ALPHA_GEN;
+}
+
+#define EA_HIP(expr)                                              \
+    do {                                                          \
+        hipError_t e_ = (expr);                                   \
+        if (e_ != hipSuccess) { g_last_hip_error = (int)e_; return EA_ERR_HIP; } \
+    } while (0)
+
+template <class K>
+int launch(K kernel, dim3 grid, size_t smem, hipStream_t s, Params p) {
+    // kernels above 64 KiB of dynamic LDS need the limit raised (cheap, idempotent)
+    EA_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(kernel, grid, dim3(THREADS), smem, s, p);
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
+template <class Ein, class Eout, int D>
+int launch_transpose(const void* in, void* out, int BH, int N, const unsigned int* amax_bits, hipStream_t s) {
+    hipLaunchKernelGGL((transpose_kernel<Ein, Eout, D>), dim3(N / 64, D / 64, BH), dim3(THREADS), 0, s,
+                       (const typename Ein::elem*)in, (typename Eout::elem*)out, N, amax_bits);
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
+// E: input element type; E2F: stage-2 operand type of the forward (P, V^T); E2B: of the backward
+template <class E, class E2F, class E2B, int D, int AM>
+struct Ops {
+    static int fwd(Params p, hipStream_t s) {
+        int rc = launch_transpose<E, E2F, D>(p.V, (void*)p.Vt, p.BH, p.N, nullptr, s);
+        if (rc) return rc;
+        const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
+        rc = launch(tau_kernel<E, D, QB, AM, NBINS>, grid, TauSmem<E, D, QB, NBINS>::BYTES, s, p);
+        if (rc) return rc;
+        return launch(out_kernel<E, E2F, D, QB, AM, false>, grid, OutSmem<E, E2F, D, QB, false>::BYTES, s, p);
+    }
+    static int bwd(Params p, bool rebuild_mask, hipStream_t s) {
+        int rc;
+        const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
+        if (rebuild_mask) {
+            hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
+            EA_HIP(hipGetLastError());
+            rc = launch(out_kernel<E, E2F, D, QB, AM, true>, grid, OutSmem<E, E2F, D, QB, true>::BYTES, s, p);
+            if (rc) return rc;
+        }
+        const unsigned int* go_amax = nullptr;
+        if (E2B::SCALED) {
+            hipLaunchKernelGGL((amax_kernel<E>), dim3(1024), dim3(THREADS), 0, s, (const typename E::elem*)p.dO,
+                               (long)p.BH * p.N * D, p.scal);
+            EA_HIP(hipGetLastError());
+            go_amax = p.scal;
+        }
+        if ((rc = launch_transpose<E, E2B, D>(p.K, (void*)p.Kt, p.BH, p.N, nullptr, s))) return rc;
+        if ((rc = launch_transpose<E, E2B, D>(p.Q, (void*)p.Qt, p.BH, p.N, nullptr, s))) return rc;
+        if ((rc = launch_transpose<E, E2B, D>(p.dO, (void*)p.dOt, p.BH, p.N, go_amax, s))) return rc;
+        rc = launch(dq_kernel<E, E2B, D, QB, AM>, grid, DqSmem<E, E2B, D, QB>::BYTES, s, p);
+        if (rc) return rc;
+        return launch(dkdv_kernel<E, E2B, D, QB, AM>, grid, DkdvSmem<E, E2B, D, QB>::BYTES, s, p);
+    }
+};
+
+template <class E, class E2F, class E2B, int D>
+int dispatch_alpha(bool is_bwd, Params p, bool rebuild, hipStream_t s) {
+    switch (alpha_mode(p.alpha)) {
+        case ALPHA_15: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_15>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_15>::fwd(p, s);
+        case ALPHA_20: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_20>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_20>::fwd(p, s);
+        default: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_GEN>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_GEN>::fwd(p, s);
+    }
+}
+
+int dispatch(bool is_bwd, ea_dtype t, int d, Params p, bool rebuild, hipStream_t s) {
+    // bf16 inputs: score-shaped products (Q K^T, dO V^T) on bf16 MFMA; the second-stage products
+    // (P V, dS K, P^T dO, dS^T Q) on fp16 MFMA: P lies in [0,1] and dS, dO are divided by known
+    // bounds first, so fp16's range suffices and its 3 extra mantissa bits keep the rounding of
+    // P and dS well inside the tolerances; bf16 values convert to fp16 exactly while
+    // 2^-14 <= |x| < 65504 (smaller ones within 2^-25 absolute).
+    if (t == EA_BF16) {
+        if (d == 64) return dispatch_alpha<Bf16, F16, F16, 64>(is_bwd, p, rebuild, s);
+        return dispatch_alpha<Bf16, F16, F16, 128>(is_bwd, p, rebuild, s);
+    }
+    if (d == 64) return dispatch_alpha<F32, F32, F32, 64>(is_bwd, p, rebuild, s);
+    return dispatch_alpha<F32, F32, F32, 128>(is_bwd, p, rebuild, s);
+}
+
+Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int causal) {
+    Params p{};
+    p.BH = B * H; p.N = N; p.T = N / 64; p.W = (p.T + 31) / 32;
+    p.causal = causal ? 1 : 0;
+    p.alpha = alpha;
+    p.inv_sqrt_d = 1.f / sqrtf((float)d);
+    p.c = (alpha - 1.f) * p.inv_sqrt_d;
+    p.r = 1.f / (alpha - 1.f);
+    p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
+    p.max_sweeps = MAX_SWEEPS;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int entmax_attn_mask_tile(void) { return ea::TILE; }
+int entmax_attn_histogram_bins(void) { return NBINS; }
+int entmax_attn_last_hip_error(void) { return g_last_hip_error; }
+
+size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype t, int causal, int is_bwd) {
+    (void)causal;
+    if (check_common(B, H, N, d, t, 1.5f) != EA_OK) return 0;
+    return is_bwd ? bwd_layout(B, H, N, d, t).total : fwd_layout(B, H, N, d, t).total;
+}
+
+int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
+                    int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, int causal,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!Q || !K || !V || !O || !tau || !block_mask) return EA_ERR_NULL;
+    int rc = check_common(B, H, N, d, t, alpha);
+    if (rc) return rc;
+    const Layout L = fwd_layout(B, H, N, d, t);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return EA_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Params p = base_params(B, H, N, d, t, alpha, causal);
+    p.Q = Q; p.K = K; p.V = V;
+    p.O = O; p.tau = tau; p.mask = block_mask; p.iters = iters;
+    p.stats = (unsigned long long*)(ws + L.stats);
+    p.Vt = ws + L.a;
+    p.wmask = (int32_t*)(ws + L.wmask);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, (unsigned int*)nullptr);
+    EA_HIP(hipGetLastError());
+    return dispatch(false, t, d, p, false, s);
+}
+
+int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
+                    const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
+                    ea_dtype t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    (void)O;
+    if (!Q || !K || !V || !dO || !tau || !dQ || !dK || !dV) return EA_ERR_NULL;
+    int rc = check_common(B, H, N, d, t, alpha);
+    if (rc) return rc;
+    const Layout L = bwd_layout(B, H, N, d, t);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return EA_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    hipStream_t s = (hipStream_t)hip_stream;
+    Params p = base_params(B, H, N, d, t, alpha, causal);
+    p.Q = Q; p.K = K; p.V = V; p.dO = dO;
+    p.tau = const_cast<float*>(tau);
+    p.dQ = dQ; p.dK = dK; p.dV = dV;
+    p.stats = (unsigned long long*)(ws + L.stats);
+    p.Kt = ws + L.a; p.Qt = ws + L.b; p.dOt = ws + L.c;
+    p.delta = (float*)(ws + L.delta);
+    p.wmask = (int32_t*)(ws + L.wmask);
+    const bool rebuild = (block_mask == nullptr);
+    p.mask = rebuild ? (int32_t*)(ws + L.mask) : const_cast<int32_t*>(block_mask);
+    p.scal = (unsigned int*)(ws + L.stats + EA_STATS_WORDS * 8);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, p.scal);
+    EA_HIP(hipGetLastError());
+    return dispatch(true, t, d, p, rebuild, s);
+}
+
+const char* entmax_attn_strerror(int code) {
+    switch (code) {
+        case EA_OK: return "ok";
+        case EA_ERR_NULL: return "a required pointer is NULL";
+        case EA_ERR_ALPHA: return "alpha must be finite and in (1, 2]";
+        case EA_ERR_SHAPE: return "bad shape: need B,H > 0, N a positive multiple of 64 (<= 131072), d in {64, 128}";
+        case EA_ERR_DTYPE: return "unknown dtype";
+        case EA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+        case EA_ERR_HIP: return "a HIP call failed (see entmax_attn_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

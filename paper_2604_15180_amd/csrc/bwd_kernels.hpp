@@ -1,0 +1,324 @@
+// Backward kernels (Sec. 3.3 "Backward pass", Alg. 2-3 of the AdaSplash-2 paper):
+//   dq_kernel   : per 128*QB query rows, over the set bits of their mask rows:
+//                 sweep A  delta_r = sum_j U_rj dP_rj / sum_j U_rj,  U = P^(2-alpha), dP = dO V^T
+//                 sweep B  dS = U (dP - delta),  dQ = dS K / sqrt(d)                  (Alg. 3)
+//   dkdv_kernel : per 128*QB keys, over the set bits of their mask columns:
+//                 dV += P^T dO,  dK += dS^T Q / sqrt(d)                               (Alg. 2)
+// With y = (alpha-1) s - tau on the support:  P = y^r,  U = y^(r-1),  r = 1/(alpha-1).
+#pragma once
+#include "common.hpp"
+
+namespace ea {
+
+template <class E, class E2, int D, int QB>
+struct DqSmem {
+    static constexpr int BR = 32 * QB * NWAVES;
+    static constexpr int MR = BR / 64;
+    static constexpr int RBYTES = RowTile<E, D>::BYTES;
+    static constexpr int CBYTES = ColTile<E2, D>::BYTES;
+    static constexpr int BYTES = 2 * RBYTES + CBYTES + 4 * (MR * MAX_W + MAX_T + 4);
+};
+
+template <class E, class E2, int D, int QB, int AM>
+__global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
+    using SM = DqSmem<E, E2, D, QB>;
+    using RT = RowTile<E, D>;
+    using CT = ColTile<E2, D>;
+    using elem = typename E::elem;
+    constexpr int BR = SM::BR, MR = SM::MR;
+    extern __shared__ __align__(16) char smem[];
+    char* kbuf = smem;
+    char* vbuf = smem + SM::RBYTES;
+    char* ktbuf = smem + 2 * SM::RBYTES;
+    uint32_t* fm = (uint32_t*)(smem + 2 * SM::RBYTES + SM::CBYTES);
+    int* tl = (int*)(fm + MR * MAX_W);
+    int* tl_count = tl + MAX_T;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
+    const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
+    const bool active = qw0 < N;
+    const long hoff = (long)bh * N * D;
+    const elem* Kh = (const elem*)p.K + hoff;
+    const elem* Vh = (const elem*)p.V + hoff;
+    const typename E2::elem* Kth = (const typename E2::elem*)p.Kt + hoff;
+    const int myrow = (wave * 32 * QB) / 64;
+    const float c = p.c, r = p.r;
+
+    for (int i = tid; i < MR * W; i += THREADS)
+        fm[i] = (I * MR + i / W < T) ? (uint32_t)p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
+    __syncthreads();
+    build_tile_list(fm, MR, W, tl, tl_count, tid);
+
+    Owned<E, D, QB> qf, gf;
+    load_owned<E, D, QB>(qf, (const elem*)p.Q + hoff, active ? qw0 : 0, lane);
+    load_owned<E, D, QB>(gf, (const elem*)p.dO + hoff, active ? qw0 : 0, lane);
+    float thr[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) thr[qb] = active ? p.tau[(long)bh * N + qw0 + 32 * qb + n] : 0.f;
+
+    Staged<RT::NCH> stk, stv;
+    Staged<CT::NCH> stkt;
+    f32x16 S[2][QB], dP[2][QB];
+    unsigned long long ntile_a = 0, ntile_b = 0;
+
+    // ---- sweep A: delta ----------------------------------------------------------------
+    float num[QB], den[QB], gmax[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
+    stream_tiles(
+        *tl_count,
+        [&](int it) {
+            const long j = tl[it];
+            gload_rows<E, D>(stk, Kh, j * 64, tid);
+            gload_rows<E, D>(stv, Vh, j * 64, tid);
+        },
+        [&]() { sstore_rows<E, D>(stk, kbuf, tid); sstore_rows<E, D>(stv, vbuf, tid); },
+        [&](int it) {
+            const int j = tl[it];
+            if (!mask_bit(fm, W, myrow, j)) return;
+            stage1<E, D, QB>(S, kbuf, qf, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, (long)j * 64, qw0, lane);
+            stage1<E, D, QB>(dP, vbuf, gf, lane);
+            ++ntile_a;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
+                        const float u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                        num[qb] = fmaf(u, dP[kb][qb][v], num[qb]);
+                        den[qb] += u;
+                        if constexpr (E2::SCALED) gmax[qb] = fmaxf(gmax[qb], (y > 0.f) ? fabsf(dP[kb][qb][v]) : 0.f);
+                    }
+        });
+    // |dS| = U |dP - delta| <= max_support |dP| + |delta| =: bound (U <= 1 since y < 1, r >= 1).
+    // With a narrow-range stage-2 type, dS / bound goes through the MFMA and the result is
+    // multiplied back per row; the largest bound is published for the dK/dV kernel.
+    float delta[QB], bound[QB], inv_bound[QB], out_scale[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float dn = xhalf_sum(den[qb]);
+        delta[qb] = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;
+        if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = delta[qb];
+        if constexpr (E2::SCALED) {
+            bound[qb] = xhalf_max(gmax[qb]) + fabsf(delta[qb]);
+            inv_bound[qb] = bound[qb] > 0.f ? 1.f / bound[qb] : 0.f;
+            out_scale[qb] = bound[qb] * p.inv_sqrt_d;
+        } else {
+            bound[qb] = 0.f; inv_bound[qb] = 1.f; out_scale[qb] = p.inv_sqrt_d;
+        }
+    }
+    if constexpr (E2::SCALED) {
+        float bm = 0.f;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) bm = fmaxf(bm, bound[qb]);
+        bm = wave_max(bm);
+        if (lane == 0 && active) atomicMax(&p.scal[1], __float_as_uint(bm));
+    }
+
+    // ---- sweep B: dQ -------------------------------------------------------------------
+    f32x16 X[D / 32][QB];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
+    stream_tiles(
+        *tl_count,
+        [&](int it) {
+            const long j = tl[it];
+            gload_rows<E, D>(stk, Kh, j * 64, tid);
+            gload_rows<E, D>(stv, Vh, j * 64, tid);
+            gload_cols<E2, D>(stkt, Kth, N, j * 64, tid);
+        },
+        [&]() {
+            sstore_rows<E, D>(stk, kbuf, tid);
+            sstore_rows<E, D>(stv, vbuf, tid);
+            sstore_cols<E2, D>(stkt, ktbuf, tid);
+        },
+        [&](int it) {
+            const int j = tl[it];
+            if (!mask_bit(fm, W, myrow, j)) return;
+            stage1<E, D, QB>(S, kbuf, qf, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, (long)j * 64, qw0, lane);
+            stage1<E, D, QB>(dP, vbuf, gf, lane);
+            ++ntile_b;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
+                        const float u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                        S[kb][qb][v] = u * (dP[kb][qb][v] - delta[qb]) * inv_bound[qb];
+                    }
+            stage2<E2, D, QB>(X, ktbuf, S, lane);
+        });
+    if (active) store_owned_T<D, QB>(p.dQ + hoff, qw0, X, out_scale, lane);
+    if (lane == 0) {
+        atomicAdd(&p.stats[2], ntile_a * QB);
+        atomicAdd(&p.stats[3], ntile_b * QB);
+    }
+}
+
+template <class E, class E2, int D, int QB>
+struct DkdvSmem {
+    static constexpr int BC = 32 * QB * NWAVES;
+    static constexpr int MC = BC / 64;
+    static constexpr int RBYTES = RowTile<E, D>::BYTES;
+    static constexpr int CBYTES = ColTile<E2, D>::BYTES;
+    static constexpr int BYTES = 2 * RBYTES + 2 * CBYTES + 4 * (2 * TILE + MAX_T + 16);
+};
+
+template <class E, class E2, int D, int QB, int AM>
+__global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
+    using SM = DkdvSmem<E, E2, D, QB>;
+    using RT = RowTile<E, D>;
+    using CT = ColTile<E2, D>;
+    using elem = typename E::elem;
+    constexpr int BC = SM::BC, MC = SM::MC;
+    extern __shared__ __align__(16) char smem[];
+    char* qbuf = smem;
+    char* gbuf = smem + SM::RBYTES;
+    char* qtbuf = smem + 2 * SM::RBYTES;
+    char* gtbuf = qtbuf + SM::CBYTES;
+    float* tau_s = (float*)(gtbuf + SM::CBYTES);
+    float* del_s = tau_s + TILE;
+    int* tl = (int*)(del_s + TILE);          // entries: query tile | column flags << 16
+    int* wcnt = tl + MAX_T;                  // per-wave counts + running total
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, J;
+    map_block(blockIdx.x, p.BH, (N + BC - 1) / BC, bh, J);
+    J = (N + BC - 1) / BC - 1 - J;            // causal: the first key tiles have the longest columns
+    const long k0 = (long)J * BC, kw0 = k0 + wave * 32 * QB;
+    const bool active = kw0 < N;
+    const long hoff = (long)bh * N * D;
+    const elem* Qh = (const elem*)p.Q + hoff;
+    const elem* Gh = (const elem*)p.dO + hoff;
+    const typename E2::elem* Qth = (const typename E2::elem*)p.Qt + hoff;
+    const typename E2::elem* Gth = (const typename E2::elem*)p.dOt + hoff;
+    // dO^T was stored divided by max|dO|, and dS is divided by the dq kernel's largest bound
+    float go_amax = 1.f, ds_bound = 1.f, ds_inv = 1.f;
+    if constexpr (E2::SCALED) {
+        go_amax = __uint_as_float(p.scal[0]);
+        if (!(go_amax > 0.f)) go_amax = 1.f;
+        ds_bound = __uint_as_float(p.scal[1]);
+        ds_inv = ds_bound > 0.f ? 1.f / ds_bound : 0.f;
+    }
+    const int mycol = (wave * 32 * QB) / 64;  // my mask column within the group
+    const int jc0 = J * MC;                   // first mask column of the group
+    const float c = p.c, r = p.r;
+
+    // ---- column walk of the row-packed mask: list of query tiles with a set bit -------------
+    const int i_min = p.causal ? jc0 : 0;
+    if (tid == 0) wcnt[4] = 0;
+    __syncthreads();
+    for (int base = i_min; base < T; base += THREADS) {
+        const int i = base + tid;
+        int flags = 0;
+        if (i < T) {
+#pragma unroll
+            for (int cidx = 0; cidx < MC; ++cidx) {
+                const int j = jc0 + cidx;
+                if (j >= T) continue;
+                const uint32_t w = (uint32_t)p.mask[((long)bh * T + i) * W + (j >> 5)];
+                flags |= (int)((w >> (j & 31)) & 1u) << cidx;
+            }
+        }
+        const unsigned long long bal = __ballot(flags != 0);
+        if (lane == 0) wcnt[wave] = __popcll(bal);
+        __syncthreads();
+        int off = wcnt[4];
+        for (int w2 = 0; w2 < wave; ++w2) off += wcnt[w2];
+        off += __popcll(bal & ((1ull << lane) - 1ull));
+        if (flags != 0) tl[off] = i | (flags << 16);
+        __syncthreads();
+        if (tid == 0) wcnt[4] += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        __syncthreads();
+    }
+    const int ntl = wcnt[4];
+
+    Owned<E, D, QB> kf, vf;
+    load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, active ? kw0 : 0, lane);
+    load_owned<E, D, QB>(vf, (const elem*)p.V + hoff, active ? kw0 : 0, lane);
+
+    f32x16 XV[D / 32][QB], XK[D / 32][QB];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { XV[db][qb][v] = 0.f; XK[db][qb][v] = 0.f; }
+
+    Staged<RT::NCH> stq, stg;
+    Staged<CT::NCH> stqt, stgt;
+    float st_vec = 0.f;
+    f32x16 S[2][QB], dP[2][QB];
+    unsigned long long ntile_done = 0;
+    stream_tiles(
+        ntl,
+        [&](int it) {
+            const long i = tl[it] & 0xffff;
+            gload_rows<E, D>(stq, Qh, i * 64, tid);
+            gload_rows<E, D>(stg, Gh, i * 64, tid);
+            gload_cols<E2, D>(stqt, Qth, N, i * 64, tid);
+            gload_cols<E2, D>(stgt, Gth, N, i * 64, tid);
+            if (tid < TILE) st_vec = p.tau[(long)bh * N + i * 64 + tid];
+            else if (tid < 2 * TILE) st_vec = p.delta[(long)bh * N + i * 64 + tid - TILE];
+        },
+        [&]() {
+            sstore_rows<E, D>(stq, qbuf, tid);
+            sstore_rows<E, D>(stg, gbuf, tid);
+            sstore_cols<E2, D>(stqt, qtbuf, tid);
+            sstore_cols<E2, D>(stgt, gtbuf, tid);
+            if (tid < 2 * TILE) tau_s[tid] = st_vec;     // tau_s and del_s are adjacent
+        },
+        [&](int it) {
+            const int ent = tl[it];
+            const long i = ent & 0xffff;
+            if (!((ent >> (16 + mycol)) & 1)) return;
+            stage1<E, D, QB>(S, qbuf, kf, lane);
+            // streamed rows are queries here: hide key > query
+            if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, i * 64, kw0, lane);
+            stage1<E, D, QB>(dP, gbuf, vf, lane);
+            ++ntile_done;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = trow(kb, v, h);
+                    const float tq = tau_s[row], dq = del_s[row];
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb) {
+                        const float y = fmaf(c, S[kb][qb][v], -tq);
+                        const bool on = y > 0.f;
+                        const float u = on ? pow_r1<AM>(y, r) : 0.f;
+                        float pr;
+                        if constexpr (AM == ALPHA_20) pr = on ? y : 0.f;
+                        else pr = on ? u * y : 0.f;
+                        S[kb][qb][v] = pr;
+                        dP[kb][qb][v] = u * (dP[kb][qb][v] - dq) * ds_inv;
+                    }
+                }
+            stage2<E2, D, QB>(XV, gtbuf, S, lane);
+            stage2<E2, D, QB>(XK, qtbuf, dP, lane);
+        });
+    if (active) {
+        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
+        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, ds_bound * p.inv_sqrt_d, lane);
+    }
+    if (lane == 0) atomicAdd(&p.stats[4], ntile_done * QB);
+}
+
+}  // namespace ea

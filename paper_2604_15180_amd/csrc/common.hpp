@@ -1,0 +1,126 @@
+// Pieces shared by the forward and backward kernels: parameter block, block->work mapping,
+// the entmax power functions, mask-word helpers, the tile streaming loop.
+#pragma once
+#include "tiles.hpp"
+
+namespace ea {
+
+constexpr int MAX_T = 2048;     // N <= 131072
+constexpr int MAX_W = 64;       // mask words per row
+constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
+
+struct Params {
+    const void* Q; const void* K; const void* V; const void* dO;
+    const void* Kt; const void* Vt; const void* Qt; const void* dOt;   // transposed copies [BH][d][N]
+    float* O; float* tau; float* delta;
+    float* dQ; float* dK; float* dV;
+    int32_t* mask;        // exported / final mask   [BH][T][W]
+    int32_t* wmask;       // working mask (superset) [BH][T][W]
+    int32_t* iters;       // nullable
+    unsigned long long* stats;
+    // bits of two non-negative floats kept in the workspace (atomicMax on the bit patterns):
+    // scal[0] = max |dO|, scal[1] = max over rows of the bound on |dS| (see dq_kernel)
+    unsigned int* scal;
+    int BH, N, T, W;
+    int causal;
+    float c;              // (alpha-1)/sqrt(d): x = c * <q,k>
+    float r;              // 1/(alpha-1)
+    float alpha;
+    float inv_sqrt_d;
+    float tol;
+    int max_sweeps;
+};
+
+// Consecutive block ids are dealt round-robin to the 8 XCDs (each with its own L2).  When the
+// number of heads divides by 8 every XCD gets whole heads, so the work-groups that run together
+// on one XCD stream the same K/V tiles.  Within a head the longest (causal: last) tiles go first.
+EA_DEV void map_block(int bid, int BH, int ntile, int& bh, int& I) {
+    int lin = bid;
+    if ((BH & 7) == 0) {
+        const int per = (BH >> 3) * ntile;
+        lin = (bid & 7) * per + (bid >> 3);
+    }
+    bh = lin / ntile;
+    I = ntile - 1 - (lin % ntile);
+}
+
+// y > 0:  y^r, y^(r-1), y^(r-2)  with r = 1/(alpha-1)
+template <int AM> EA_DEV float pow_r(float y, float r) {
+    if constexpr (AM == ALPHA_15) return y * y;
+    else if constexpr (AM == ALPHA_20) return y;
+    else return __builtin_amdgcn_exp2f(r * __builtin_amdgcn_logf(y));
+}
+template <int AM> EA_DEV float pow_r1(float y, float r) {
+    if constexpr (AM == ALPHA_15) return y;
+    else if constexpr (AM == ALPHA_20) return 1.f;
+    else return __builtin_amdgcn_exp2f((r - 1.f) * __builtin_amdgcn_logf(y));
+}
+template <int AM> EA_DEV float pow_r2(float y, float r) {
+    if constexpr (AM == ALPHA_15) return 1.f;
+    else if constexpr (AM == ALPHA_20) return 0.f;
+    else return __builtin_amdgcn_exp2f((r - 2.f) * __builtin_amdgcn_logf(y));
+}
+
+// Software-pipelined walk over `ntiles` streamed tiles with one LDS buffer set:
+// registers <- global(it+1) is issued before the math on tile `it`, so the loads fly under it.
+template <class LoadF, class StoreF, class ComputeF>
+EA_DEV void stream_tiles(int ntiles, LoadF gload, StoreF sstore, ComputeF compute) {
+    if (ntiles > 0) gload(0);
+    for (int it = 0; it < ntiles; ++it) {
+        sstore();
+        __syncthreads();
+        if (it + 1 < ntiles) gload(it + 1);
+        compute(it);
+        __syncthreads();
+    }
+}
+
+// Union of `rows` mask rows (LDS, `W` words each) -> ascending list of tile indices in LDS.
+// Called by all threads; the first wave does the work.  Uses one wave-wide exclusive scan of
+// the per-word popcounts (W <= 64).
+EA_DEV void build_tile_list(const uint32_t* words, int rows, int W, int* list, int* count, int tid) {
+    if (tid < 64) {
+        uint32_t u = 0;
+        if (tid < W)
+            for (int r = 0; r < rows; ++r) u |= words[r * W + tid];
+        const int cnt = __popc(u);
+        int incl = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(incl, off);
+            if (tid >= off) incl += t;
+        }
+        int pos = incl - cnt;
+        while (u) {
+            const int b = __ffs(u) - 1;
+            u &= u - 1;
+            list[pos++] = tid * 32 + b;
+        }
+        if (tid == 63) *count = incl;
+    }
+    __syncthreads();
+}
+
+EA_DEV bool mask_bit(const uint32_t* words, int W, int row, int j) {
+    return (words[row * W + (j >> 5)] >> (j & 31)) & 1u;
+}
+
+// Hide keys above the diagonal: element (tile row, owned row) of a stage-1 result with
+// streamed index s_idx = s0 + trow and owned index o_idx = o0 + 32 qb + n.
+// KEYS_STREAMED: streamed rows are keys (hide when key > query), else streamed rows are queries.
+template <int QB, bool KEYS_STREAMED>
+EA_DEV void causal_hide(f32x16 (&C)[2][QB], long s0, long o0, int lane) {
+    const int n = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long s = s0 + trow(kb, v, h), o = o0 + 32 * qb + n;
+                const bool hide = KEYS_STREAMED ? (s > o) : (o > s);
+                if (hide) C[kb][qb][v] = -INFINITY;
+            }
+}
+
+}  // namespace ea

@@ -1,0 +1,456 @@
+// Forward kernels (Alg. 1 of the AdaSplash-2 paper), re-cut for CDNA4:
+//   tau_kernel : Phase 1 (row max), Phase 2 (LDS histogram -> tau_0), Phase 3 (safeguarded
+//                Halley/Newton refinement to convergence + working block mask at tau_0)
+//   out_kernel : Phase 4 (O = P V over the working mask) + the exported mask at the final tau
+// One work-group = 128*QB query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
+// B operands in registers; 64-key tiles of K (and V^T) stream through LDS.
+#pragma once
+#include "common.hpp"
+
+namespace ea {
+
+// ---- histogram solve (App. C.3), one thread per row, centred units ------------------------
+// Returns the root tau_h of f_h(tau) = -1 + sum_k H_k [k/NB - tau]_+^r  (Eq. 9).
+template <int AM, int NB>
+EA_DEV float solve_histogram(const uint32_t* H, float r) {
+    constexpr float h = 1.f / NB;
+    if constexpr (AM == ALPHA_15 || AM == ALPHA_20) {
+        // descending scan keeping S0, S1, S2 of the active bins; the active set is the largest
+        // one whose closed-form root lies below the left edge of its lowest non-empty bin
+        float S0 = 0.f, S1 = 0.f, S2 = 0.f, best = -h;
+        for (int k = NB - 1; k >= 0; --k) {
+            const float cnt = (float)H[k];
+            if (cnt == 0.f) continue;
+            const float e = k * h;
+            S0 += cnt; S1 += cnt * e; S2 += cnt * e * e;
+            float t;
+            if constexpr (AM == ALPHA_20) {
+                t = (S1 - 1.f) / S0;
+            } else {
+                const float mean = S1 / S0;
+                const float disc = fmaxf(mean * mean - (S2 - 1.f) / S0, 0.f);
+                t = mean - sqrtf(disc);
+            }
+            if (t < e) best = t;
+        }
+        return best;
+    } else {
+        // general alpha: bisection of f_h on [-h, (NB-1)/NB], then Newton from the left end
+        // (f_h is convex and decreasing for alpha <= 2, so Newton from the left is monotone)
+        auto eval = [&](float tau, float& f1) {
+            float f = -1.f; f1 = 0.f;
+            for (int k = NB - 1; k >= 0; --k) {
+                const float y = k * h - tau;
+                if (y <= 0.f) break;
+                const float cnt = (float)H[k];
+                if (cnt == 0.f) continue;
+                const float pr1 = pow_r1<AM>(y, r);
+                f += cnt * pr1 * y;
+                f1 -= cnt * r * pr1;
+            }
+            return f;
+        };
+        float lo = -h, hi = (NB - 1) * h, d1;
+        for (int i = 0; i < 12; ++i) {
+            const float mid = 0.5f * (lo + hi);
+            if (eval(mid, d1) >= 0.f) lo = mid; else hi = mid;
+        }
+        float tau = lo;
+        for (int i = 0; i < 4; ++i) {
+            const float f = eval(tau, d1);
+            if (d1 >= 0.f) break;
+            const float nt = tau - f / d1;
+            if (!(nt > tau) || nt > hi) break;
+            tau = nt;
+        }
+        return tau;
+    }
+}
+
+template <class E, int D, int QB, int NB>
+struct TauSmem {
+    static constexpr int BR = 32 * QB * NWAVES;
+    static constexpr int MR = BR / 64;
+    static constexpr int KBYTES = RowTile<E, D>::BYTES;
+    static constexpr int HIST_WORDS = BR * (NB + 1);
+    // floats: base, thr, lo, hi, F, G, Hs per row; ints: done, iters per row
+    static constexpr int BYTES = KBYTES + 4 * (HIST_WORDS + 7 * BR + 2 * BR + MR * MAX_W + MAX_T + 4);
+};
+
+template <class E, int D, int QB, int AM, int NB>
+__global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
+    using SM = TauSmem<E, D, QB, NB>;
+    using KT = RowTile<E, D>;
+    using elem = typename E::elem;
+    constexpr int BR = SM::BR, MR = SM::MR;
+    extern __shared__ __align__(16) char smem[];
+    char* kbuf = smem;
+    uint32_t* hist = (uint32_t*)(smem + SM::KBYTES);
+    float* rs_base = (float*)(hist + SM::HIST_WORDS);
+    float* rs_thr = rs_base + BR;
+    float* rs_lo = rs_thr + BR;
+    float* rs_hi = rs_lo + BR;
+    float* rs_F = rs_hi + BR;
+    float* rs_G = rs_F + BR;
+    float* rs_H = rs_G + BR;
+    int* rs_done = (int*)(rs_H + BR);
+    int* rs_iters = rs_done + BR;
+    uint32_t* wm = (uint32_t*)(rs_iters + BR);
+    int* tl = (int*)(wm + MR * MAX_W);
+    int* tl_count = tl + MAX_T;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
+    const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
+    const bool active = qw0 < N;          // N is a multiple of 64: the last group may be half empty
+    const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
+    const elem* Kh = (const elem*)p.K + (long)bh * N * D;
+    const int njt = p.causal ? min((int)((q0 + BR) / 64), T) : T;          // tiles the group streams
+    const int wjt = !active ? 0 : p.causal ? (int)((qw0 + 32 * QB - 1) / 64) + 1 : T;   // tiles this wave needs
+    const int myrow = (wave * 32 * QB) / 64;                               // my mask row in the group
+    const float c = p.c, r = p.r;
+
+    Owned<E, D, QB> qf;
+    load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
+    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;
+    for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
+
+    Staged<KT::NCH> st;
+    f32x16 C[2][QB];
+    unsigned long long ntile_done = 0;
+    auto sstore = [&]() { sstore_rows<E, D>(st, kbuf, tid); };
+    auto gload_seq = [&](int it) { gload_rows<E, D>(st, Kh, (long)it * 64, tid); };
+    auto scores = [&](int j) {
+        stage1<E, D, QB>(C, kbuf, qf, lane);
+        if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, (long)j * 64, qw0, lane);
+        ++ntile_done;
+    };
+
+    // ---- Phase 1: row maximum -----------------------------------------------------------
+    float rmax[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) rmax[qb] = -INFINITY;
+    stream_tiles(njt, gload_seq, sstore, [&](int j) {
+        if (j >= wjt) return;
+        scores(j);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) rmax[qb] = fmaxf(rmax[qb], C[kb][qb][v]);
+    });
+    float base[QB];   // m - 1 in raw units: z = x - base (Eq. 6)
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        rmax[qb] = xhalf_max(rmax[qb]);
+        base[qb] = fmaf(c, rmax[qb], -1.f);
+        if (h == 0) rs_base[wave * 32 * QB + 32 * qb + n] = base[qb];
+    }
+
+    // ---- Phase 2: per-row histogram of the centred scores in LDS (Eq. 7-8) ---------------
+    stream_tiles(njt, gload_seq, sstore, [&](int j) {
+        if (j >= wjt) return;
+        scores(j);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float lmax = -INFINITY;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) lmax = fmaxf(lmax, C[kb][qb][v]);
+            if (__any(fmaf(c, lmax, -base[qb]) >= 0.f)) {
+                uint32_t* hrow = hist + (wave * 32 * QB + 32 * qb + n) * (NB + 1);
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float z = fmaf(c, C[kb][qb][v], -base[qb]);
+                        if (z >= 0.f) atomicAdd(&hrow[min((int)(z * NB), NB - 1)], 1u);
+                    }
+            }
+        }
+    });
+    // tau_0 = max(tau_h, 0) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1), in raw units
+    if (tid < BR) {
+        const float tau_h = solve_histogram<AM, NB>(hist + tid * (NB + 1), r);
+        const float t0 = fmaxf(tau_h - 1e-6f, 0.f);
+        rs_thr[tid] = t0 + rs_base[tid];
+        rs_lo[tid] = t0 + rs_base[tid];
+        rs_hi[tid] = tau_h + 1.f / NB + 1e-6f + rs_base[tid];
+        rs_done[tid] = (q0 + tid < N) ? 0 : 1;
+        rs_iters[tid] = 0;
+    }
+    __syncthreads();
+
+    // ---- Phase 3: refinement sweeps; the first also records the working mask --------------
+    int nsweeps = 0;
+    for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
+        ++nsweeps;
+        float thr[QB], F[QB], G[QB], Hs[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            thr[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
+            F[qb] = G[qb] = Hs[qb] = 0.f;
+        }
+        const bool first = (sweep == 0);
+        auto body = [&](int j) {
+            if (j >= wjt) return;
+            if (!first && !mask_bit(wm, W, myrow, j)) return;
+            scores(j);
+            bool hit = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float lmax = -INFINITY;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) lmax = fmaxf(lmax, C[kb][qb][v]);
+                if (__any(fmaf(c, lmax, -thr[qb]) > 0.f)) {
+                    hit = true;
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const float y = fmaf(c, C[kb][qb][v], -thr[qb]);
+                            if constexpr (AM == ALPHA_15) {
+                                const float yp = fmaxf(y, 0.f);
+                                F[qb] = fmaf(yp, yp, F[qb]);
+                                G[qb] += yp;
+                                Hs[qb] += (y > 0.f) ? 1.f : 0.f;
+                            } else if constexpr (AM == ALPHA_20) {
+                                F[qb] += fmaxf(y, 0.f);
+                                G[qb] += (y > 0.f) ? 1.f : 0.f;
+                            } else {
+                                if (y > 0.f) {
+                                    const float p2 = pow_r2<AM>(y, r);
+                                    Hs[qb] += p2;
+                                    G[qb] = fmaf(p2, y, G[qb]);
+                                    F[qb] = fmaf(p2 * y, y, F[qb]);
+                                }
+                            }
+                        }
+                }
+            }
+            if (first && hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
+        };
+        if (first) stream_tiles(njt, gload_seq, sstore, body);
+        else stream_tiles(*tl_count, [&](int it) { gload_rows<E, D>(st, Kh, (long)tl[it] * 64, tid); }, sstore,
+                          [&](int it) { body(tl[it]); });
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float f = xhalf_sum(F[qb]), g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
+            if (h == 0) {
+                const int row = wave * 32 * QB + 32 * qb + n;
+                rs_F[row] = f; rs_G[row] = g; rs_H[row] = hs;
+            }
+        }
+        __syncthreads();
+        // hybrid update (Sec. 3.2): Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2,
+        // bisection whenever the proposed point leaves the bracket
+        int pending = 0;
+        if (tid < BR && !rs_done[tid]) {
+            const float tau = rs_thr[tid];
+            const float f = rs_F[tid] - 1.f;
+            const float f1 = -r * rs_G[tid];
+            rs_iters[tid] += 1;
+            bool done = fabsf(f) <= p.tol;
+            if (!done) {
+                float lo = rs_lo[tid], hi = rs_hi[tid];
+                if (f > 0.f) lo = tau; else hi = tau;
+                float delta;
+                if (p.alpha <= 1.5f) {
+                    const float f2 = r * (r - 1.f) * rs_H[tid];
+                    delta = -2.f * f * f1 / (2.f * f1 * f1 - f * f2);
+                } else {
+                    delta = -f / f1;
+                }
+                float cand = tau + delta;
+                if (!(cand > lo && cand < hi)) cand = 0.5f * (lo + hi);
+                done = fabsf(cand - tau) < p.tol;
+                rs_thr[tid] = cand; rs_lo[tid] = lo; rs_hi[tid] = hi;
+            }
+            rs_done[tid] = done;
+            pending = !done;
+        }
+        const int left = __syncthreads_count(pending);
+        if (first) build_tile_list(wm, MR, W, tl, tl_count, tid);
+        if (left == 0) break;
+    }
+
+    // ---- results ------------------------------------------------------------------------
+    if (tid < BR && q0 + tid < N) {
+        p.tau[(long)bh * N + q0 + tid] = rs_thr[tid];
+        if (p.iters) p.iters[(long)bh * N + q0 + tid] = rs_iters[tid];
+    }
+    for (int i = tid; i < MR * W; i += THREADS)
+        if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
+    if (lane == 0) atomicAdd(&p.stats[0], ntile_done * QB);
+    if (tid == 0) atomicAdd(&p.stats[5], (unsigned long long)nsweeps);
+}
+
+template <class E, class E2, int D, int QB, bool MASK_ONLY>
+struct OutSmem {
+    static constexpr int BR = 32 * QB * NWAVES;
+    static constexpr int MR = BR / 64;
+    static constexpr int KBYTES = RowTile<E, D>::BYTES;
+    static constexpr int VBYTES = MASK_ONLY ? 0 : ColTile<E2, D>::BYTES;
+    static constexpr int BYTES = KBYTES + VBYTES + 4 * (2 * MR * MAX_W + MAX_T + 4);
+};
+
+// Phase 4.  MASK_ONLY: no V, no O - only the mask at the given tau (used by the backward when
+// the caller passes no mask).
+template <class E, class E2, int D, int QB, int AM, bool MASK_ONLY>
+__global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
+    using SM = OutSmem<E, E2, D, QB, MASK_ONLY>;
+    using KT = RowTile<E, D>;
+    using VT = ColTile<E2, D>;
+    using elem = typename E::elem;
+    constexpr int BR = SM::BR, MR = SM::MR;
+    extern __shared__ __align__(16) char smem[];
+    char* kbuf = smem;
+    char* vbuf = smem + SM::KBYTES;
+    uint32_t* wm = (uint32_t*)(smem + SM::KBYTES + SM::VBYTES);
+    uint32_t* fm = wm + MR * MAX_W;
+    int* tl = (int*)(fm + MR * MAX_W);
+    int* tl_count = tl + MAX_T;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
+    const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
+    const bool active = qw0 < N;
+    const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
+    const elem* Kh = (const elem*)p.K + (long)bh * N * D;
+    const typename E2::elem* Vth = MASK_ONLY ? nullptr : (const typename E2::elem*)p.Vt + (long)bh * N * D;
+    const int myrow = (wave * 32 * QB) / 64;
+    const float c = p.c, r = p.r;
+
+    for (int i = tid; i < MR * W; i += THREADS) {
+        wm[i] = (I * MR + i / W < T) ? (uint32_t)p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
+        fm[i] = 0u;
+    }
+    __syncthreads();
+    build_tile_list(wm, MR, W, tl, tl_count, tid);
+
+    Owned<E, D, QB> qf;
+    load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
+    float thr[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) thr[qb] = active ? p.tau[(long)bh * N + qw0 + 32 * qb + n] : 0.f;
+
+    f32x16 X[D / 32][QB];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
+
+    Staged<KT::NCH> stk;
+    Staged<MASK_ONLY ? 1 : VT::NCH> stv;
+    f32x16 C[2][QB];
+    unsigned long long ntile_done = 0;
+    stream_tiles(
+        *tl_count,
+        [&](int it) {
+            const long j = tl[it];
+            gload_rows<E, D>(stk, Kh, j * 64, tid);
+            if constexpr (!MASK_ONLY) gload_cols<E2, D>(stv, Vth, N, j * 64, tid);
+        },
+        [&]() {
+            sstore_rows<E, D>(stk, kbuf, tid);
+            if constexpr (!MASK_ONLY) sstore_cols<E2, D>(stv, vbuf, tid);
+        },
+        [&](int it) {
+            const int j = tl[it];
+            if (!mask_bit(wm, W, myrow, j)) return;
+            stage1<E, D, QB>(C, kbuf, qf, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, (long)j * 64, qw0, lane);
+            ++ntile_done;
+            bool any_pos = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float y = fmaf(c, C[kb][qb][v], -thr[qb]);
+                        any_pos |= (y > 0.f);
+                        if constexpr (AM == ALPHA_GEN) C[kb][qb][v] = (y > 0.f) ? pow_r<AM>(y, r) : 0.f;
+                        else C[kb][qb][v] = pow_r<AM>(fmaxf(y, 0.f), r);
+                    }
+            if (!__any(any_pos)) return;
+            if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
+            if constexpr (!MASK_ONLY) stage2<E2, D, QB>(X, vbuf, C, lane);
+        });
+
+    if constexpr (!MASK_ONLY)
+        if (active) store_owned_T<D, QB>(p.O + (long)bh * N * D, qw0, X, 1.f, lane);
+    for (int i = tid; i < MR * W; i += THREADS)
+        if (I * MR + i / W < T) p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)fm[i];
+    if (lane == 0) atomicAdd(&p.stats[MASK_ONLY ? 6 : 1], ntile_done * QB);
+}
+
+// All causally visible tiles set: the working mask handed to out_kernel<MASK_ONLY>.
+__global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, int causal) {
+    const long total = (long)BH * T * W;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const int m = (int)(i % W), row = (int)((i / W) % T);
+        const int last = causal ? row : T - 1;       // last visible tile
+        uint32_t w = 0;
+        const int lo = 32 * m;
+        if (last >= lo) {
+            const int nb = min(last - lo + 1, 32);
+            w = (nb == 32) ? 0xffffffffu : ((1u << nb) - 1u);
+        }
+        wmask[i] = (int32_t)w;
+    }
+}
+
+// [BH][N][D] (elements of Ein) -> [BH][D][N] (elements of Eout), through a 64x64 LDS tile.
+// `amax_bits` (nullable): bits of a float a >= 0; the copy is divided by a when a > 0.
+template <class Ein, class Eout, int D>
+__global__ __launch_bounds__(THREADS) void transpose_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
+                                                            const unsigned int* amax_bits) {
+    __shared__ float tile[64][65];
+    float mul = 1.f;
+    if (amax_bits) {
+        const float a = __uint_as_float(*amax_bits);
+        if (a > 0.f) mul = 1.f / a;
+    }
+    const int bh = blockIdx.z, r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+    const typename Ein::elem* src = in + (long)bh * N * D;
+    typename Eout::elem* dst = out + (long)bh * N * D;
+    for (int i = threadIdx.x; i < 64 * 64; i += THREADS) {
+        const int rr = i / 64, cc = i % 64;
+        tile[rr][cc] = (float)src[(long)(r0 + rr) * D + c0 + cc];
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 64 * 64; i += THREADS) {
+        const int cc = i / 64, rr = i % 64;
+        dst[(long)(c0 + cc) * N + r0 + rr] = Eout::from_float(tile[rr][cc] * mul);
+    }
+}
+
+__global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int* scal) {
+    if ((int)threadIdx.x < n) stats[threadIdx.x] = 0ull;
+    if (scal && threadIdx.x < 2) scal[threadIdx.x] = 0u;
+}
+
+// max |x| over a tensor -> atomicMax on the float's bit pattern (non-negative floats order as ints)
+template <class E>
+__global__ __launch_bounds__(THREADS) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
+    float m = 0.f;
+    for (long i = blockIdx.x * (long)THREADS + threadIdx.x; i < n; i += (long)gridDim.x * THREADS)
+        m = fmaxf(m, fabsf((float)x[i]));
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
+}
+
+}  // namespace ea
