@@ -1,0 +1,195 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused alpha-entmax attention hot path on one MI355X.
+
+Workload (configs[2] of the benchmark spec, the one its metric is quoted on): alpha = 1.5, bf16,
+B = 2, H = 16, N = 16384, d = 128, causal, Q,K ~ N(0, sigma^2) with sigma swept over
+{1, 2, 3, 4}, V, dO ~ N(0, 1); seeded synthetic tensors, resident in HBM before timing.
+One step = forward + backward over each of the four sigma batches.  `value` is the
+dense-equivalent (FlashAttention convention, causal half) FLOPs of a step over its time.
+Per sigma point the line also carries measured block sparsity, mean tau iterations per row,
+the MFMA flops actually issued and their fraction of the bf16 dense MFMA peak.
+
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak (published)
+METRIC = "effective fwd+bwd TFLOP/s vs block sparsity at N=16k; mean τ iterations/row"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def executed_flops(stats, d):
+    """MFMA flops issued, from the kernels' own sub-tile counters (one sub-tile = 64x32 scores)."""
+    unit = 2.0 * 64 * 32 * d
+    parts = {
+        "tau": unit * stats.get("tau_subtiles", 0),
+        "out": unit * (stats.get("out_subtiles", 0) + stats.get("out_pv_subtiles", 0)),
+        "dq": unit * (2 * stats.get("delta_subtiles", 0) + 3 * stats.get("dq_subtiles", 0)),
+        "dkdv": unit * 4 * stats.get("dkdv_subtiles", 0),
+    }
+    return parts
+
+
+def block_sparsity(mask, T, causal):
+    m = mask.cpu().numpy().view(np.uint32)
+    set_bits = int(np.unpackbits(m.view(np.uint8)).sum())
+    heads = m.shape[0] * m.shape[1]
+    visible = heads * (T * (T + 1) // 2 if causal else T * T)
+    return 1.0 - set_bits / visible
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--sigmas", type=str, default="1,2,3,4")
+    ap.add_argument("--block-rho", type=float, default=0.0,
+                    help="block-correlated query variant of the generator (0 = i.i.d. rows as in the config)")
+    ap.add_argument("--small", action="store_true", help="N=2048 instead of 16384 (plumbing check only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU; heads would shard over GPUs with no communication, "
+            "but nothing here launches a second rank. Use --gpus 1.")
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the HIP path has no CPU fallback")
+        sys.exit(2)
+
+    import paper_2604_15180_amd as ea
+    import workloads
+
+    ea.lib()
+    dev = torch.device("cuda:0")
+    cfg = dict(workloads.CONFIGS["c3_bf16_n16k"])
+    if args.small:
+        cfg["N"] = 2048
+    B, H, N, d, alpha, causal = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["alpha"], cfg["causal"]
+    T = N // 64
+    sigmas = [float(s) for s in args.sigmas.split(",")]
+
+    points = []
+    for i, sg in enumerate(sigmas):
+        q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sg, seed=3000 + i, block_rho=args.block_rho)
+        pt = dict(sigma=sg, cpu=(q, k, v, do) if i == min(1, len(sigmas) - 1) else None,
+                  Q=q.to(dev), K=k.to(dev), V=v.to(dev), dO=do.to(dev))
+        pt["ws_f"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device=dev)
+        pt["ws_b"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device=dev)
+        points.append(pt)
+        log(f"generated sigma={sg}")
+
+    def step(record=None):
+        for pt in points:
+            O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True,
+                                                      workspace=pt["ws_f"])
+            dQ, dK, dV = ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal,
+                                            block_mask=mask, workspace=pt["ws_b"])
+            if record is not None:
+                record.append((mask, iters))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # per-point wall time (events on the stream the library launches on), outside the timed region
+    per_point = []
+    for pt in points:
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record()
+        O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True, workspace=pt["ws_f"])
+        e1.record()
+        ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
+        e2.record()
+        torch.cuda.synchronize()
+        st = ea.read_stats(pt["ws_f"])
+        st_b = ea.read_stats(pt["ws_b"])
+        for kname in ("delta_subtiles", "dq_subtiles", "dkdv_subtiles"):
+            st[kname] = st_b[kname]
+        per_point.append(dict(fwd_ms=e0.elapsed_time(e1), bwd_ms=e1.elapsed_time(e2), stats=st,
+                              sparsity=block_sparsity(mask, T, causal), iters=float(iters.float().mean().item())))
+
+    # ---- timed region: exactly K steps -----------------------------------------------------
+    ea.entmax_attn_timer_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kt = ea.entmax_attn_timer_read()
+    ea.entmax_attn_timer_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    dense_flops_point = 14.0 * B * H * N * N * d * (0.5 if causal else 1.0)
+    value = dense_flops_point * len(points) / (ms_per_step * 1e-3) / 1e12
+
+    sweep, exec_total = [], {"tau": 0.0, "out": 0.0, "dq": 0.0, "dkdv": 0.0}
+    for pt, pp in zip(points, per_point):
+        parts = executed_flops(pp["stats"], d)
+        for kname in exec_total:
+            exec_total[kname] += parts[kname]
+        tot_ms = pp["fwd_ms"] + pp["bwd_ms"]
+        ex = sum(parts.values())
+        sweep.append(dict(sigma=pt["sigma"], block_sparsity=round(pp["sparsity"], 4), mean_tau_iters=round(pp["iters"], 3),
+                          fwd_ms=round(pp["fwd_ms"], 3), bwd_ms=round(pp["bwd_ms"], 3),
+                          effective_tflops=round(dense_flops_point / (tot_ms * 1e-3) / 1e12, 1),
+                          executed_tflops=round(ex / (tot_ms * 1e-3) / 1e12, 1),
+                          mfma_frac_executed=round(ex / (tot_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)))
+
+    # dominant kernel: largest summed time in the timed region; flops per launch from the counters
+    # (the counters of one step, averaged over the sigma points it launches on)
+    dom = max((k for k in kt if k in exec_total), key=lambda k: kt[k][0])
+    dom_ms, dom_launches = kt[dom]
+    dom_avg_ms = dom_ms / dom_launches
+    dom_flops_per_launch = exec_total[dom] / len(points)
+    achieved = dom_flops_per_launch / (dom_avg_ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel=dom + "_kernel", achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4), traffic=None,
+                    avg_launch_ms=round(dom_avg_ms, 3),
+                    kernels={k: dict(avg_ms=round(v[0] / v[1], 3), launches=v[1],
+                                     tflops=(round(exec_total[k] / len(points) / (v[0] / v[1] * 1e-3) / 1e12, 1)
+                                             if k in exec_total else None)) for k, v in kt.items()})
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import entmax_oracle as eo
+        src = next(pt for pt in points if pt["cpu"] is not None)
+        n_heads = 2            # bounded sample: whole heads, so dK/dV are complete
+        q, k, v, do = (np.ascontiguousarray(t[:1, :n_heads].to(torch.float64).numpy()) for t in src["cpu"])
+        c0 = time.perf_counter()
+        eo.attn_fwd(q, k, v, alpha, causal, want_margin=False)
+        eo.attn_bwd(q, k, v, do, alpha, causal)
+        c1 = time.perf_counter()
+        cpu_flops = 14.0 * n_heads * N * N * d * (0.5 if causal else 1.0)
+        cpu_baseline = dict(value=round(cpu_flops / (c1 - c0) / 1e12, 5), unit="TFLOP/s", cores=eo.num_threads(),
+                            kind="oracle", seconds=round(c1 - c0, 2),
+                            sample=f"float64 oracle, forward+backward, {n_heads} whole heads (b=0, h<{n_heads}) of the "
+                                   f"sigma={src['sigma']:g} batch ({n_heads} of {B * H} heads of one of {len(points)} batches)")
+
+    out = dict(metric=METRIC, value=round(value, 2), unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
+               dtype="bf16", data="synthetic",
+               config=dict(workload=f"configs[2]: alpha=1.5 bf16 B={B} H={H} N={N} d={d} causal, sigma sweep {sigmas}, "
+                                    f"generator={'iid' if args.block_rho == 0 else 'block-correlated rho=%g' % args.block_rho}",
+                           step="forward+backward over each sigma batch", histogram_bins=ea.entmax_attn_histogram_bins()),
+               mean_tau_iters=round(float(np.mean([pp["iters"] for pp in per_point])), 3),
+               sweep=sweep, roofline=roofline, cpu_baseline=cpu_baseline)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

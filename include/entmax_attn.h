@@ -59,7 +59,8 @@ enum {
     EA_STAT_DQ_TILES = 3,    /* sub-tiles visited by the dQ sweep (3 matmuls each) */
     EA_STAT_DKDV_TILES = 4,  /* sub-tiles visited by the dK/dV kernel (4 matmuls each) */
     EA_STAT_SWEEPS = 5,      /* sum over work-groups of refinement sweeps run */
-    EA_STAT_MASK_TILES = 6   /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
+    EA_STAT_MASK_TILES = 6,  /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
+    EA_STAT_OUT_PV_TILES = 7 /* sub-tiles of the output phase whose P V product was issued */
 };
 
 /* Edge of the square score tiles that one bit of the block mask stands for (64). */
@@ -110,6 +111,27 @@ const char* entmax_attn_strerror(int code);
 /* hipError_t (as int) of the most recent failing HIP call made by this library on the calling
  * thread, 0 if none. */
 int entmax_attn_last_hip_error(void);
+
+/*
+ * Optional per-kernel timing (measurement aid, used by the benchmark; Sec. 4.2 reports forward
+ * and backward times separately).  While enabled, every entmax_attn_fwd / entmax_attn_bwd call
+ * records HIP events on its stream around each of its kernels, for up to 256 calls between
+ * reads.  entmax_attn_timer_read waits for the recorded events, writes per slot the summed
+ * kernel time in ms and the number of launches (arrays of at least EA_TIMER_SLOTS entries), and
+ * starts a new recording window.  Enabling creates the events once; not thread-safe.
+ */
+#define EA_TIMER_SLOTS 8
+enum {
+    EA_TIMER_FWD_PREP = 0,  /* V -> V^T copy */
+    EA_TIMER_TAU = 1,       /* phases 1-3 */
+    EA_TIMER_OUT = 2,       /* phase 4 */
+    EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
+    EA_TIMER_BWD_PREP = 4,  /* max|dO| and the K^T, Q^T, dO^T copies */
+    EA_TIMER_DQ = 5,        /* delta sweep + dQ */
+    EA_TIMER_DKDV = 6       /* dK, dV */
+};
+int entmax_attn_timer_enable(int on);
+int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);
 
 /* Histogram bins B and work-group query rows used by the threshold kernel (introspection for
  * tests and the benchmark report). */

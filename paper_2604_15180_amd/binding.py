@@ -15,7 +15,9 @@ _lib = None
 EA_F32, EA_BF16 = 0, 1
 EA_STATS_WORDS = 16
 STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
-              "sweeps", "mask_subtiles")
+              "sweeps", "mask_subtiles", "out_pv_subtiles")
+EA_TIMER_SLOTS = 8
+TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "unused")
 
 
 class EntmaxAttnError(RuntimeError):
@@ -51,6 +53,10 @@ def lib():
         L.entmax_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
         L.entmax_attn_bwd.restype = ci
         L.entmax_attn_bwd.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+        L.entmax_attn_timer_enable.restype = ci
+        L.entmax_attn_timer_enable.argtypes = [ci]
+        L.entmax_attn_timer_read.restype = ci
+        L.entmax_attn_timer_read.argtypes = [ctypes.POINTER(cf), ctypes.POINTER(ci), ci]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
         L.entmax_attn_strerror.argtypes = [ci]
         _lib = L
@@ -145,6 +151,18 @@ def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspa
     _check(rc)
     entmax_attn_bwd.last_workspace = ws
     return dQ, dK, dV
+
+
+def entmax_attn_timer_enable(on):
+    _check(lib().entmax_attn_timer_enable(int(bool(on))))
+
+
+def entmax_attn_timer_read():
+    """-> {kernel name: (summed ms, launches)} since the last read (waits for the events)."""
+    ms = (ctypes.c_float * EA_TIMER_SLOTS)()
+    cnt = (ctypes.c_int * EA_TIMER_SLOTS)()
+    _check(lib().entmax_attn_timer_read(ms, cnt, EA_TIMER_SLOTS))
+    return {TIMER_NAMES[k]: (float(ms[k]), int(cnt[k])) for k in range(EA_TIMER_SLOTS) if cnt[k]}
 
 
 def read_stats(workspace):

@@ -18,6 +18,36 @@ constexpr int MAX_SWEEPS = 12;
 
 thread_local int g_last_hip_error = 0;
 
+// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch.
+// Off by default (then nothing below runs).  Slots name the kernels of one fwd or bwd call.
+constexpr int TIMER_SLOTS = EA_TIMER_SLOTS;
+constexpr int TIMER_MAX_CALLS = 256;
+struct KernelTimer {
+    bool enabled = false;
+    int ncalls = 0;                                   // calls recorded since the last reset
+    hipEvent_t ev[TIMER_MAX_CALLS][TIMER_SLOTS][2];
+    unsigned char used[TIMER_MAX_CALLS][TIMER_SLOTS];
+    bool created = false;
+} g_timer;
+int g_timer_call = -1;                                // slot row of the call in flight, -1 = off
+
+struct ScopedKernelTime {
+    int slot; hipStream_t s; bool on;
+    ScopedKernelTime(int slot_, hipStream_t s_) : slot(slot_), s(s_), on(g_timer_call >= 0) {
+        if (on) (void)hipEventRecord(g_timer.ev[g_timer_call][slot][0], s);
+    }
+    ~ScopedKernelTime() {
+        if (on) { (void)hipEventRecord(g_timer.ev[g_timer_call][slot][1], s); g_timer.used[g_timer_call][slot] = 1; }
+    }
+};
+void timer_begin_call() {
+    g_timer_call = -1;
+    if (g_timer.enabled && g_timer.ncalls < TIMER_MAX_CALLS) {
+        g_timer_call = g_timer.ncalls++;
+        for (int k = 0; k < TIMER_SLOTS; ++k) g_timer.used[g_timer_call][k] = 0;
+    }
+}
+
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
@@ -93,23 +123,34 @@ int launch_transpose(const void* in, void* out, int BH, int N, const unsigned in
 template <class E, class E2F, class E2B, int D, int AM>
 struct Ops {
     static int fwd(Params p, hipStream_t s) {
-        int rc = launch_transpose<E, E2F, D>(p.V, (void*)p.Vt, p.BH, p.N, nullptr, s);
-        if (rc) return rc;
+        int rc;
+        {
+            ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
+            rc = launch_transpose<E, E2F, D>(p.V, (void*)p.Vt, p.BH, p.N, nullptr, s);
+            if (rc) return rc;
+        }
         const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
-        rc = launch(tau_kernel<E, D, QB, AM, NBINS>, grid, TauSmem<E, D, QB, NBINS>::BYTES, s, p);
-        if (rc) return rc;
+        {
+            ScopedKernelTime t(EA_TIMER_TAU, s);
+            rc = launch(tau_kernel<E, D, QB, AM, NBINS>, grid, TauSmem<E, D, QB, NBINS>::BYTES, s, p);
+            if (rc) return rc;
+        }
+        ScopedKernelTime t(EA_TIMER_OUT, s);
         return launch(out_kernel<E, E2F, D, QB, AM, false>, grid, OutSmem<E, E2F, D, QB, false>::BYTES, s, p);
     }
     static int bwd(Params p, bool rebuild_mask, hipStream_t s) {
         int rc;
         const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
         if (rebuild_mask) {
+            ScopedKernelTime t(EA_TIMER_MASK, s);
             hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
             EA_HIP(hipGetLastError());
             rc = launch(out_kernel<E, E2F, D, QB, AM, true>, grid, OutSmem<E, E2F, D, QB, true>::BYTES, s, p);
             if (rc) return rc;
         }
         const unsigned int* go_amax = nullptr;
+        {
+        ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
         if (E2B::SCALED) {
             hipLaunchKernelGGL((amax_kernel<E>), dim3(1024), dim3(THREADS), 0, s, (const typename E::elem*)p.dO,
                                (long)p.BH * p.N * D, p.scal);
@@ -119,8 +160,13 @@ struct Ops {
         if ((rc = launch_transpose<E, E2B, D>(p.K, (void*)p.Kt, p.BH, p.N, nullptr, s))) return rc;
         if ((rc = launch_transpose<E, E2B, D>(p.Q, (void*)p.Qt, p.BH, p.N, nullptr, s))) return rc;
         if ((rc = launch_transpose<E, E2B, D>(p.dO, (void*)p.dOt, p.BH, p.N, go_amax, s))) return rc;
-        rc = launch(dq_kernel<E, E2B, D, QB, AM>, grid, DqSmem<E, E2B, D, QB>::BYTES, s, p);
-        if (rc) return rc;
+        }
+        {
+            ScopedKernelTime t(EA_TIMER_DQ, s);
+            rc = launch(dq_kernel<E, E2B, D, QB, AM>, grid, DqSmem<E, E2B, D, QB>::BYTES, s, p);
+            if (rc) return rc;
+        }
+        ScopedKernelTime t(EA_TIMER_DKDV, s);
         return launch(dkdv_kernel<E, E2B, D, QB, AM>, grid, DkdvSmem<E, E2B, D, QB>::BYTES, s, p);
     }
 };
@@ -193,6 +239,7 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.wmask = (int32_t*)(ws + L.wmask);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
+    timer_begin_call();
     return dispatch(false, t, d, p, false, s);
 }
 
@@ -220,7 +267,37 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     p.scal = (unsigned int*)(ws + L.stats + EA_STATS_WORDS * 8);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, p.scal);
     EA_HIP(hipGetLastError());
+    timer_begin_call();
     return dispatch(true, t, d, p, rebuild, s);
+}
+
+int entmax_attn_timer_enable(int on) {
+    if (on && !g_timer.created) {
+        for (int c = 0; c < TIMER_MAX_CALLS; ++c)
+            for (int k = 0; k < TIMER_SLOTS; ++k)
+                for (int e = 0; e < 2; ++e) EA_HIP(hipEventCreate(&g_timer.ev[c][k][e]));
+        g_timer.created = true;
+    }
+    g_timer.enabled = on != 0;
+    g_timer.ncalls = 0;
+    g_timer_call = -1;
+    return EA_OK;
+}
+
+int entmax_attn_timer_read(float* ms_sum, int* launches, int slots) {
+    if (!ms_sum || !launches || slots < TIMER_SLOTS) return EA_ERR_NULL;
+    for (int k = 0; k < TIMER_SLOTS; ++k) { ms_sum[k] = 0.f; launches[k] = 0; }
+    for (int c = 0; c < g_timer.ncalls; ++c)
+        for (int k = 0; k < TIMER_SLOTS; ++k) {
+            if (!g_timer.used[c][k]) continue;
+            EA_HIP(hipEventSynchronize(g_timer.ev[c][k][1]));
+            float ms = 0.f;
+            EA_HIP(hipEventElapsedTime(&ms, g_timer.ev[c][k][0], g_timer.ev[c][k][1]));
+            ms_sum[k] += ms;
+            launches[k] += 1;
+        }
+    g_timer.ncalls = 0;
+    return EA_OK;
 }
 
 const char* entmax_attn_strerror(int code) {

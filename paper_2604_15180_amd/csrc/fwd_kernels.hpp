@@ -355,7 +355,7 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
     Staged<KT::NCH> stk;
     Staged<MASK_ONLY ? 1 : VT::NCH> stv;
     f32x16 C[2][QB];
-    unsigned long long ntile_done = 0;
+    unsigned long long ntile_done = 0, npv_done = 0;
     stream_tiles(
         *tl_count,
         [&](int it) {
@@ -387,14 +387,17 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
                     }
             if (!__any(any_pos)) return;
             if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
-            if constexpr (!MASK_ONLY) stage2<E2, D, QB>(X, vbuf, C, lane);
+            if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, vbuf, C, lane); ++npv_done; }
         });
 
     if constexpr (!MASK_ONLY)
         if (active) store_owned_T<D, QB>(p.O + (long)bh * N * D, qw0, X, 1.f, lane);
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)fm[i];
-    if (lane == 0) atomicAdd(&p.stats[MASK_ONLY ? 6 : 1], ntile_done * QB);
+    if (lane == 0) {
+        atomicAdd(&p.stats[MASK_ONLY ? 6 : 1], ntile_done * QB);
+        if (!MASK_ONLY) atomicAdd(&p.stats[7], npv_done * QB);
+    }
 }
 
 // All causally visible tiles set: the working mask handed to out_kernel<MASK_ONLY>.
