@@ -168,7 +168,7 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import entmax_oracle as eo
         src = next(pt for pt in points if pt["cpu"] is not None)
-        n_heads = 2            # bounded sample: whole heads, so dK/dV are complete
+        n_heads = 16           # bounded sample: whole heads, so dK/dV are complete
         q, k, v, do = (np.ascontiguousarray(t[:1, :n_heads].to(torch.float64).numpy()) for t in src["cpu"])
         c0 = time.perf_counter()
         eo.attn_fwd(q, k, v, alpha, causal, want_margin=False)
