@@ -18,6 +18,9 @@ def build(force: bool = True, verbose: bool = False) -> str:
             return LIB
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # keep MFMA results in ordinary VGPRs: the AGPR form costs a v_accvgpr copy per
+           # accumulator register each time the vector ALUs touch a score tile
+           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
            "-Wno-unused-command-line-argument"]
     if verbose:
         cmd += ["-Rpass-analysis=kernel-resource-usage"]

@@ -12,7 +12,8 @@ namespace {
 
 using namespace ea;
 
-constexpr int QB = 1;        // 32*QB query rows per wave, 128*QB per work-group
+constexpr int QB = 1;        // 32*QB owned rows per wave, 128*QB per work-group (output and backward kernels)
+constexpr int QB_TAU = 2;    // same for the threshold kernel, which carries no output accumulators
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
 
@@ -132,7 +133,8 @@ struct Ops {
         const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
-            rc = launch(tau_kernel<E, D, QB, AM, NBINS>, grid, TauSmem<E, D, QB, NBINS>::BYTES, s, p);
+            const dim3 grid_tau(p.BH * ((p.N + 128 * QB_TAU - 1) / (128 * QB_TAU)));
+            rc = launch(tau_kernel<E, D, QB_TAU, AM, NBINS>, grid_tau, TauSmem<E, D, QB_TAU, NBINS>::BYTES, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
             const int j = tl[it];
             if (!mask_bit(fm, W, myrow, j)) return;
             stage1<E, D, QB>(S, kbuf, qf, lane);
-            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, (long)j * 64, qw0, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
             stage1<E, D, QB>(dP, vbuf, gf, lane);
             ++ntile_a;
 #pragma unroll
@@ -91,16 +91,19 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
-                        const float u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
-                        num[qb] = fmaf(u, dP[kb][qb][v], num[qb]);
+                        float u;
+                        if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
+                        else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                        const float t = u * dP[kb][qb][v];
+                        num[qb] += t;
                         den[qb] += u;
-                        if constexpr (E2::SCALED) gmax[qb] = fmaxf(gmax[qb], (y > 0.f) ? fabsf(dP[kb][qb][v]) : 0.f);
+                        if constexpr (E2::SCALED) gmax[qb] = fmaxf(gmax[qb], fabsf(t));
                     }
         });
-    // |dS| = U |dP - delta| <= max_support |dP| + |delta| =: bound (U <= 1 since y < 1, r >= 1).
+    // |dS| = U |dP - delta| <= max |U dP| + |delta| =: bound (U <= 1 since y < 1, r >= 1).
     // With a narrow-range stage-2 type, dS / bound goes through the MFMA and the result is
     // multiplied back per row; the largest bound is published for the dK/dV kernel.
-    float delta[QB], bound[QB], inv_bound[QB], out_scale[QB];
+    float delta[QB], bound[QB], inv_bound[QB], out_scale[QB], delta_s[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float dn = xhalf_sum(den[qb]);
@@ -113,6 +116,7 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
         } else {
             bound[qb] = 0.f; inv_bound[qb] = 1.f; out_scale[qb] = p.inv_sqrt_d;
         }
+        delta_s[qb] = delta[qb] * inv_bound[qb];
     }
     if constexpr (E2::SCALED) {
         float bm = 0.f;
@@ -147,7 +151,7 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
             const int j = tl[it];
             if (!mask_bit(fm, W, myrow, j)) return;
             stage1<E, D, QB>(S, kbuf, qf, lane);
-            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, (long)j * 64, qw0, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
             stage1<E, D, QB>(dP, vbuf, gf, lane);
             ++ntile_b;
 #pragma unroll
@@ -157,8 +161,10 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
-                        const float u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
-                        S[kb][qb][v] = u * (dP[kb][qb][v] - delta[qb]) * inv_bound[qb];
+                        float u;
+                        if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
+                        else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                        S[kb][qb][v] = u * fmaf(dP[kb][qb][v], inv_bound[qb], -delta_s[qb]);
                     }
             stage2<E2, D, QB>(X, ktbuf, S, lane);
         });
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
             gload_cols<E2, D>(stqt, Qth, N, i * 64, tid);
             gload_cols<E2, D>(stgt, Gth, N, i * 64, tid);
             if (tid < TILE) st_vec = p.tau[(long)bh * N + i * 64 + tid];
-            else if (tid < 2 * TILE) st_vec = p.delta[(long)bh * N + i * 64 + tid - TILE];
+            else if (tid < 2 * TILE) st_vec = p.delta[(long)bh * N + i * 64 + tid - TILE] * ds_inv;
         },
         [&]() {
             sstore_rows<E, D>(stq, qbuf, tid);
@@ -290,7 +296,7 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
             if (!((ent >> (16 + mycol)) & 1)) return;
             stage1<E, D, QB>(S, qbuf, kf, lane);
             // streamed rows are queries here: hide key > query
-            if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, i * 64, kw0, lane);
+            if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, (int)i * 64, (int)kw0, lane);
             stage1<E, D, QB>(dP, gbuf, vf, lane);
             ++ntile_done;
 #pragma unroll
@@ -301,14 +307,13 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
                     const float tq = tau_s[row], dq = del_s[row];
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        const float y = fmaf(c, S[kb][qb][v], -tq);
-                        const bool on = y > 0.f;
-                        const float u = on ? pow_r1<AM>(y, r) : 0.f;
-                        float pr;
-                        if constexpr (AM == ALPHA_20) pr = on ? y : 0.f;
-                        else pr = on ? u * y : 0.f;
-                        S[kb][qb][v] = pr;
-                        dP[kb][qb][v] = u * (dP[kb][qb][v] - dq) * ds_inv;
+                        // del_s holds delta * ds_inv
+                        const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
+                        float u;
+                        if constexpr (AM == ALPHA_15) u = yp;
+                        else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
+                        S[kb][qb][v] = u * yp;
+                        dP[kb][qb][v] = u * fmaf(dP[kb][qb][v], ds_inv, -dq);
                     }
                 }
             stage2<E2, D, QB>(XV, gtbuf, S, lane);

@@ -109,16 +109,19 @@ EA_DEV bool mask_bit(const uint32_t* words, int W, int row, int j) {
 // streamed index s_idx = s0 + trow and owned index o_idx = o0 + 32 qb + n.
 // KEYS_STREAMED: streamed rows are keys (hide when key > query), else streamed rows are queries.
 template <int QB, bool KEYS_STREAMED>
-EA_DEV void causal_hide(f32x16 (&C)[2][QB], long s0, long o0, int lane) {
+EA_DEV void causal_hide(f32x16 (&C)[2][QB], int s0, int o0, int lane) {
     const int n = lane & 31, h = lane >> 5;
+    // hide when (s0 + trow) > (o0 + 32 qb + n)   [keys streamed]   i.e. trow > lim
+    //        or (o0 + 32 qb + n) > (s0 + trow)   [queries streamed] i.e. trow < lim
+    const int lim0 = o0 + n - s0 - 8 * h;      // compare 32 kb + 16 (v/8) + v%8 against lim0 + 32 qb
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const long s = s0 + trow(kb, v, h), o = o0 + 32 * qb + n;
-                const bool hide = KEYS_STREAMED ? (s > o) : (o > s);
+                const int t = 32 * kb + 16 * (v >> 3) + (v & 7) - 32 * qb;   // compile-time constant
+                const bool hide = KEYS_STREAMED ? (t > lim0) : (t < lim0);
                 if (hide) C[kb][qb][v] = -INFINITY;
             }
 }

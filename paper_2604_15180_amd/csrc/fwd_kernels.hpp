@@ -125,7 +125,7 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
     auto gload_seq = [&](int it) { gload_rows<E, D>(st, Kh, (long)it * 64, tid); };
     auto scores = [&](int j) {
         stage1<E, D, QB>(C, kbuf, qf, lane);
-        if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, (long)j * 64, qw0, lane);
+        if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
         ++ntile_done;
     };
 
@@ -191,10 +191,12 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
     for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
         ++nsweeps;
         float thr[QB], F[QB], G[QB], Hs[QB];
+        int cnt[QB];      // number of scores above tau (alpha = 1.5: f'' sum; alpha = 2: f' sum)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             thr[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
             F[qb] = G[qb] = Hs[qb] = 0.f;
+            cnt[qb] = 0;
         }
         const bool first = (sweep == 0);
         auto body = [&](int j) {
@@ -220,10 +222,10 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
                                 const float yp = fmaxf(y, 0.f);
                                 F[qb] = fmaf(yp, yp, F[qb]);
                                 G[qb] += yp;
-                                Hs[qb] += (y > 0.f) ? 1.f : 0.f;
+                                cnt[qb] += (y > 0.f);
                             } else if constexpr (AM == ALPHA_20) {
                                 F[qb] += fmaxf(y, 0.f);
-                                G[qb] += (y > 0.f) ? 1.f : 0.f;
+                                cnt[qb] += (y > 0.f);
                             } else {
                                 if (y > 0.f) {
                                     const float p2 = pow_r2<AM>(y, r);
@@ -242,6 +244,8 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
                           [&](int it) { body(tl[it]); });
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
+            if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
+            if constexpr (AM == ALPHA_20) G[qb] = (float)cnt[qb];
             const float f = xhalf_sum(F[qb]), g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
             if (h == 0) {
                 const int row = wave * 32 * QB + 32 * qb + n;
@@ -371,21 +375,21 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
             const int j = tl[it];
             if (!mask_bit(wm, W, myrow, j)) return;
             stage1<E, D, QB>(C, kbuf, qf, lane);
-            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, (long)j * 64, qw0, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
-            bool any_pos = false;
+            float ymax = 0.f;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const float y = fmaf(c, C[kb][qb][v], -thr[qb]);
-                        any_pos |= (y > 0.f);
-                        if constexpr (AM == ALPHA_GEN) C[kb][qb][v] = (y > 0.f) ? pow_r<AM>(y, r) : 0.f;
-                        else C[kb][qb][v] = pow_r<AM>(fmaxf(y, 0.f), r);
+                        const float yp = fmaxf(fmaf(c, C[kb][qb][v], -thr[qb]), 0.f);
+                        ymax = fmaxf(ymax, yp);
+                        if constexpr (AM == ALPHA_GEN) C[kb][qb][v] = (yp > 0.f) ? pow_r<AM>(yp, r) : 0.f;
+                        else C[kb][qb][v] = pow_r<AM>(yp, r);
                     }
-            if (!__any(any_pos)) return;
+            if (!__any(ymax > 0.f)) return;
             if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
             if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, vbuf, C, lane); ++npv_done; }
         });
