@@ -37,7 +37,7 @@ def executed_flops(stats, d):
     parts = {
         "tau": unit * stats.get("tau_subtiles", 0),
         "out": unit * (stats.get("out_subtiles", 0) + stats.get("out_pv_subtiles", 0)),
-        "dq": unit * (2 * stats.get("delta_subtiles", 0) + 3 * stats.get("dq_subtiles", 0)),
+        "dq": unit * 4 * stats.get("dq_subtiles", 0),
         "dkdv": unit * 4 * stats.get("dkdv_subtiles", 0),
     }
     return parts

@@ -55,8 +55,8 @@ enum {
      * wavefront computes per MFMA block pair; one matmul on a sub-tile is 2*64*32*d flops */
     EA_STAT_TAU_TILES = 0,   /* sub-tiles scored by the max, histogram and refinement sweeps (1 matmul each) */
     EA_STAT_OUT_TILES = 1,   /* sub-tiles scored by the output phase (2 matmuls each where P != 0) */
-    EA_STAT_DELTA_TILES = 2, /* sub-tiles visited by the delta sweep of the backward (2 matmuls each) */
-    EA_STAT_DQ_TILES = 3,    /* sub-tiles visited by the dQ sweep (3 matmuls each) */
+    EA_STAT_DELTA_TILES = 2, /* unused (delta is found inside the dQ sweep) */
+    EA_STAT_DQ_TILES = 3,    /* sub-tiles visited by the dQ kernel (4 matmuls each) */
     EA_STAT_DKDV_TILES = 4,  /* sub-tiles visited by the dK/dV kernel (4 matmuls each) */
     EA_STAT_SWEEPS = 5,      /* sum over work-groups of refinement sweeps run */
     EA_STAT_MASK_TILES = 6,  /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
@@ -90,9 +90,11 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Backward (Alg. 2-3): delta sweep + dQ kernel over mask rows, dK/dV kernel over mask columns.
+ * Backward (Alg. 2-3): dQ kernel (which also finds delta) over mask rows, dK/dV kernel over mask columns.
  *   Q, K, V, dO in   [B,H,N,d] of `dtype`
- *   O           in   accepted for signature parity with Alg. 2-3, not read (may be NULL)
+ *   O           in   [B,H,N,d] float32, the forward's output; used only to centre the dQ sums
+ *                    (<dO_r, O_r> is subtracted from dP before rounding); may be NULL, at the price
+ *                    of extra rounding error in dQ when dP is large and nearly constant on a row's support
  *   tau         in   [B,H,N] float32 as returned by the forward
  *   block_mask  in   as returned by the forward, or NULL: then it is rebuilt from tau with one
  *                    dense score sweep
@@ -126,8 +128,8 @@ enum {
     EA_TIMER_TAU = 1,       /* phases 1-3 */
     EA_TIMER_OUT = 2,       /* phase 4 */
     EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
-    EA_TIMER_BWD_PREP = 4,  /* max|dO| and the K^T, Q^T, dO^T copies */
-    EA_TIMER_DQ = 5,        /* delta sweep + dQ */
+    EA_TIMER_BWD_PREP = 4,  /* row statistics of dO, V and the K^T, Q^T, dO^T copies */
+    EA_TIMER_DQ = 5,        /* delta + dQ */
     EA_TIMER_DKDV = 6       /* dK, dV */
 };
 int entmax_attn_timer_enable(int on);

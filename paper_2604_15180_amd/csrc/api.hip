@@ -13,7 +13,7 @@ namespace {
 using namespace ea;
 
 constexpr int QB = 1;        // 32*QB owned rows per wave, 128*QB per work-group (output and backward kernels)
-constexpr int QB_TAU = 2;    // same for the threshold kernel, which carries no output accumulators
+constexpr int QB_TAU = 1;    // same for the threshold kernel, which carries no output accumulators
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
 
@@ -154,8 +154,11 @@ struct Ops {
         {
         ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
         if (E2B::SCALED) {
-            hipLaunchKernelGGL((amax_kernel<E>), dim3(1024), dim3(THREADS), 0, s, (const typename E::elem*)p.dO,
-                               (long)p.BH * p.N * D, p.scal);
+            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(THREADS), 0, s, (const typename E::elem*)p.dO,
+                               (long)p.BH * p.N, p.scal, p.scal + 2);
+            EA_HIP(hipGetLastError());
+            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(THREADS), 0, s, (const typename E::elem*)p.V,
+                               (long)p.BH * p.N, (unsigned int*)nullptr, p.scal + 3);
             EA_HIP(hipGetLastError());
             go_amax = p.scal;
         }
@@ -248,7 +251,6 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
 int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
                     const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
                     ea_dtype t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    (void)O;
     if (!Q || !K || !V || !dO || !tau || !dQ || !dK || !dV) return EA_ERR_NULL;
     int rc = check_common(B, H, N, d, t, alpha);
     if (rc) return rc;
@@ -259,6 +261,7 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     Params p = base_params(B, H, N, d, t, alpha, causal);
     p.Q = Q; p.K = K; p.V = V; p.dO = dO;
     p.tau = const_cast<float*>(tau);
+    p.O = const_cast<float*>((const float*)O);
     p.dQ = dQ; p.dK = dK; p.dV = dV;
     p.stats = (unsigned long long*)(ws + L.stats);
     p.Kt = ws + L.a; p.Qt = ws + L.b; p.dOt = ws + L.c;

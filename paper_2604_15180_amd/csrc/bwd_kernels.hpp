@@ -1,7 +1,7 @@
 // Backward kernels (Sec. 3.3 "Backward pass", Alg. 2-3 of the AdaSplash-2 paper):
-//   dq_kernel   : per 128*QB query rows, over the set bits of their mask rows:
-//                 sweep A  delta_r = sum_j U_rj dP_rj / sum_j U_rj,  U = P^(2-alpha), dP = dO V^T
-//                 sweep B  dS = U (dP - delta),  dQ = dS K / sqrt(d)                  (Alg. 3)
+//   dq_kernel   : per 128*QB query rows, over the set bits of their mask rows, in one sweep:
+//                 delta_r = sum_j U_rj dP_rj / sum_j U_rj,  U = P^(2-alpha), dP = dO V^T
+//                 dQ = [ (U o dP) K - delta (U K) ] / sqrt(d)  ( = dS K / sqrt(d), Alg. 3)
 //   dkdv_kernel : per 128*QB keys, over the set bits of their mask columns:
 //                 dV += P^T dO,  dK += dS^T Q / sqrt(d)                               (Alg. 2)
 // With y = (alpha-1) s - tau on the support:  P = y^r,  U = y^(r-1),  r = 1/(alpha-1).
@@ -60,80 +60,49 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) thr[qb] = active ? p.tau[(long)bh * N + qw0 + 32 * qb + n] : 0.f;
 
-    Staged<RT::NCH> stk, stv;
-    Staged<CT::NCH> stkt;
-    f32x16 S[2][QB], dP[2][QB];
-    unsigned long long ntile_a = 0, ntile_b = 0;
-
-    // ---- sweep A: delta ----------------------------------------------------------------
-    float num[QB], den[QB], gmax[QB];
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
-    stream_tiles(
-        *tl_count,
-        [&](int it) {
-            const long j = tl[it];
-            gload_rows<E, D>(stk, Kh, j * 64, tid);
-            gload_rows<E, D>(stv, Vh, j * 64, tid);
-        },
-        [&]() { sstore_rows<E, D>(stk, kbuf, tid); sstore_rows<E, D>(stv, vbuf, tid); },
-        [&](int it) {
-            const int j = tl[it];
-            if (!mask_bit(fm, W, myrow, j)) return;
-            stage1<E, D, QB>(S, kbuf, qf, lane);
-            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
-            stage1<E, D, QB>(dP, vbuf, gf, lane);
-            ++ntile_a;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
-                        float u;
-                        if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
-                        else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
-                        const float t = u * dP[kb][qb][v];
-                        num[qb] += t;
-                        den[qb] += u;
-                        if constexpr (E2::SCALED) gmax[qb] = fmaxf(gmax[qb], fabsf(t));
-                    }
-        });
-    // |dS| = U |dP - delta| <= max |U dP| + |delta| =: bound (U <= 1 since y < 1, r >= 1).
-    // With a narrow-range stage-2 type, dS / bound goes through the MFMA and the result is
-    // multiplied back per row; the largest bound is published for the dK/dV kernel.
-    float delta[QB], bound[QB], inv_bound[QB], out_scale[QB], delta_s[QB];
+    // One sweep over the set bits of the mask rows.  With dS = U (dP - delta) and any centre e:
+    //     dQ sqrt(d) = sum_j dS_j K_j = sum_j (U (dP - e))_j K_j - (delta - e) sum_j U_j K_j
+    //                = XA - (delta - e) XB,     delta - e = sum(U (dP - e)) / sum(U),
+    // so delta comes out of the row sums of the same sweep and the scores are computed once.
+    // The centre e = <dO_r, O_r> = sum_j P_rj dP_rj is the P-weighted mean of dP over the support
+    // (delta is the U-weighted one): it keeps XA - (delta - e) XB free of the cancellation that
+    // e = 0 would bring when dP is nearly constant over the support.  Without O, e = 0.
+    // |dP_rj| = |<dO_r, V_j>| <= max_r |dO_r| max_j |V_j| =: pb (row 2-norms from rownorm_kernel)
+    // and |e| <= pb (O_r is a convex combination of V rows), so |U (dP - e)| <= 2 pb; with a
+    // narrow-range stage-2 type U (dP - e) / (2 pb) feeds the MFMA.
+    float pb = 1.f, inv_pb = 1.f;
+    if constexpr (E2::SCALED) {
+        pb = 2.f * __uint_as_float(p.scal[2]) * __uint_as_float(p.scal[3]);
+        inv_pb = pb > 0.f ? 1.f / pb : 0.f;
+    }
+    float ctr[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float dn = xhalf_sum(den[qb]);
-        delta[qb] = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;
-        if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = delta[qb];
-        if constexpr (E2::SCALED) {
-            bound[qb] = xhalf_max(gmax[qb]) + fabsf(delta[qb]);
-            inv_bound[qb] = bound[qb] > 0.f ? 1.f / bound[qb] : 0.f;
-            out_scale[qb] = bound[qb] * p.inv_sqrt_d;
-        } else {
-            bound[qb] = 0.f; inv_bound[qb] = 1.f; out_scale[qb] = p.inv_sqrt_d;
+        float acc = 0.f;
+        if (p.O && active) {
+            const float* orow = p.O + hoff + (qw0 + 32 * qb + n) * (long)D + h * (D / 2);
+            const elem* grow = (const elem*)p.dO + hoff + (qw0 + 32 * qb + n) * (long)D + h * (D / 2);
+#pragma unroll 8
+            for (int e = 0; e < D / 2; ++e) acc = fmaf(orow[e], (float)grow[e], acc);
         }
-        delta_s[qb] = delta[qb] * inv_bound[qb];
-    }
-    if constexpr (E2::SCALED) {
-        float bm = 0.f;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) bm = fmaxf(bm, bound[qb]);
-        bm = wave_max(bm);
-        if (lane == 0 && active) atomicMax(&p.scal[1], __float_as_uint(bm));
+        ctr[qb] = xhalf_sum(acc);
     }
 
-    // ---- sweep B: dQ -------------------------------------------------------------------
-    f32x16 X[D / 32][QB];
+    f32x16 XA[D / 32][QB], XB[D / 32][QB];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
+            for (int v = 0; v < 16; ++v) { XA[db][qb][v] = 0.f; XB[db][qb][v] = 0.f; }
+
+    Staged<RT::NCH> stk, stv;
+    Staged<CT::NCH> stkt;
+    f32x16 S[2][QB], dP[2][QB];
+    unsigned long long ntile = 0;
+    float num[QB], den[QB], gmax[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
     stream_tiles(
         *tl_count,
         [&](int it) {
@@ -153,7 +122,7 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
             stage1<E, D, QB>(S, kbuf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
             stage1<E, D, QB>(dP, vbuf, gf, lane);
-            ++ntile_b;
+            ++ntile;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -164,15 +133,37 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
                         float u;
                         if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
                         else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
-                        S[kb][qb][v] = u * fmaf(dP[kb][qb][v], inv_bound[qb], -delta_s[qb]);
+                        const float t = u * (dP[kb][qb][v] - ctr[qb]);
+                        num[qb] += t;
+                        den[qb] += u;
+                        gmax[qb] = fmaxf(gmax[qb], fabsf(t));
+                        S[kb][qb][v] = t * inv_pb;
+                        dP[kb][qb][v] = u;
                     }
-            stage2<E2, D, QB>(X, ktbuf, S, lane);
+            stage2<E2, D, QB>(XA, ktbuf, S, lane);
+            stage2<E2, D, QB>(XB, ktbuf, dP, lane);
         });
-    if (active) store_owned_T<D, QB>(p.dQ + hoff, qw0, X, out_scale, lane);
-    if (lane == 0) {
-        atomicAdd(&p.stats[2], ntile_a * QB);
-        atomicAdd(&p.stats[3], ntile_b * QB);
+
+    // delta, and the bound max|U (dP - e)| + |delta - e| >= |dS| published for the dK/dV kernel
+    float bm = 0.f;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float dn = xhalf_sum(den[qb]);
+        const float drel = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;      // delta - e
+        if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = drel + ctr[qb];
+        bm = fmaxf(bm, xhalf_max(gmax[qb]) + fabsf(drel));
+        const float sa = pb * p.inv_sqrt_d, sb = drel * p.inv_sqrt_d;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) XA[db][qb][v] = sa * XA[db][qb][v] - sb * XB[db][qb][v];
     }
+    if constexpr (E2::SCALED) {
+        bm = wave_max(bm);
+        if (lane == 0 && active) atomicMax(&p.scal[1], __float_as_uint(bm));
+    }
+    if (active) store_owned_T<D, QB>(p.dQ + hoff, qw0, XA, 1.f, lane);
+    if (lane == 0) atomicAdd(&p.stats[3], ntile * QB);
 }
 
 template <class E, class E2, int D, int QB>

@@ -12,14 +12,16 @@ constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 struct Params {
     const void* Q; const void* K; const void* V; const void* dO;
     const void* Kt; const void* Vt; const void* Qt; const void* dOt;   // transposed copies [BH][d][N]
-    float* O; float* tau; float* delta;
+    float* O;             // forward: output; backward: the forward's output (nullable)
+    float* tau; float* delta;
     float* dQ; float* dK; float* dV;
     int32_t* mask;        // exported / final mask   [BH][T][W]
     int32_t* wmask;       // working mask (superset) [BH][T][W]
     int32_t* iters;       // nullable
     unsigned long long* stats;
-    // bits of two non-negative floats kept in the workspace (atomicMax on the bit patterns):
-    // scal[0] = max |dO|, scal[1] = max over rows of the bound on |dS| (see dq_kernel)
+    // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
+    // scal[0] = max |dO|, scal[1] = max over rows of the bound on |dS| (see dq_kernel),
+    // scal[2] = max row 2-norm of dO, scal[3] = max row 2-norm of V
     unsigned int* scal;
     int BH, N, T, W;
     int causal;

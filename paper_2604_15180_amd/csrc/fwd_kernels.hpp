@@ -447,17 +447,33 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(const typename Ein::
 
 __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int* scal) {
     if ((int)threadIdx.x < n) stats[threadIdx.x] = 0ull;
-    if (scal && threadIdx.x < 2) scal[threadIdx.x] = 0u;
+    if (scal && threadIdx.x < 4) scal[threadIdx.x] = 0u;
 }
 
-// max |x| over a tensor -> atomicMax on the float's bit pattern (non-negative floats order as ints)
-template <class E>
-__global__ __launch_bounds__(THREADS) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
-    float m = 0.f;
-    for (long i = blockIdx.x * (long)THREADS + threadIdx.x; i < n; i += (long)gridDim.x * THREADS)
-        m = fmaxf(m, fabsf((float)x[i]));
-    m = wave_max(m);
-    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
+// Per row of a [rows][D] matrix: max |x| -> amax_bits (nullable) and max row 2-norm -> norm_bits,
+// both by atomicMax on the float's bit pattern (non-negative floats order as unsigned ints).
+template <class E, int D>
+__global__ __launch_bounds__(THREADS) void rownorm_kernel(const typename E::elem* x, long rows, unsigned int* amax_bits,
+                                                          unsigned int* norm_bits) {
+    const int lane = threadIdx.x & 63;
+    float am = 0.f, nm = 0.f;
+    for (long row = blockIdx.x * (long)NWAVES + (threadIdx.x >> 6); row < rows; row += (long)gridDim.x * NWAVES) {
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < D / 64; ++e) {
+            const float v = (float)x[row * D + e * 64 + lane];
+            ss = fmaf(v, v, ss);
+            am = fmaxf(am, fabsf(v));
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
+        nm = fmaxf(nm, ss);
+    }
+    am = wave_max(am);
+    if (lane == 0) {
+        if (amax_bits) atomicMax(amax_bits, __float_as_uint(am));
+        atomicMax(norm_bits, __float_as_uint(sqrtf(nm) * 1.0001f));
+    }
 }
 
 }  // namespace ea
