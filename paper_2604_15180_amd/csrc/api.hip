@@ -12,8 +12,12 @@ namespace {
 
 using namespace ea;
 
-constexpr int QB = 1;        // 32*QB owned rows per wave, 128*QB per work-group (output and backward kernels)
-constexpr int QB_TAU = 1;    // same for the threshold kernel, which carries no output accumulators
+constexpr int QB = 1;        // 32*QB owned rows per wave
+// waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
+constexpr int NW_TAU = 4, NBUF_TAU = 2;
+constexpr int NW_OUT = 4, NBUF_OUT = 2;
+constexpr int NW_DQ = 4, NBUF_DQ = 1;
+constexpr int NW_DKDV = 4, NBUF_DKDV = 1;
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
 
@@ -52,7 +56,7 @@ void timer_begin_call() {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, delta, mask, wmask, total;
+    size_t stats, a, b, c, delta, mask, wmask, tmax, total;
 };
 
 // element size of the transposed copies
@@ -65,6 +69,7 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.stats = off; off += align256(EA_STATS_WORDS * 8);
     L.a = off; off += align256(BH * N * d * t_elem(t));          // V^T
     L.wmask = off; off += align256(BH * T * W * 4);
+    L.tmax = off; off += align256(BH * T * (size_t)N * 2);       // per-row key-tile maxima, fp16
     L.total = off;
     return L;
 }
@@ -104,17 +109,17 @@ int alpha_mode(float alpha) {
     } while (0)
 
 template <class K>
-int launch(K kernel, dim3 grid, size_t smem, hipStream_t s, Params p) {
+int launch(K kernel, dim3 grid, int threads, size_t smem, hipStream_t s, Params p) {
     // kernels above 64 KiB of dynamic LDS need the limit raised (cheap, idempotent)
     EA_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(kernel, grid, dim3(THREADS), smem, s, p);
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, s, p);
     EA_HIP(hipGetLastError());
     return EA_OK;
 }
 
 template <class Ein, class Eout, int D>
 int launch_transpose(const void* in, void* out, int BH, int N, const unsigned int* amax_bits, hipStream_t s) {
-    hipLaunchKernelGGL((transpose_kernel<Ein, Eout, D>), dim3(N / 64, D / 64, BH), dim3(THREADS), 0, s,
+    hipLaunchKernelGGL((transpose_kernel<Ein, Eout, D>), dim3(N / 64, D / 64, BH), dim3(256), 0, s,
                        (const typename Ein::elem*)in, (typename Eout::elem*)out, N, amax_bits);
     EA_HIP(hipGetLastError());
     return EA_OK;
@@ -130,34 +135,38 @@ struct Ops {
             rc = launch_transpose<E, E2F, D>(p.V, (void*)p.Vt, p.BH, p.N, nullptr, s);
             if (rc) return rc;
         }
-        const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
-            const dim3 grid_tau(p.BH * ((p.N + 128 * QB_TAU - 1) / (128 * QB_TAU)));
-            rc = launch(tau_kernel<E, D, QB_TAU, AM, NBINS>, grid_tau, TauSmem<E, D, QB_TAU, NBINS>::BYTES, s, p);
+            rc = launch(tau_kernel<E, D, QB, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64,
+                        TauSmem<E, D, QB, NBINS, NW_TAU, NBUF_TAU>::BYTES, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
-        return launch(out_kernel<E, E2F, D, QB, AM, false>, grid, OutSmem<E, E2F, D, QB, false>::BYTES, s, p);
+        return launch(out_kernel<E, E2F, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
+                      OutSmem<E, E2F, D, QB, false, NW_OUT, NBUF_OUT>::BYTES, s, p);
+    }
+    static dim3 groups(const Params& p, int nw) {
+        const int rows = 32 * QB * nw;
+        return dim3(p.BH * ((p.N + rows - 1) / rows));
     }
     static int bwd(Params p, bool rebuild_mask, hipStream_t s) {
         int rc;
-        const dim3 grid(p.BH * ((p.N + 128 * QB - 1) / (128 * QB)));
         if (rebuild_mask) {
             ScopedKernelTime t(EA_TIMER_MASK, s);
             hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
             EA_HIP(hipGetLastError());
-            rc = launch(out_kernel<E, E2F, D, QB, AM, true>, grid, OutSmem<E, E2F, D, QB, true>::BYTES, s, p);
+            rc = launch(out_kernel<E, E2F, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
+                        OutSmem<E, E2F, D, QB, true, NW_OUT, NBUF_OUT>::BYTES, s, p);
             if (rc) return rc;
         }
         const unsigned int* go_amax = nullptr;
         {
         ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
         if (E2B::SCALED) {
-            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(THREADS), 0, s, (const typename E::elem*)p.dO,
+            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
                                (long)p.BH * p.N, p.scal, p.scal + 2);
             EA_HIP(hipGetLastError());
-            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(THREADS), 0, s, (const typename E::elem*)p.V,
+            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.V,
                                (long)p.BH * p.N, (unsigned int*)nullptr, p.scal + 3);
             EA_HIP(hipGetLastError());
             go_amax = p.scal;
@@ -168,11 +177,13 @@ struct Ops {
         }
         {
             ScopedKernelTime t(EA_TIMER_DQ, s);
-            rc = launch(dq_kernel<E, E2B, D, QB, AM>, grid, DqSmem<E, E2B, D, QB>::BYTES, s, p);
+            rc = launch(dq_kernel<E, E2B, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64,
+                        DqSmem<E, E2B, D, QB, NW_DQ, NBUF_DQ>::BYTES, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_DKDV, s);
-        return launch(dkdv_kernel<E, E2B, D, QB, AM>, grid, DkdvSmem<E, E2B, D, QB>::BYTES, s, p);
+        return launch(dkdv_kernel<E, E2B, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64,
+                      DkdvSmem<E, E2B, D, QB, NW_DKDV, NBUF_DKDV>::BYTES, s, p);
     }
 };
 
@@ -242,6 +253,7 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.stats = (unsigned long long*)(ws + L.stats);
     p.Vt = ws + L.a;
     p.wmask = (int32_t*)(ws + L.wmask);
+    p.tmax = (_Float16*)(ws + L.tmax);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
     timer_begin_call();

@@ -10,31 +10,29 @@
 
 namespace ea {
 
-template <class E, class E2, int D, int QB>
+template <class E, class E2, int D, int QB, int NW, int NBUF>
 struct DqSmem {
-    static constexpr int BR = 32 * QB * NWAVES;
-    static constexpr int MR = BR / 64;
+    static constexpr int BR = 32 * QB * NW;
+    static constexpr int MR = (BR + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
     static constexpr int CBYTES = ColTile<E2, D>::BYTES;
-    static constexpr int BYTES = 2 * RBYTES + CBYTES + 4 * (MR * MAX_W + MAX_T + 4);
+    static constexpr int SET = 2 * RBYTES + CBYTES;          // K, V, K^T tiles
+    static constexpr int BYTES = NBUF * SET + 4 * (MR * MAX_W + MAX_T + 4);
 };
 
-template <class E, class E2, int D, int QB, int AM>
-__global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
-    using SM = DqSmem<E, E2, D, QB>;
-    using RT = RowTile<E, D>;
-    using CT = ColTile<E2, D>;
+template <class E, class E2, int D, int QB, int AM, int NW, int NBUF>
+__global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
+    using SM = DqSmem<E, E2, D, QB, NW, NBUF>;
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
+    constexpr int THREADS = NW * 64;
     extern __shared__ __align__(16) char smem[];
-    char* kbuf = smem;
-    char* vbuf = smem + SM::RBYTES;
-    char* ktbuf = smem + 2 * SM::RBYTES;
-    uint32_t* fm = (uint32_t*)(smem + 2 * SM::RBYTES + SM::CBYTES);
+    char* bufs = smem;                        // set s at bufs + s*SET: K tile, V tile, K^T tile
+    uint32_t* fm = (uint32_t*)(smem + NBUF * SM::SET);
     int* tl = (int*)(fm + MR * MAX_W);
     int* tl_count = tl + MAX_T;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int N = p.N, T = p.T, W = p.W;
     int bh, I;
@@ -50,7 +48,6 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
 
     for (int i = tid; i < MR * W; i += THREADS)
         fm[i] = (I * MR + i / W < T) ? (uint32_t)p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
-    __syncthreads();
     build_tile_list(fm, MR, W, tl, tl_count, tid);
 
     Owned<E, D, QB> qf, gf;
@@ -96,29 +93,26 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) { XA[db][qb][v] = 0.f; XB[db][qb][v] = 0.f; }
 
-    Staged<RT::NCH> stk, stv;
-    Staged<CT::NCH> stkt;
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile = 0;
     float num[QB], den[QB], gmax[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
-    stream_tiles(
+    stream_tiles<NBUF>(
         *tl_count,
-        [&](int it) {
+        [&](int it, int set) {
             const long j = tl[it];
-            gload_rows<E, D>(stk, Kh, j * 64, tid);
-            gload_rows<E, D>(stv, Vh, j * 64, tid);
-            gload_cols<E2, D>(stkt, Kth, N, j * 64, tid);
+            char* b = bufs + set * SM::SET;
+            issue_rows<E, D, NW>(b, Kh, j * 64, wave, lane);
+            issue_rows<E, D, NW>(b + SM::RBYTES, Vh, j * 64, wave, lane);
+            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES, Kth, N, j * 64, wave, lane);
         },
-        [&]() {
-            sstore_rows<E, D>(stk, kbuf, tid);
-            sstore_rows<E, D>(stv, vbuf, tid);
-            sstore_cols<E2, D>(stkt, ktbuf, tid);
-        },
-        [&](int it) {
+        [&](int it, int set) {
             const int j = tl[it];
             if (!mask_bit(fm, W, myrow, j)) return;
+            const char* kbuf = bufs + set * SM::SET;
+            const char* vbuf = kbuf + SM::RBYTES;
+            const char* ktbuf = kbuf + 2 * SM::RBYTES;
             stage1<E, D, QB>(S, kbuf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
             stage1<E, D, QB>(dP, vbuf, gf, lane);
@@ -166,33 +160,29 @@ __global__ __launch_bounds__(THREADS) void dq_kernel(Params p) {
     if (lane == 0) atomicAdd(&p.stats[3], ntile * QB);
 }
 
-template <class E, class E2, int D, int QB>
+template <class E, class E2, int D, int QB, int NW, int NBUF>
 struct DkdvSmem {
-    static constexpr int BC = 32 * QB * NWAVES;
-    static constexpr int MC = BC / 64;
+    static constexpr int BC = 32 * QB * NW;
+    static constexpr int MC = (BC + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
     static constexpr int CBYTES = ColTile<E2, D>::BYTES;
-    static constexpr int BYTES = 2 * RBYTES + 2 * CBYTES + 4 * (2 * TILE + MAX_T + 16);
+    static constexpr int SET = 2 * RBYTES + 2 * CBYTES + 4 * 2 * TILE;   // Q, dO, Q^T, dO^T tiles, tau, delta
+    static constexpr int BYTES = NBUF * SET + 4 * (MAX_T + 16);
 };
 
-template <class E, class E2, int D, int QB, int AM>
-__global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
-    using SM = DkdvSmem<E, E2, D, QB>;
-    using RT = RowTile<E, D>;
-    using CT = ColTile<E2, D>;
+template <class E, class E2, int D, int QB, int AM, int NW, int NBUF>
+__global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
+    using SM = DkdvSmem<E, E2, D, QB, NW, NBUF>;
     using elem = typename E::elem;
     constexpr int BC = SM::BC, MC = SM::MC;
+    constexpr int THREADS = NW * 64;
+    static_assert(NW >= 2, "tau and delta rows are fetched by waves 0 and 1");
     extern __shared__ __align__(16) char smem[];
-    char* qbuf = smem;
-    char* gbuf = smem + SM::RBYTES;
-    char* qtbuf = smem + 2 * SM::RBYTES;
-    char* gtbuf = qtbuf + SM::CBYTES;
-    float* tau_s = (float*)(gtbuf + SM::CBYTES);
-    float* del_s = tau_s + TILE;
-    int* tl = (int*)(del_s + TILE);          // entries: query tile | column flags << 16
-    int* wcnt = tl + MAX_T;                  // per-wave counts + running total
+    char* bufs = smem;                       // set s: Q tile, dO tile, Q^T tile, dO^T tile, tau[64], delta[64]
+    int* tl = (int*)(smem + NBUF * SM::SET); // entries: query tile | column flags << 16
+    int* wcnt = tl + MAX_T;                  // per-wave counts, [8] = running total
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int N = p.N, T = p.T, W = p.W;
     int bh, J;
@@ -219,7 +209,7 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
 
     // ---- column walk of the row-packed mask: list of query tiles with a set bit -------------
     const int i_min = p.causal ? jc0 : 0;
-    if (tid == 0) wcnt[4] = 0;
+    if (tid == 0) wcnt[8] = 0;
     __syncthreads();
     for (int base = i_min; base < T; base += THREADS) {
         const int i = base + tid;
@@ -236,15 +226,19 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
         const unsigned long long bal = __ballot(flags != 0);
         if (lane == 0) wcnt[wave] = __popcll(bal);
         __syncthreads();
-        int off = wcnt[4];
+        int off = wcnt[8];
         for (int w2 = 0; w2 < wave; ++w2) off += wcnt[w2];
         off += __popcll(bal & ((1ull << lane) - 1ull));
         if (flags != 0) tl[off] = i | (flags << 16);
         __syncthreads();
-        if (tid == 0) wcnt[4] += wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        if (tid == 0) {
+            int tot = wcnt[8];
+            for (int w2 = 0; w2 < NW; ++w2) tot += wcnt[w2];
+            wcnt[8] = tot;
+        }
         __syncthreads();
     }
-    const int ntl = wcnt[4];
+    const int ntl = wcnt[8];
 
     Owned<E, D, QB> kf, vf;
     load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, active ? kw0 : 0, lane);
@@ -258,33 +252,32 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) { XV[db][qb][v] = 0.f; XK[db][qb][v] = 0.f; }
 
-    Staged<RT::NCH> stq, stg;
-    Staged<CT::NCH> stqt, stgt;
-    float st_vec = 0.f;
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile_done = 0;
-    stream_tiles(
+    constexpr int VEC_OFF = 2 * SM::RBYTES + 2 * SM::CBYTES;
+    stream_tiles<NBUF>(
         ntl,
-        [&](int it) {
+        [&](int it, int set) {
             const long i = tl[it] & 0xffff;
-            gload_rows<E, D>(stq, Qh, i * 64, tid);
-            gload_rows<E, D>(stg, Gh, i * 64, tid);
-            gload_cols<E2, D>(stqt, Qth, N, i * 64, tid);
-            gload_cols<E2, D>(stgt, Gth, N, i * 64, tid);
-            if (tid < TILE) st_vec = p.tau[(long)bh * N + i * 64 + tid];
-            else if (tid < 2 * TILE) st_vec = p.delta[(long)bh * N + i * 64 + tid - TILE] * ds_inv;
+            char* b = bufs + set * SM::SET;
+            issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
+            issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
+            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES, Qth, N, i * 64, wave, lane);
+            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES + SM::CBYTES, Gth, N, i * 64, wave, lane);
+            // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
+            if (wave == 0) load4_to_lds(p.tau + (long)bh * N + i * 64 + lane, b + VEC_OFF);
+            if (wave == 1) load4_to_lds(p.delta + (long)bh * N + i * 64 + lane, b + VEC_OFF + 4 * TILE);
         },
-        [&]() {
-            sstore_rows<E, D>(stq, qbuf, tid);
-            sstore_rows<E, D>(stg, gbuf, tid);
-            sstore_cols<E2, D>(stqt, qtbuf, tid);
-            sstore_cols<E2, D>(stgt, gtbuf, tid);
-            if (tid < 2 * TILE) tau_s[tid] = st_vec;     // tau_s and del_s are adjacent
-        },
-        [&](int it) {
+        [&](int it, int set) {
             const int ent = tl[it];
             const long i = ent & 0xffff;
             if (!((ent >> (16 + mycol)) & 1)) return;
+            const char* qbuf = bufs + set * SM::SET;
+            const char* gbuf = qbuf + SM::RBYTES;
+            const char* qtbuf = qbuf + 2 * SM::RBYTES;
+            const char* gtbuf = qtbuf + SM::CBYTES;
+            const float* tau_s = (const float*)(qbuf + VEC_OFF);
+            const float* del_s = tau_s + TILE;
             stage1<E, D, QB>(S, qbuf, kf, lane);
             // streamed rows are queries here: hide key > query
             if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, (int)i * 64, (int)kw0, lane);
@@ -295,10 +288,9 @@ __global__ __launch_bounds__(THREADS) void dkdv_kernel(Params p) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int row = trow(kb, v, h);
-                    const float tq = tau_s[row], dq = del_s[row];
+                    const float tq = tau_s[row], dq = del_s[row] * ds_inv;
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        // del_s holds delta * ds_inv
                         const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
                         float u;
                         if constexpr (AM == ALPHA_15) u = yp;

@@ -18,6 +18,7 @@ struct Params {
     int32_t* mask;        // exported / final mask   [BH][T][W]
     int32_t* wmask;       // working mask (superset) [BH][T][W]
     int32_t* iters;       // nullable
+    _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
     // scal[0] = max |dO|, scal[1] = max over rows of the bound on |dS| (see dq_kernel),
@@ -63,17 +64,29 @@ template <int AM> EA_DEV float pow_r2(float y, float r) {
     else return __builtin_amdgcn_exp2f((r - 2.f) * __builtin_amdgcn_logf(y));
 }
 
-// Software-pipelined walk over `ntiles` streamed tiles with one LDS buffer set:
-// registers <- global(it+1) is issued before the math on tile `it`, so the loads fly under it.
-template <class LoadF, class StoreF, class ComputeF>
-EA_DEV void stream_tiles(int ntiles, LoadF gload, StoreF sstore, ComputeF compute) {
-    if (ntiles > 0) gload(0);
-    for (int it = 0; it < ntiles; ++it) {
-        sstore();
+// Walk over `ntiles` streamed tiles.  issue(it, set) starts the direct global->LDS loads of tile
+// `it` into buffer set `set`; compute(it, set) does the math on it.
+// NBUF == 2: the loads of tile it+1 fly under the math of tile it, one barrier per tile.
+// NBUF == 1: half the LDS; loads and math alternate (other work-groups on the CU fill the gaps).
+template <int NBUF, class IssueF, class ComputeF>
+EA_DEV void stream_tiles(int ntiles, IssueF issue, ComputeF compute) {
+    if constexpr (NBUF == 2) {
+        if (ntiles > 0) issue(0, 0);
+        for (int it = 0; it < ntiles; ++it) {
+            wait_loads();
+            __syncthreads();     // tile `it` has landed for every wave; everyone is done with tile it-1
+            if (it + 1 < ntiles) issue(it + 1, (it + 1) & 1);
+            compute(it, it & 1);
+        }
         __syncthreads();
-        if (it + 1 < ntiles) gload(it + 1);
-        compute(it);
-        __syncthreads();
+    } else {
+        for (int it = 0; it < ntiles; ++it) {
+            issue(it, 0);
+            wait_loads();
+            __syncthreads();
+            compute(it, 0);
+            __syncthreads();
+        }
     }
 }
 
@@ -81,6 +94,7 @@ EA_DEV void stream_tiles(int ntiles, LoadF gload, StoreF sstore, ComputeF comput
 // Called by all threads; the first wave does the work.  Uses one wave-wide exclusive scan of
 // the per-word popcounts (W <= 64).
 EA_DEV void build_tile_list(const uint32_t* words, int rows, int W, int* list, int* count, int tid) {
+    __syncthreads();
     if (tid < 64) {
         uint32_t u = 0;
         if (tid < W)

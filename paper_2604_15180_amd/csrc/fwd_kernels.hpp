@@ -1,6 +1,7 @@
 // Forward kernels (Alg. 1 of the AdaSplash-2 paper), re-cut for CDNA4:
-//   tau_kernel : Phase 1 (row max), Phase 2 (LDS histogram -> tau_0), Phase 3 (safeguarded
-//                Halley/Newton refinement to convergence + working block mask at tau_0)
+//   tau_kernel : Phase 1 (row max, plus per-row tile maxima -> candidate tiles), Phase 2 (LDS
+//                histogram over the candidates -> tau_0), Phase 3 (safeguarded Halley/Newton
+//                refinement to convergence + working block mask at tau_0)
 //   out_kernel : Phase 4 (O = P V over the working mask) + the exported mask at the final tau
 // One work-group = 128*QB query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
 // B operands in registers; 64-key tiles of K (and V^T) stream through LDS.
@@ -67,20 +68,21 @@ EA_DEV float solve_histogram(const uint32_t* H, float r) {
     }
 }
 
-template <class E, int D, int QB, int NB>
+template <class E, int D, int QB, int NB, int NW, int NBUF>
 struct TauSmem {
-    static constexpr int BR = 32 * QB * NWAVES;
-    static constexpr int MR = BR / 64;
-    static constexpr int KBYTES = RowTile<E, D>::BYTES;
+    static constexpr int BR = 32 * QB * NW;
+    static constexpr int MR = (BR + 63) / 64;
+    static constexpr int KBYTES = NBUF * RowTile<E, D>::BYTES;
     static constexpr int HIST_WORDS = BR * (NB + 1);
     // floats: base, thr, lo, hi, F, G, Hs per row; ints: done, iters per row
-    static constexpr int BYTES = KBYTES + 4 * (HIST_WORDS + 7 * BR + 2 * BR + MR * MAX_W + MAX_T + 4);
+    static constexpr int BYTES = KBYTES + 4 * (HIST_WORDS + 7 * BR + 2 * BR + 2 * MR * MAX_W + MAX_T + 4);
 };
 
-template <class E, int D, int QB, int AM, int NB>
-__global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
-    using SM = TauSmem<E, D, QB, NB>;
+template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
+__global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
+    using SM = TauSmem<E, D, QB, NB, NW, NBUF>;
     using KT = RowTile<E, D>;
+    constexpr int THREADS = NW * 64;
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
     extern __shared__ __align__(16) char smem[];
@@ -96,16 +98,18 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
     int* rs_done = (int*)(rs_H + BR);
     int* rs_iters = rs_done + BR;
     uint32_t* wm = (uint32_t*)(rs_iters + BR);
-    int* tl = (int*)(wm + MR * MAX_W);
+    uint32_t* cand = wm + MR * MAX_W;
+    int* tl = (int*)(cand + MR * MAX_W);
     int* tl_count = tl + MAX_T;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
     const int N = p.N, T = p.T, W = p.W;
     int bh, I;
     map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
     const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
     const bool active = qw0 < N;          // N is a multiple of 64: the last group may be half empty
+    _Float16* tmax_g = p.tmax + (long)bh * T * N;      // [T][N] per-row tile maxima, rounded up
     const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + (long)bh * N * D;
     const int njt = p.causal ? min((int)((q0 + BR) / 64), T) : T;          // tiles the group streams
@@ -115,16 +119,14 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
-    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;
+    for (int i = tid; i < MR * W; i += THREADS) { wm[i] = 0u; cand[i] = 0u; }
     for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
 
-    Staged<KT::NCH> st;
     f32x16 C[2][QB];
     unsigned long long ntile_done = 0;
-    auto sstore = [&]() { sstore_rows<E, D>(st, kbuf, tid); };
-    auto gload_seq = [&](int it) { gload_rows<E, D>(st, Kh, (long)it * 64, tid); };
-    auto scores = [&](int j) {
-        stage1<E, D, QB>(C, kbuf, qf, lane);
+    auto issue_seq = [&](int it, int set) { issue_rows<E, D, NW>(kbuf + set * KT::BYTES, Kh, (long)it * 64, wave, lane); };
+    auto scores = [&](int j, int set) {
+        stage1<E, D, QB>(C, kbuf + set * KT::BYTES, qf, lane);
         if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
         ++ntile_done;
     };
@@ -133,15 +135,23 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
     float rmax[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) rmax[qb] = -INFINITY;
-    stream_tiles(njt, gload_seq, sstore, [&](int j) {
+    // Besides the running maximum, every (row, key tile) maximum goes to HBM (fp16, rounded up):
+    // once the row maxima are final, only tiles holding a score within 1 of its row's maximum
+    // (in (alpha-1) s units, Eq. 5-6) can matter to the histogram, to f, or to P.
+    stream_tiles<NBUF>(njt, issue_seq, [&](int j, int set) {
         if (j >= wjt) return;
-        scores(j);
+        scores(j, set);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
+        for (int qb = 0; qb < QB; ++qb) {
+            float lm = -INFINITY;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) rmax[qb] = fmaxf(rmax[qb], C[kb][qb][v]);
+                for (int v = 0; v < 16; ++v) lm = fmaxf(lm, C[kb][qb][v]);
+            rmax[qb] = fmaxf(rmax[qb], lm);
+            const float tm = xhalf_max(lm);
+            if (h == 0) tmax_g[(long)j * N + qw0 + 32 * qb + n] = (_Float16)(tm + fabsf(tm) * (1.f / 1024.f) + 1e-7f);
+        }
     });
     float base[QB];   // m - 1 in raw units: z = x - base (Eq. 6)
 #pragma unroll
@@ -150,11 +160,31 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
         base[qb] = fmaf(c, rmax[qb], -1.f);
         if (h == 0) rs_base[wave * 32 * QB + 32 * qb + n] = base[qb];
     }
+    // candidate tiles of this wave's rows: lanes 0-31 test tile j0, lanes 32-63 tile j0+1
+    __threadfence();
+    for (int j0 = 0; j0 < wjt; j0 += 2) {
+        const int j = j0 + h;
+        bool cnd = false;
+        if (j < wjt) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+                cnd |= fmaf(c, (float)tmax_g[(long)j * N + qw0 + 32 * qb + n], -base[qb]) >= 0.f;
+        }
+        const unsigned long long bal = __ballot(cnd);
+        if (lane == 0) {
+            if (bal & 0xffffffffull) atomicOr(&cand[myrow * W + (j0 >> 5)], 1u << (j0 & 31));
+            if (bal >> 32) atomicOr(&cand[myrow * W + ((j0 + 1) >> 5)], 1u << ((j0 + 1) & 31));
+        }
+    }
+    __syncthreads();
+    build_tile_list(cand, MR, W, tl, tl_count, tid);
+    auto issue_list = [&](int it, int set) { issue_rows<E, D, NW>(kbuf + set * KT::BYTES, Kh, (long)tl[it] * 64, wave, lane); };
 
     // ---- Phase 2: per-row histogram of the centred scores in LDS (Eq. 7-8) ---------------
-    stream_tiles(njt, gload_seq, sstore, [&](int j) {
-        if (j >= wjt) return;
-        scores(j);
+    stream_tiles<NBUF>(*tl_count, issue_list, [&](int it, int set) {
+        const int j = tl[it];
+        if (!mask_bit(cand, W, myrow, j)) return;
+        scores(j, set);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float lmax = -INFINITY;
@@ -199,10 +229,9 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
             cnt[qb] = 0;
         }
         const bool first = (sweep == 0);
-        auto body = [&](int j) {
-            if (j >= wjt) return;
-            if (!first && !mask_bit(wm, W, myrow, j)) return;
-            scores(j);
+        auto body = [&](int j, int set) {
+            if (!mask_bit(first ? cand : wm, W, myrow, j)) return;
+            scores(j, set);
             bool hit = false;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
@@ -239,9 +268,7 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
             }
             if (first && hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
         };
-        if (first) stream_tiles(njt, gload_seq, sstore, body);
-        else stream_tiles(*tl_count, [&](int it) { gload_rows<E, D>(st, Kh, (long)tl[it] * 64, tid); }, sstore,
-                          [&](int it) { body(tl[it]); });
+        stream_tiles<NBUF>(*tl_count, issue_list, [&](int it, int set) { body(tl[it], set); });
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
@@ -296,33 +323,32 @@ __global__ __launch_bounds__(THREADS) void tau_kernel(Params p) {
     if (tid == 0) atomicAdd(&p.stats[5], (unsigned long long)nsweeps);
 }
 
-template <class E, class E2, int D, int QB, bool MASK_ONLY>
+template <class E, class E2, int D, int QB, bool MASK_ONLY, int NW, int NBUF>
 struct OutSmem {
-    static constexpr int BR = 32 * QB * NWAVES;
-    static constexpr int MR = BR / 64;
+    static constexpr int BR = 32 * QB * NW;
+    static constexpr int MR = (BR + 63) / 64;
     static constexpr int KBYTES = RowTile<E, D>::BYTES;
     static constexpr int VBYTES = MASK_ONLY ? 0 : ColTile<E2, D>::BYTES;
-    static constexpr int BYTES = KBYTES + VBYTES + 4 * (2 * MR * MAX_W + MAX_T + 4);
+    static constexpr int SET = KBYTES + VBYTES;              // one buffer set
+    static constexpr int BYTES = NBUF * SET + 4 * (2 * MR * MAX_W + MAX_T + 4);
 };
 
 // Phase 4.  MASK_ONLY: no V, no O - only the mask at the given tau (used by the backward when
 // the caller passes no mask).
-template <class E, class E2, int D, int QB, int AM, bool MASK_ONLY>
-__global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
-    using SM = OutSmem<E, E2, D, QB, MASK_ONLY>;
-    using KT = RowTile<E, D>;
-    using VT = ColTile<E2, D>;
+template <class E, class E2, int D, int QB, int AM, bool MASK_ONLY, int NW, int NBUF>
+__global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
+    using SM = OutSmem<E, E2, D, QB, MASK_ONLY, NW, NBUF>;
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
+    constexpr int THREADS = NW * 64;
     extern __shared__ __align__(16) char smem[];
-    char* kbuf = smem;
-    char* vbuf = smem + SM::KBYTES;
-    uint32_t* wm = (uint32_t*)(smem + SM::KBYTES + SM::VBYTES);
+    char* kbuf = smem;                       // set s: K tile at kbuf + s*SET, V^T tile right after it
+    uint32_t* wm = (uint32_t*)(smem + NBUF * SM::SET);
     uint32_t* fm = wm + MR * MAX_W;
     int* tl = (int*)(fm + MR * MAX_W);
     int* tl_count = tl + MAX_T;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31;
     const int N = p.N, T = p.T, W = p.W;
     int bh, I;
@@ -339,7 +365,6 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
         wm[i] = (I * MR + i / W < T) ? (uint32_t)p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
         fm[i] = 0u;
     }
-    __syncthreads();
     build_tile_list(wm, MR, W, tl, tl_count, tid);
 
     Owned<E, D, QB> qf;
@@ -356,25 +381,19 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
 
-    Staged<KT::NCH> stk;
-    Staged<MASK_ONLY ? 1 : VT::NCH> stv;
     f32x16 C[2][QB];
     unsigned long long ntile_done = 0, npv_done = 0;
-    stream_tiles(
+    stream_tiles<NBUF>(
         *tl_count,
-        [&](int it) {
+        [&](int it, int set) {
             const long j = tl[it];
-            gload_rows<E, D>(stk, Kh, j * 64, tid);
-            if constexpr (!MASK_ONLY) gload_cols<E2, D>(stv, Vth, N, j * 64, tid);
+            issue_rows<E, D, NW>(kbuf + set * SM::SET, Kh, j * 64, wave, lane);
+            if constexpr (!MASK_ONLY) issue_cols<E2, D, NW>(kbuf + set * SM::SET + SM::KBYTES, Vth, N, j * 64, wave, lane);
         },
-        [&]() {
-            sstore_rows<E, D>(stk, kbuf, tid);
-            if constexpr (!MASK_ONLY) sstore_cols<E2, D>(stv, vbuf, tid);
-        },
-        [&](int it) {
+        [&](int it, int set) {
             const int j = tl[it];
             if (!mask_bit(wm, W, myrow, j)) return;
-            stage1<E, D, QB>(C, kbuf, qf, lane);
+            stage1<E, D, QB>(C, kbuf + set * SM::SET, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
             float ymax = 0.f;
@@ -391,7 +410,7 @@ __global__ __launch_bounds__(THREADS) void out_kernel(Params p) {
                     }
             if (!__any(ymax > 0.f)) return;
             if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
-            if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, vbuf, C, lane); ++npv_done; }
+            if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, kbuf + set * SM::SET + SM::KBYTES, C, lane); ++npv_done; }
         });
 
     if constexpr (!MASK_ONLY)
@@ -423,7 +442,7 @@ __global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, int causa
 // [BH][N][D] (elements of Ein) -> [BH][D][N] (elements of Eout), through a 64x64 LDS tile.
 // `amax_bits` (nullable): bits of a float a >= 0; the copy is divided by a when a > 0.
 template <class Ein, class Eout, int D>
-__global__ __launch_bounds__(THREADS) void transpose_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
+__global__ __launch_bounds__(256) void transpose_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
                                                             const unsigned int* amax_bits) {
     __shared__ float tile[64][65];
     float mul = 1.f;
@@ -434,12 +453,12 @@ __global__ __launch_bounds__(THREADS) void transpose_kernel(const typename Ein::
     const int bh = blockIdx.z, r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
     const typename Ein::elem* src = in + (long)bh * N * D;
     typename Eout::elem* dst = out + (long)bh * N * D;
-    for (int i = threadIdx.x; i < 64 * 64; i += THREADS) {
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int rr = i / 64, cc = i % 64;
         tile[rr][cc] = (float)src[(long)(r0 + rr) * D + c0 + cc];
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 64; i += THREADS) {
+    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
         const int cc = i / 64, rr = i % 64;
         dst[(long)(c0 + cc) * N + r0 + rr] = Eout::from_float(tile[rr][cc] * mul);
     }
@@ -453,11 +472,11 @@ __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int
 // Per row of a [rows][D] matrix: max |x| -> amax_bits (nullable) and max row 2-norm -> norm_bits,
 // both by atomicMax on the float's bit pattern (non-negative floats order as unsigned ints).
 template <class E, int D>
-__global__ __launch_bounds__(THREADS) void rownorm_kernel(const typename E::elem* x, long rows, unsigned int* amax_bits,
+__global__ __launch_bounds__(256) void rownorm_kernel(const typename E::elem* x, long rows, unsigned int* amax_bits,
                                                           unsigned int* norm_bits) {
     const int lane = threadIdx.x & 63;
     float am = 0.f, nm = 0.f;
-    for (long row = blockIdx.x * (long)NWAVES + (threadIdx.x >> 6); row < rows; row += (long)gridDim.x * NWAVES) {
+    for (long row = blockIdx.x * 4L + (threadIdx.x >> 6); row < rows; row += (long)gridDim.x * 4) {
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < D / 64; ++e) {

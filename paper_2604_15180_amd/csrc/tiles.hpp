@@ -1,5 +1,5 @@
-// Tile primitives for gfx950 (CDNA4): 32x32 MFMA fragments, LDS tile layouts, global->LDS
-// staging.  Everything here is wave64 code for one 256-thread work-group (4 waves).
+// Tile primitives for gfx950 (CDNA4): 32x32 MFMA fragments, swizzled LDS tile layouts, direct
+// global->LDS loads.  Everything here is wave64 code for a work-group of NW waves.
 //
 // Shapes.  A work-group streams 64-row tiles (keys in the forward and in the dQ kernel, queries
 // in the dK/dV kernel) through LDS; each wave owns 32*QB rows of the other operand in registers.
@@ -27,10 +27,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int THREADS = 256;
-constexpr int NWAVES = 4;
 constexpr int TILE = 64;        // rows of a streamed tile = mask granularity
-constexpr int PAD_BYTES = 16;   // LDS row padding
 
 #define EA_DEV __device__ __forceinline__
 
@@ -79,65 +76,66 @@ EA_DEV int perm_row(int m) {
 }
 
 // ---- LDS layouts ---------------------------------------------------------------------------
-template <class E, int D> struct RowTile {      // 64 rows x D elements, row-major, padded
+// Tiles are filled by direct global->LDS loads (global_load_lds_dwordx4): one wave instruction
+// writes 64 consecutive 16-byte chunks, so rows cannot be padded.  Bank conflicts are avoided by
+// an XOR swizzle instead: chunk c of row r lives at chunk position c ^ swz(r) of that row, where
+// swz makes the 16 rows that one ds_read_b128 phase touches land in 16 distinct bank groups.
+// The loading lane simply fetches the global chunk that belongs at its LDS position.
+template <int CPR> EA_DEV int swz(int row) {   // CPR = 16-byte chunks per row (8, 16 or 32)
+    if constexpr (CPR == 8) return (row >> 1) & 7;
+    else return row & 15;
+}
+template <class E, int D> struct RowTile {      // 64 rows x D elements, row-major
     static constexpr int ROW_BYTES = D * (int)sizeof(typename E::elem);
-    static constexpr int LD_BYTES = ROW_BYTES + PAD_BYTES;
-    static constexpr int BYTES = TILE * LD_BYTES;
-    static constexpr int CHUNKS_PER_ROW = ROW_BYTES / 16;
-    static constexpr int NCH = TILE * CHUNKS_PER_ROW / THREADS;   // 16-byte chunks per thread
+    static constexpr int BYTES = TILE * ROW_BYTES;
+    static constexpr int CPR = ROW_BYTES / 16;
+    static constexpr int NINST = BYTES / 1024;   // wave-wide load instructions per tile
 };
-template <class E, int D> struct ColTile {      // D rows x 64 elements (the transposed tile), padded
+template <class E, int D> struct ColTile {      // D rows x 64 elements (the transposed tile)
     static constexpr int ROW_BYTES = TILE * (int)sizeof(typename E::elem);
-    static constexpr int LD_BYTES = ROW_BYTES + PAD_BYTES;
-    static constexpr int BYTES = D * LD_BYTES;
-    static constexpr int CHUNKS_PER_ROW = ROW_BYTES / 16;
-    static constexpr int NCH = D * CHUNKS_PER_ROW / THREADS;
+    static constexpr int BYTES = D * ROW_BYTES;
+    static constexpr int CPR = ROW_BYTES / 16;
+    static constexpr int NINST = BYTES / 1024;
 };
 
-template <int NCH> struct Staged { u32x4 r[NCH]; };
+EA_DEV void load16_to_lds(const void* g, char* lds_wave_base) {
+    // LDS address = wave-uniform base + lane * 16 (the instruction offset stays 0: it would be
+    // added to the global address as well)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
 
-// global [.., D] row-major rows row0..row0+63 -> registers
-template <class E, int D>
-EA_DEV void gload_rows(Staged<RowTile<E, D>::NCH>& st, const typename E::elem* g, long row0, int tid) {
+EA_DEV void load4_to_lds(const void* g, char* lds_wave_base) {   // LDS address = base + lane * 4
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
+}
+
+// rows row0..row0+63 of a row-major [.., D] matrix -> LDS tile; the NW waves share the NINST loads
+template <class E, int D, int NW>
+EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave, int lane) {
     using L = RowTile<E, D>;
+    static_assert(L::NINST % NW == 0, "loads must divide evenly over the waves");
     const char* base = (const char*)g + row0 * (long)L::ROW_BYTES;
 #pragma unroll
-    for (int p = 0; p < L::NCH; ++p) {
-        const int c = p * THREADS + tid;
-        st.r[p] = *(const u32x4*)(base + (long)c * 16);   // rows are contiguous in memory
+    for (int i = 0; i < L::NINST / NW; ++i) {
+        const int t = i * NW + wave;              // wave is wave-uniform (an SGPR)
+        const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
+        load16_to_lds(base + row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16), lds + t * 1024);
     }
 }
-template <class E, int D>
-EA_DEV void sstore_rows(const Staged<RowTile<E, D>::NCH>& st, char* lds, int tid) {
-    using L = RowTile<E, D>;
-#pragma unroll
-    for (int p = 0; p < L::NCH; ++p) {
-        const int c = p * THREADS + tid;
-        const int row = c / L::CHUNKS_PER_ROW, col = c % L::CHUNKS_PER_ROW;
-        *(u32x4*)(lds + row * L::LD_BYTES + col * 16) = st.r[p];
-    }
-}
-// global transposed copy [D][N] (elements of E), columns col0..col0+63 -> registers
-template <class E, int D>
-EA_DEV void gload_cols(Staged<ColTile<E, D>::NCH>& st, const typename E::elem* gT, long N, long col0, int tid) {
+// columns col0..col0+63 of the transposed copy [D][N] -> LDS tile
+template <class E, int D, int NW>
+EA_DEV void issue_cols(char* lds, const typename E::elem* gT, long N, long col0, int wave, int lane) {
     using L = ColTile<E, D>;
+    static_assert(L::NINST % NW == 0, "loads must divide evenly over the waves");
 #pragma unroll
-    for (int p = 0; p < L::NCH; ++p) {
-        const int c = p * THREADS + tid;
-        const int row = c / L::CHUNKS_PER_ROW, col = c % L::CHUNKS_PER_ROW;
-        st.r[p] = *(const u32x4*)((const char*)(gT + (long)row * N + col0) + col * 16);
+    for (int i = 0; i < L::NINST / NW; ++i) {
+        const int t = i * NW + wave;
+        const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
+        load16_to_lds((const char*)(gT + (long)row * N + col0) + ((pos ^ swz<L::CPR>(row)) * 16), lds + t * 1024);
     }
 }
-template <class E, int D>
-EA_DEV void sstore_cols(const Staged<ColTile<E, D>::NCH>& st, char* lds, int tid) {
-    using L = ColTile<E, D>;
-#pragma unroll
-    for (int p = 0; p < L::NCH; ++p) {
-        const int c = p * THREADS + tid;
-        const int row = c / L::CHUNKS_PER_ROW, col = c % L::CHUNKS_PER_ROW;
-        *(u32x4*)(lds + row * L::LD_BYTES + col * 16) = st.r[p];
-    }
-}
+EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
 
 // ---- owned operand: rows of a row-major [.., D] matrix held in registers as MFMA B fragments --
 template <class E, int D, int QB> struct Owned { typename E::frag f[QB][D / E::KSTEP]; };
@@ -154,39 +152,61 @@ EA_DEV void load_owned(Owned<E, D, QB>& o, const typename E::elem* g, long row0,
     }
 }
 
-// ---- stage 1: C[kb][qb] = tile(64 x D, LDS row-major) . owned^T -----------------------------
+// ---- stage 1: C[kb][qb] = tile(64 x D, LDS row-major, swizzled) . owned^T -----------------------
 template <class E, int D, int QB>
 EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, QB>& own, int lane) {
     using L = RowTile<E, D>;
+    constexpr int ES = (int)sizeof(typename E::elem);
     const int m = lane & 31, h = lane >> 5;
-    const char* r0 = lds_tile + perm_row(m) * L::LD_BYTES + h * E::EPL * (int)sizeof(typename E::elem);
-    const char* r1 = r0 + 32 * L::LD_BYTES;
+    const int row = perm_row(m);
+    const int sw = swz<L::CPR>(row) * 16;        // swz(row + 32) == swz(row)
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) C[kb][qb][v] = 0.f;
+    if constexpr (E::EPL == 8) {
+        // lane half h takes chunk 2s+h of the row: byte (2s+h)*16 ^ sw = ((h*16) ^ sw) ^ (s*32)
+        const int lane_off = row * L::ROW_BYTES + ((h * 16) ^ sw);
 #pragma unroll
-    for (int s = 0; s < D / E::KSTEP; ++s) {
-        const int off = s * E::KSTEP * (int)sizeof(typename E::elem);
-        const typename E::frag a0 = *(const typename E::frag*)(r0 + off);
-        const typename E::frag a1 = *(const typename E::frag*)(r1 + off);
+        for (int s = 0; s < D / E::KSTEP; ++s) {
+            const char* a = lds_tile + (lane_off ^ (s * 32));
+            const typename E::frag a0 = *(const typename E::frag*)a;
+            const typename E::frag a1 = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            C[0][qb] = E::mma(a0, own.f[qb][s], C[0][qb]);
-            C[1][qb] = E::mma(a1, own.f[qb][s], C[1][qb]);
+            for (int qb = 0; qb < QB; ++qb) {
+                C[0][qb] = E::mma(a0, own.f[qb][s], C[0][qb]);
+                C[1][qb] = E::mma(a1, own.f[qb][s], C[1][qb]);
+            }
+        }
+    } else {
+        // one element 2s+h per lane: chunk s/2, word 2(s%2)+h inside it
+        const int lane_off = row * L::ROW_BYTES + sw + h * ES;
+#pragma unroll
+        for (int s = 0; s < D / E::KSTEP; ++s) {
+            const char* a = lds_tile + ((lane_off ^ ((s / 2) * 16)) + 2 * (s % 2) * ES);
+            const typename E::frag a0 = *(const typename E::frag*)a;
+            const typename E::frag a1 = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                C[0][qb] = E::mma(a0, own.f[qb][s], C[0][qb]);
+                C[1][qb] = E::mma(a1, own.f[qb][s], C[1][qb]);
+            }
         }
     }
 }
 
-// ---- stage 2: X[db][qb] += tileT(D x 64, LDS) . Y[kb][qb] -----------------------------------
+// ---- stage 2: X[db][qb] += tileT(D x 64, LDS, swizzled) . Y[kb][qb] ---------------------------
 template <class E2, int D, int QB>
 EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tileT, const f32x16 (&Y)[2][QB], int lane) {
     using L = ColTile<E2, D>;
+    constexpr int ES = (int)sizeof(typename E2::elem);
     const int m = lane & 31, h = lane >> 5;
-    const char* base = lds_tileT + m * L::LD_BYTES;
+    const int sw = swz<L::CPR>(m) * 16;          // swz(32 db + m) == swz(m)
     if constexpr (E2::EPL == 8) {
+        // 8 consecutive tile rows 32kb+16s2+8h.. = chunk 4kb+2s2+h of row 32db+m
+        const int lane_off = m * L::ROW_BYTES + ((h * 16) ^ sw);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -196,23 +216,26 @@ EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tileT, const f32x16 
                 for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                     for (int t = 0; t < 8; ++t) b[qb][t] = E2::from_float(Y[kb][qb][8 * s2 + t]);
-                const int coff = (32 * kb + 16 * s2 + 8 * h) * (int)sizeof(typename E2::elem);
+                const char* base = lds_tileT + (lane_off ^ ((4 * kb + 2 * s2) * 16));
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db) {
-                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::LD_BYTES + coff);
+                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::ROW_BYTES);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
                 }
             }
     } else {
+        // one tile row per step: element trow = 32kb+16(v/8)+8h+v%8 -> chunk 8kb+4(v/8)+2h+(v%8)/4
+        const int lane_off = m * L::ROW_BYTES + ((2 * h * 16) ^ sw);
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int coff = trow(kb, v, h) * (int)sizeof(typename E2::elem);
+                const int cc = 8 * kb + 4 * (v >> 3) + ((v & 7) >> 2);
+                const char* base = lds_tileT + ((lane_off ^ (cc * 16)) + (v & 3) * ES);
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db) {
-                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::LD_BYTES + coff);
+                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::ROW_BYTES);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) X[db][qb] = E2::mma(a, Y[kb][qb][v], X[db][qb]);
                 }
