@@ -16,8 +16,8 @@ constexpr int QB = 1;        // 32*QB owned rows per wave
 // waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
 constexpr int NW_TAU = 4, NBUF_TAU = 2;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
-constexpr int NW_DQ = 4, NBUF_DQ = 1;
-constexpr int NW_DKDV = 4, NBUF_DKDV = 1;
+constexpr int NW_DQ = 2, NBUF_DQ = 1;
+constexpr int NW_DKDV = 2, NBUF_DKDV = 1;
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
 
