@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 #include "bwd_kernels.hpp"
 #include "fwd_kernels.hpp"
 
@@ -56,10 +58,10 @@ void timer_begin_call() {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, delta, mask, wmask, tmax, total;
+    size_t stats, a, b, c, d, delta, mask, wmask, tmax, total;
 };
 
-// element size of the transposed copies
+// element size of the stage-2 copies
 inline size_t t_elem(ea_dtype t) { return t == EA_BF16 ? 2 : 4; }
 
 Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
@@ -67,7 +69,7 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
     L.stats = off; off += align256(EA_STATS_WORDS * 8);
-    L.a = off; off += align256(BH * N * d * t_elem(t));          // V^T
+    L.a = off; off += align256(BH * N * d * t_elem(t));          // V in the stage-2 type
     L.wmask = off; off += align256(BH * T * W * 4);
     L.tmax = off; off += align256(BH * T * (size_t)N * 2);       // per-row key-tile maxima, fp16
     L.total = off;
@@ -78,9 +80,10 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
     L.stats = off; off += align256(EA_STATS_WORDS * 8);
-    L.a = off; off += align256(BH * N * d * t_elem(t));          // K^T
-    L.b = off; off += align256(BH * N * d * t_elem(t));          // Q^T
-    L.c = off; off += align256(BH * N * d * t_elem(t));          // dO^T
+    L.a = off; off += align256(BH * N * d * t_elem(t));          // K, Q, V, dO in the stage-2 type
+    L.b = off; off += align256(BH * N * d * t_elem(t));
+    L.c = off; off += align256(BH * N * d * t_elem(t));
+    L.d = off; off += align256(BH * N * d * t_elem(t));
     L.delta = off; off += align256(BH * N * 4);
     L.mask = off; off += align256(BH * T * W * 4);               // rebuilt mask (mask == NULL)
     L.wmask = off; off += align256(BH * T * W * 4);
@@ -117,23 +120,27 @@ int launch(K kernel, dim3 grid, int threads, size_t smem, hipStream_t s, Params 
     return EA_OK;
 }
 
-template <class Ein, class Eout, int D>
-int launch_transpose(const void* in, void* out, int BH, int N, const unsigned int* amax_bits, hipStream_t s) {
-    hipLaunchKernelGGL((transpose_kernel<Ein, Eout, D>), dim3(N / 64, D / 64, BH), dim3(256), 0, s,
-                       (const typename Ein::elem*)in, (typename Eout::elem*)out, N, amax_bits);
+template <class Ein, class Eout>
+int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, hipStream_t s) {
+    hipLaunchKernelGGL((convert_kernel<Ein, Eout>), dim3(2048), dim3(256), 0, s, (const typename Ein::elem*)in,
+                       (typename Eout::elem*)out, n, amax_bits);
     EA_HIP(hipGetLastError());
     return EA_OK;
 }
 
-// E: input element type; E2F: stage-2 operand type of the forward (P, V^T); E2B: of the backward
-template <class E, class E2F, class E2B, int D, int AM>
+// E: input element type; E2: element type of every second-stage product and of the whole backward
+// (for bf16 inputs: fp16; the copies are made by convert_kernel)
+template <class E, class E2, int D, int AM>
 struct Ops {
+    static constexpr bool COPY = !std::is_same<E, E2>::value;
     static int fwd(Params p, hipStream_t s) {
         int rc;
         {
             ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
-            rc = launch_transpose<E, E2F, D>(p.V, (void*)p.Vt, p.BH, p.N, nullptr, s);
-            if (rc) return rc;
+            if (COPY) {
+                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr, s);
+                if (rc) return rc;
+            }
         }
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
@@ -142,72 +149,77 @@ struct Ops {
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
-        return launch(out_kernel<E, E2F, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
-                      OutSmem<E, E2F, D, QB, false, NW_OUT, NBUF_OUT>::BYTES, s, p);
+        return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
+                      OutSmem<E, E2, D, QB, false, NW_OUT, NBUF_OUT>::BYTES, s, p);
     }
     static dim3 groups(const Params& p, int nw) {
         const int rows = 32 * QB * nw;
         return dim3(p.BH * ((p.N + rows - 1) / rows));
     }
-    static int bwd(Params p, bool rebuild_mask, hipStream_t s) {
+    // `copies`: workspace room for K, Q, V, dO in E2 (used when COPY)
+    static int bwd(Params p, bool rebuild_mask, void* const copies[4], hipStream_t s) {
         int rc;
         if (rebuild_mask) {
             ScopedKernelTime t(EA_TIMER_MASK, s);
             hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
             EA_HIP(hipGetLastError());
-            rc = launch(out_kernel<E, E2F, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
-                        OutSmem<E, E2F, D, QB, true, NW_OUT, NBUF_OUT>::BYTES, s, p);
+            rc = launch(out_kernel<E, E2, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
+                        OutSmem<E, E2, D, QB, true, NW_OUT, NBUF_OUT>::BYTES, s, p);
             if (rc) return rc;
         }
-        const unsigned int* go_amax = nullptr;
         {
-        ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
-        if (E2B::SCALED) {
-            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
-                               (long)p.BH * p.N, p.scal, p.scal + 2);
-            EA_HIP(hipGetLastError());
-            hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.V,
-                               (long)p.BH * p.N, (unsigned int*)nullptr, p.scal + 3);
-            EA_HIP(hipGetLastError());
-            go_amax = p.scal;
-        }
-        if ((rc = launch_transpose<E, E2B, D>(p.K, (void*)p.Kt, p.BH, p.N, nullptr, s))) return rc;
-        if ((rc = launch_transpose<E, E2B, D>(p.Q, (void*)p.Qt, p.BH, p.N, nullptr, s))) return rc;
-        if ((rc = launch_transpose<E, E2B, D>(p.dO, (void*)p.dOt, p.BH, p.N, go_amax, s))) return rc;
+            ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
+            if (E2::SCALED) {
+                hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
+                                   (long)p.BH * p.N, p.scal, p.scal + 2);
+                EA_HIP(hipGetLastError());
+                hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.V,
+                                   (long)p.BH * p.N, (unsigned int*)nullptr, p.scal + 3);
+                EA_HIP(hipGetLastError());
+            }
+            if (COPY) {
+                const long n = (long)p.BH * p.N * D;
+                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, s))) return rc;
+                p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
+            }
         }
         {
             ScopedKernelTime t(EA_TIMER_DQ, s);
-            rc = launch(dq_kernel<E, E2B, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64,
-                        DqSmem<E, E2B, D, QB, NW_DQ, NBUF_DQ>::BYTES, s, p);
+            rc = launch(dq_kernel<E2, E2, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64,
+                        DqSmem<E2, E2, D, QB, NW_DQ, NBUF_DQ>::BYTES, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_DKDV, s);
-        return launch(dkdv_kernel<E, E2B, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64,
-                      DkdvSmem<E, E2B, D, QB, NW_DKDV, NBUF_DKDV>::BYTES, s, p);
+        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64,
+                      DkdvSmem<E2, E2, D, QB, NW_DKDV, NBUF_DKDV>::BYTES, s, p);
     }
 };
 
-template <class E, class E2F, class E2B, int D>
-int dispatch_alpha(bool is_bwd, Params p, bool rebuild, hipStream_t s) {
+template <class E, class E2, int D>
+int dispatch_alpha(bool is_bwd, Params p, bool rebuild, void* const copies[4], hipStream_t s) {
     switch (alpha_mode(p.alpha)) {
-        case ALPHA_15: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_15>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_15>::fwd(p, s);
-        case ALPHA_20: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_20>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_20>::fwd(p, s);
-        default: return is_bwd ? Ops<E, E2F, E2B, D, ALPHA_GEN>::bwd(p, rebuild, s) : Ops<E, E2F, E2B, D, ALPHA_GEN>::fwd(p, s);
+        case ALPHA_15: return is_bwd ? Ops<E, E2, D, ALPHA_15>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_15>::fwd(p, s);
+        case ALPHA_20: return is_bwd ? Ops<E, E2, D, ALPHA_20>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_20>::fwd(p, s);
+        default: return is_bwd ? Ops<E, E2, D, ALPHA_GEN>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_GEN>::fwd(p, s);
     }
 }
 
-int dispatch(bool is_bwd, ea_dtype t, int d, Params p, bool rebuild, hipStream_t s) {
-    // bf16 inputs: score-shaped products (Q K^T, dO V^T) on bf16 MFMA; the second-stage products
-    // (P V, dS K, P^T dO, dS^T Q) on fp16 MFMA: P lies in [0,1] and dS, dO are divided by known
-    // bounds first, so fp16's range suffices and its 3 extra mantissa bits keep the rounding of
-    // P and dS well inside the tolerances; bf16 values convert to fp16 exactly while
-    // 2^-14 <= |x| < 65504 (smaller ones within 2^-25 absolute).
+int dispatch(bool is_bwd, ea_dtype t, int d, Params p, bool rebuild, void* const copies[4], hipStream_t s) {
+    // bf16 inputs: the forward scores (Q K^T) run on bf16 MFMA straight from the inputs.  Every
+    // second-stage product (P V, dS K, P^T dO, dS^T Q) and the whole backward run on fp16 MFMA
+    // from fp16 copies: P lies in [0,1] and dS, dO are divided by known bounds first, so fp16's
+    // range suffices and its 3 extra mantissa bits keep the rounding of P and dS well inside the
+    // tolerances; bf16 values convert to fp16 exactly while 2^-17 <= |x| < 65504 (smaller ones
+    // within 2^-25 absolute; larger ones are outside this library's domain).
     if (t == EA_BF16) {
-        if (d == 64) return dispatch_alpha<Bf16, F16, F16, 64>(is_bwd, p, rebuild, s);
-        return dispatch_alpha<Bf16, F16, F16, 128>(is_bwd, p, rebuild, s);
+        if (d == 64) return dispatch_alpha<Bf16, F16, 64>(is_bwd, p, rebuild, copies, s);
+        return dispatch_alpha<Bf16, F16, 128>(is_bwd, p, rebuild, copies, s);
     }
-    if (d == 64) return dispatch_alpha<F32, F32, F32, 64>(is_bwd, p, rebuild, s);
-    return dispatch_alpha<F32, F32, F32, 128>(is_bwd, p, rebuild, s);
+    if (d == 64) return dispatch_alpha<F32, F32, 64>(is_bwd, p, rebuild, copies, s);
+    return dispatch_alpha<F32, F32, 128>(is_bwd, p, rebuild, copies, s);
 }
 
 Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int causal) {
@@ -251,13 +263,13 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.Q = Q; p.K = K; p.V = V;
     p.O = O; p.tau = tau; p.mask = block_mask; p.iters = iters;
     p.stats = (unsigned long long*)(ws + L.stats);
-    p.Vt = ws + L.a;
+    p.V2 = (t == EA_BF16) ? (const void*)(ws + L.a) : V;
     p.wmask = (int32_t*)(ws + L.wmask);
     p.tmax = (_Float16*)(ws + L.tmax);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
     timer_begin_call();
-    return dispatch(false, t, d, p, false, s);
+    return dispatch(false, t, d, p, false, nullptr, s);
 }
 
 int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
@@ -276,7 +288,7 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     p.O = const_cast<float*>((const float*)O);
     p.dQ = dQ; p.dK = dK; p.dV = dV;
     p.stats = (unsigned long long*)(ws + L.stats);
-    p.Kt = ws + L.a; p.Qt = ws + L.b; p.dOt = ws + L.c;
+    void* const copies[4] = {ws + L.a, ws + L.b, ws + L.c, ws + L.d};
     p.delta = (float*)(ws + L.delta);
     p.wmask = (int32_t*)(ws + L.wmask);
     const bool rebuild = (block_mask == nullptr);
@@ -285,7 +297,7 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, p.scal);
     EA_HIP(hipGetLastError());
     timer_begin_call();
-    return dispatch(true, t, d, p, rebuild, s);
+    return dispatch(true, t, d, p, rebuild, copies, s);
 }
 
 int entmax_attn_timer_enable(int on) {

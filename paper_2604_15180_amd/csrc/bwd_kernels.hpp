@@ -15,8 +15,7 @@ struct DqSmem {
     static constexpr int BR = 32 * QB * NW;
     static constexpr int MR = (BR + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
-    static constexpr int CBYTES = ColTile<E2, D>::BYTES;
-    static constexpr int SET = 2 * RBYTES + CBYTES;          // K, V, K^T tiles
+    static constexpr int SET = 2 * RBYTES;                   // K, V tiles
     static constexpr int BYTES = NBUF * SET + 4 * (MR * MAX_W + MAX_T + 4);
 };
 
@@ -27,7 +26,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     constexpr int BR = SM::BR, MR = SM::MR;
     constexpr int THREADS = NW * 64;
     extern __shared__ __align__(16) char smem[];
-    char* bufs = smem;                        // set s at bufs + s*SET: K tile, V tile, K^T tile
+    char* bufs = smem;                        // set s at bufs + s*SET: K tile, V tile
     uint32_t* fm = (uint32_t*)(smem + NBUF * SM::SET);
     int* tl = (int*)(fm + MR * MAX_W);
     int* tl_count = tl + MAX_T;
@@ -42,7 +41,6 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     const long hoff = (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + hoff;
     const elem* Vh = (const elem*)p.V + hoff;
-    const typename E2::elem* Kth = (const typename E2::elem*)p.Kt + hoff;
     const int myrow = (wave * 32 * QB) / 64;
     const float c = p.c, r = p.r;
 
@@ -67,9 +65,12 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     // |dP_rj| = |<dO_r, V_j>| <= max_r |dO_r| max_j |V_j| =: pb (row 2-norms from rownorm_kernel)
     // and |e| <= pb (O_r is a convex combination of V rows), so |U (dP - e)| <= 2 pb; with a
     // narrow-range stage-2 type U (dP - e) / (2 pb) feeds the MFMA.
-    float pb = 1.f, inv_pb = 1.f;
+    // (With a narrow-range type the whole backward runs on dO / max|dO|; amax undoes it at the end.)
+    float pb = 1.f, inv_pb = 1.f, amax = 1.f;
     if constexpr (E2::SCALED) {
-        pb = 2.f * __uint_as_float(p.scal[2]) * __uint_as_float(p.scal[3]);
+        amax = __uint_as_float(p.scal[0]);
+        if (!(amax > 0.f)) amax = 1.f;
+        pb = 2.f * (__uint_as_float(p.scal[2]) / amax) * __uint_as_float(p.scal[3]);
         inv_pb = pb > 0.f ? 1.f / pb : 0.f;
     }
     float ctr[QB];
@@ -105,14 +106,12 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
             char* b = bufs + set * SM::SET;
             issue_rows<E, D, NW>(b, Kh, j * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Vh, j * 64, wave, lane);
-            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES, Kth, N, j * 64, wave, lane);
         },
         [&](int it, int set) {
             const int j = tl[it];
             if (!mask_bit(fm, W, myrow, j)) return;
             const char* kbuf = bufs + set * SM::SET;
             const char* vbuf = kbuf + SM::RBYTES;
-            const char* ktbuf = kbuf + 2 * SM::RBYTES;
             stage1<E, D, QB>(S, kbuf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
             stage1<E, D, QB>(dP, vbuf, gf, lane);
@@ -134,8 +133,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
                         S[kb][qb][v] = t * inv_pb;
                         dP[kb][qb][v] = u;
                     }
-            stage2<E2, D, QB>(XA, ktbuf, S, lane);
-            stage2<E2, D, QB>(XB, ktbuf, dP, lane);
+            stage2<E2, D, QB>(XA, kbuf, S, lane);
+            stage2<E2, D, QB>(XB, kbuf, dP, lane);
         });
 
     // delta, and the bound max|U (dP - e)| + |delta - e| >= |dS| published for the dK/dV kernel
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
         const float drel = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;      // delta - e
         if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = drel + ctr[qb];
         bm = fmaxf(bm, xhalf_max(gmax[qb]) + fabsf(drel));
-        const float sa = pb * p.inv_sqrt_d, sb = drel * p.inv_sqrt_d;
+        const float sa = pb * p.inv_sqrt_d * amax, sb = drel * p.inv_sqrt_d * amax;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -165,8 +164,7 @@ struct DkdvSmem {
     static constexpr int BC = 32 * QB * NW;
     static constexpr int MC = (BC + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
-    static constexpr int CBYTES = ColTile<E2, D>::BYTES;
-    static constexpr int SET = 2 * RBYTES + 2 * CBYTES + 4 * 2 * TILE;   // Q, dO, Q^T, dO^T tiles, tau, delta
+    static constexpr int SET = 2 * RBYTES + 4 * 2 * TILE;    // Q, dO tiles, tau, delta
     static constexpr int BYTES = NBUF * SET + 4 * (MAX_T + 16);
 };
 
@@ -178,7 +176,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     constexpr int THREADS = NW * 64;
     static_assert(NW >= 2, "tau and delta rows are fetched by waves 0 and 1");
     extern __shared__ __align__(16) char smem[];
-    char* bufs = smem;                       // set s: Q tile, dO tile, Q^T tile, dO^T tile, tau[64], delta[64]
+    char* bufs = smem;                       // set s: Q tile, dO tile, tau[64], delta[64]
     int* tl = (int*)(smem + NBUF * SM::SET); // entries: query tile | column flags << 16
     int* wcnt = tl + MAX_T;                  // per-wave counts, [8] = running total
 
@@ -193,9 +191,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     const long hoff = (long)bh * N * D;
     const elem* Qh = (const elem*)p.Q + hoff;
     const elem* Gh = (const elem*)p.dO + hoff;
-    const typename E2::elem* Qth = (const typename E2::elem*)p.Qt + hoff;
-    const typename E2::elem* Gth = (const typename E2::elem*)p.dOt + hoff;
-    // dO^T was stored divided by max|dO|, and dS is divided by the dq kernel's largest bound
+    // dO is used divided by max|dO| throughout, and dS is divided by the dq kernel's largest bound
     float go_amax = 1.f, ds_bound = 1.f, ds_inv = 1.f;
     if constexpr (E2::SCALED) {
         go_amax = __uint_as_float(p.scal[0]);
@@ -254,7 +250,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile_done = 0;
-    constexpr int VEC_OFF = 2 * SM::RBYTES + 2 * SM::CBYTES;
+    constexpr int VEC_OFF = 2 * SM::RBYTES;
     stream_tiles<NBUF>(
         ntl,
         [&](int it, int set) {
@@ -262,8 +258,6 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
             char* b = bufs + set * SM::SET;
             issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
-            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES, Qth, N, i * 64, wave, lane);
-            issue_cols<E2, D, NW>(b + 2 * SM::RBYTES + SM::CBYTES, Gth, N, i * 64, wave, lane);
             // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
             if (wave == 0) load4_to_lds(p.tau + (long)bh * N + i * 64 + lane, b + VEC_OFF);
             if (wave == 1) load4_to_lds(p.delta + (long)bh * N + i * 64 + lane, b + VEC_OFF + 4 * TILE);
@@ -274,8 +268,6 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
             if (!((ent >> (16 + mycol)) & 1)) return;
             const char* qbuf = bufs + set * SM::SET;
             const char* gbuf = qbuf + SM::RBYTES;
-            const char* qtbuf = qbuf + 2 * SM::RBYTES;
-            const char* gtbuf = qtbuf + SM::CBYTES;
             const float* tau_s = (const float*)(qbuf + VEC_OFF);
             const float* del_s = tau_s + TILE;
             stage1<E, D, QB>(S, qbuf, kf, lane);
@@ -299,12 +291,12 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
                         dP[kb][qb][v] = u * fmaf(dP[kb][qb][v], ds_inv, -dq);
                     }
                 }
-            stage2<E2, D, QB>(XV, gtbuf, S, lane);
-            stage2<E2, D, QB>(XK, qtbuf, dP, lane);
+            stage2<E2, D, QB>(XV, gbuf, S, lane);
+            stage2<E2, D, QB>(XK, qbuf, dP, lane);
         });
     if (active) {
         store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
-        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, ds_bound * p.inv_sqrt_d, lane);
+        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, ds_bound * p.inv_sqrt_d * go_amax, lane);
     }
     if (lane == 0) atomicAdd(&p.stats[4], ntile_done * QB);
 }

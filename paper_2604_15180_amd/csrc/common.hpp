@@ -11,7 +11,7 @@ constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 
 struct Params {
     const void* Q; const void* K; const void* V; const void* dO;
-    const void* Kt; const void* Vt; const void* Qt; const void* dOt;   // transposed copies [BH][d][N]
+    const void* V2;       // forward: V in the stage-2 element type (fp16 copy for bf16 inputs)
     float* O;             // forward: output; backward: the forward's output (nullable)
     float* tau; float* delta;
     float* dQ; float* dK; float* dV;
@@ -21,8 +21,8 @@ struct Params {
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
-    // scal[0] = max |dO|, scal[1] = max over rows of the bound on |dS| (see dq_kernel),
-    // scal[2] = max row 2-norm of dO, scal[3] = max row 2-norm of V
+    // scal[0] = max |dO| (dO is used divided by it), scal[1] = max over rows of the bound on |dS|
+    // (see dq_kernel), scal[2] = max row 2-norm of dO, scal[3] = max row 2-norm of V
     unsigned int* scal;
     int BH, N, T, W;
     int causal;

@@ -4,7 +4,7 @@
 //                refinement to convergence + working block mask at tau_0)
 //   out_kernel : Phase 4 (O = P V over the working mask) + the exported mask at the final tau
 // One work-group = 128*QB query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
-// B operands in registers; 64-key tiles of K (and V^T) stream through LDS.
+// B operands in registers; 64-key tiles of K (and V) stream through LDS.
 #pragma once
 #include "common.hpp"
 
@@ -328,7 +328,7 @@ struct OutSmem {
     static constexpr int BR = 32 * QB * NW;
     static constexpr int MR = (BR + 63) / 64;
     static constexpr int KBYTES = RowTile<E, D>::BYTES;
-    static constexpr int VBYTES = MASK_ONLY ? 0 : ColTile<E2, D>::BYTES;
+    static constexpr int VBYTES = MASK_ONLY ? 0 : RowTile<E2, D>::BYTES;
     static constexpr int SET = KBYTES + VBYTES;              // one buffer set
     static constexpr int BYTES = NBUF * SET + 4 * (2 * MR * MAX_W + MAX_T + 4);
 };
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     constexpr int BR = SM::BR, MR = SM::MR;
     constexpr int THREADS = NW * 64;
     extern __shared__ __align__(16) char smem[];
-    char* kbuf = smem;                       // set s: K tile at kbuf + s*SET, V^T tile right after it
+    char* kbuf = smem;                       // set s: K tile at kbuf + s*SET, V tile right after it
     uint32_t* wm = (uint32_t*)(smem + NBUF * SM::SET);
     uint32_t* fm = wm + MR * MAX_W;
     int* tl = (int*)(fm + MR * MAX_W);
@@ -357,7 +357,8 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     const bool active = qw0 < N;
     const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + (long)bh * N * D;
-    const typename E2::elem* Vth = MASK_ONLY ? nullptr : (const typename E2::elem*)p.Vt + (long)bh * N * D;
+    // V in the stage-2 element type (for bf16 inputs: the fp16 copy made by convert_kernel)
+    const typename E2::elem* Vh = MASK_ONLY ? nullptr : (const typename E2::elem*)p.V2 + (long)bh * N * D;
     const int myrow = (wave * 32 * QB) / 64;
     const float c = p.c, r = p.r;
 
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
         [&](int it, int set) {
             const long j = tl[it];
             issue_rows<E, D, NW>(kbuf + set * SM::SET, Kh, j * 64, wave, lane);
-            if constexpr (!MASK_ONLY) issue_cols<E2, D, NW>(kbuf + set * SM::SET + SM::KBYTES, Vth, N, j * 64, wave, lane);
+            if constexpr (!MASK_ONLY) issue_rows<E2, D, NW>(kbuf + set * SM::SET + SM::KBYTES, Vh, j * 64, wave, lane);
         },
         [&](int it, int set) {
             const int j = tl[it];
@@ -439,28 +440,18 @@ __global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, int causa
     }
 }
 
-// [BH][N][D] (elements of Ein) -> [BH][D][N] (elements of Eout), through a 64x64 LDS tile.
-// `amax_bits` (nullable): bits of a float a >= 0; the copy is divided by a when a > 0.
-template <class Ein, class Eout, int D>
-__global__ __launch_bounds__(256) void transpose_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
-                                                            const unsigned int* amax_bits) {
-    __shared__ float tile[64][65];
+// Element-wise copy into another element type, optionally divided by a (bits of a float a >= 0).
+template <class Ein, class Eout>
+__global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* in, typename Eout::elem* out, long n,
+                                                      const unsigned int* amax_bits) {
     float mul = 1.f;
     if (amax_bits) {
         const float a = __uint_as_float(*amax_bits);
         if (a > 0.f) mul = 1.f / a;
     }
-    const int bh = blockIdx.z, r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const typename Ein::elem* src = in + (long)bh * N * D;
-    typename Eout::elem* dst = out + (long)bh * N * D;
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int rr = i / 64, cc = i % 64;
-        tile[rr][cc] = (float)src[(long)(r0 + rr) * D + c0 + cc];
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-        const int cc = i / 64, rr = i % 64;
-        dst[(long)(c0 + cc) * N + r0 + rr] = Eout::from_float(tile[rr][cc] * mul);
+    for (long i = (blockIdx.x * 256L + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[i + e] = Eout::from_float((float)in[i + e] * mul);
     }
 }
 

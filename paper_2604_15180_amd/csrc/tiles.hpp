@@ -4,17 +4,17 @@
 // Shapes.  A work-group streams 64-row tiles (keys in the forward and in the dQ kernel, queries
 // in the dK/dV kernel) through LDS; each wave owns 32*QB rows of the other operand in registers.
 //   stage 1:  C[kb][qb] = tile rows (32 kb ..) x owned rows (32 qb ..)        (contraction over d)
-//   stage 2:  X[db][qb] += tileT rows (32 db ..) x Y[kb][qb]                   (contraction over the
-//             64 tile rows), where tileT is the d x 64 transposed tile and Y is a stage-1 shaped
-//             result.  This is O^T += V^T P^T, dQ^T += K^T dS^T, dV^T += dO^T P, dK^T += Q^T dS.
+//   stage 2:  X[db][qb] += tile^T rows (32 db ..) x Y[kb][qb]                  (contraction over the
+//             64 tile rows), where Y is a stage-1 shaped result.  This is O^T += V^T P^T,
+//             dQ^T += K^T dS^T, dV^T += dO^T P, dK^T += Q^T dS.  The tile stays row-major in LDS;
+//             its transposed MFMA fragments come from the LDS transpose read ds_read_b64_tr_b16.
 // In the 32x32 accumulator layout lane (n, h) (n = lane % 32, h = lane / 32) holds output column n,
 // so every owned row lives in two lanes and row reductions are in-lane plus one 32-lane exchange.
 //
 // Row permutation.  MFMA output register v of lane half h is output row 8(v/4)+4h+v%4.  Stage 1
 // feeds tile row perm(m) into MFMA row m so that register v of half h is tile row
 // 16(v/8)+8h+v%8: the eight registers 8s..8s+7 are then exactly the eight consecutive contraction
-// slots that lane half h supplies to a K=16 MFMA of stage 2, and the matching tileT operand is one
-// 16-byte LDS read.
+// slots that lane half h supplies to a K=16 MFMA of stage 2.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -91,12 +91,6 @@ template <class E, int D> struct RowTile {      // 64 rows x D elements, row-maj
     static constexpr int CPR = ROW_BYTES / 16;
     static constexpr int NINST = BYTES / 1024;   // wave-wide load instructions per tile
 };
-template <class E, int D> struct ColTile {      // D rows x 64 elements (the transposed tile)
-    static constexpr int ROW_BYTES = TILE * (int)sizeof(typename E::elem);
-    static constexpr int BYTES = D * ROW_BYTES;
-    static constexpr int CPR = ROW_BYTES / 16;
-    static constexpr int NINST = BYTES / 1024;
-};
 
 EA_DEV void load16_to_lds(const void* g, char* lds_wave_base) {
     // LDS address = wave-uniform base + lane * 16 (the instruction offset stays 0: it would be
@@ -121,18 +115,6 @@ EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave
         const int t = i * NW + wave;              // wave is wave-uniform (an SGPR)
         const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
         load16_to_lds(base + row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16), lds + t * 1024);
-    }
-}
-// columns col0..col0+63 of the transposed copy [D][N] -> LDS tile
-template <class E, int D, int NW>
-EA_DEV void issue_cols(char* lds, const typename E::elem* gT, long N, long col0, int wave, int lane) {
-    using L = ColTile<E, D>;
-    static_assert(L::NINST % NW == 0, "loads must divide evenly over the waves");
-#pragma unroll
-    for (int i = 0; i < L::NINST / NW; ++i) {
-        const int t = i * NW + wave;
-        const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
-        load16_to_lds((const char*)(gT + (long)row * N + col0) + ((pos ^ swz<L::CPR>(row)) * 16), lds + t * 1024);
     }
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
@@ -197,16 +179,27 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
     }
 }
 
-// ---- stage 2: X[db][qb] += tileT(D x 64, LDS, swizzled) . Y[kb][qb] ---------------------------
+// ---- stage 2: X[db][qb] += tile^T . Y[kb][qb], tile = 64 x D row-major in LDS (swizzled) ------
+// 16-bit types: ds_read_b64_tr_b16 works on groups of 16 lanes.  Lane r of a group passes the
+// address of four consecutive 16-bit elements ("row r" of a 16x4 block M); lane i receives
+// M[i/4][i%4], M[4+i/4][i%4], M[8+i/4][i%4], M[12+i/4][i%4].  Group g = lane/16 serves MFMA rows
+// m = 16(g%2)..+15 (tile columns 32db+m) of lane half h = g/2, whose contraction slots t = 0..7
+// are tile rows R+t, R = 32kb+16s2+8h.  Lane r = 4e+q passes &tile[R+e][32db+16(g%2)+4q], so lane
+// i receives tile[R+0..3][32db+m]: slots 0..3.  A second read from rows R+4.. gives slots 4..7.
 template <class E2, int D, int QB>
-EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tileT, const f32x16 (&Y)[2][QB], int lane) {
-    using L = ColTile<E2, D>;
+EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tile, const f32x16 (&Y)[2][QB], int lane) {
+    using L = RowTile<E2, D>;
     constexpr int ES = (int)sizeof(typename E2::elem);
-    const int m = lane & 31, h = lane >> 5;
-    const int sw = swz<L::CPR>(m) * 16;          // swz(32 db + m) == swz(m)
     if constexpr (E2::EPL == 8) {
-        // 8 consecutive tile rows 32kb+16s2+8h.. = chunk 4kb+2s2+h of row 32db+m
-        const int lane_off = m * L::ROW_BYTES + ((h * 16) ^ sw);
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const int g = lane >> 4, i = lane & 15, e = i >> 2, q = i & 3, h = g >> 1;
+        const int r_lo = 8 * h + e, r_hi = r_lo + 4;             // rows within the 16-row step
+        const int cc = 2 * (g & 1) + (q >> 1);                     // 16-byte chunk within the 32-column block
+        // byte offsets inside the step's first row block; the chunk index is XORed with swz(row),
+        // and 4*db chunks / 16*(2kb+s2) rows are added per step (both commute with the XOR)
+        const int off_lo = r_lo * L::ROW_BYTES + ((cc ^ swz<L::CPR>(r_lo)) * 16) + (q & 1) * 8;
+        const int off_hi = r_hi * L::ROW_BYTES + ((cc ^ swz<L::CPR>(r_hi)) * 16) + (q & 1) * 8;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -216,26 +209,34 @@ EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tileT, const f32x16 
                 for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
                     for (int t = 0; t < 8; ++t) b[qb][t] = E2::from_float(Y[kb][qb][8 * s2 + t]);
-                const char* base = lds_tileT + (lane_off ^ ((4 * kb + 2 * s2) * 16));
+                const char* rows = lds_tile + (32 * kb + 16 * s2) * L::ROW_BYTES;
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db) {
-                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::ROW_BYTES);
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4*)(rows + (off_lo ^ (db * 64))));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4*)(rows + (off_hi ^ (db * 64))));
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const typename E2::frag a = __builtin_bit_cast(typename E2::frag, both);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
                 }
             }
     } else {
-        // one tile row per step: element trow = 32kb+16(v/8)+8h+v%8 -> chunk 8kb+4(v/8)+2h+(v%8)/4
-        const int lane_off = m * L::ROW_BYTES + ((2 * h * 16) ^ sw);
+        // K=2 MFMA: one tile row per lane half and step, MFMA row m = tile column 32db+m: a plain
+        // 4-byte read of tile[trow][32db+m]
+        const int m = lane & 31, h = lane >> 5;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int cc = 8 * kb + 4 * (v >> 3) + ((v & 7) >> 2);
-                const char* base = lds_tileT + ((lane_off ^ (cc * 16)) + (v & 3) * ES);
+                const int row = trow(kb, v, h);
+                const char* rbase = lds_tile + row * L::ROW_BYTES + (m & 3) * ES;
+                const int sw = swz<L::CPR>(row);
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db) {
-                    const typename E2::frag a = *(const typename E2::frag*)(base + db * 32 * L::ROW_BYTES);
+                    const int chunk = (32 * db + m) / 4;
+                    const typename E2::frag a = *(const typename E2::frag*)(rbase + ((chunk ^ sw) * 16));
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) X[db][qb] = E2::mma(a, Y[kb][qb][v], X[db][qb]);
                 }
