@@ -18,7 +18,7 @@ constexpr int QB = 1;        // 32*QB owned rows per wave
 // waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
 constexpr int NW_TAU = 4, NBUF_TAU = 2;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
-constexpr int NW_DQ = 2, NBUF_DQ = 1;
+constexpr int NW_DQ = 2, NBUF_DQ = 2;
 constexpr int NW_DKDV = 2, NBUF_DKDV = 1;
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
@@ -112,10 +112,8 @@ int alpha_mode(float alpha) {
     } while (0)
 
 template <class K>
-int launch(K kernel, dim3 grid, int threads, size_t smem, hipStream_t s, Params p) {
-    // kernels above 64 KiB of dynamic LDS need the limit raised (cheap, idempotent)
-    EA_HIP(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, s, p);
+int launch(K kernel, dim3 grid, int threads, hipStream_t s, Params p) {
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), 0, s, p);   // all LDS is static
     EA_HIP(hipGetLastError());
     return EA_OK;
 }
@@ -144,13 +142,11 @@ struct Ops {
         }
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
-            rc = launch(tau_kernel<E, D, QB, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64,
-                        TauSmem<E, D, QB, NBINS, NW_TAU, NBUF_TAU>::BYTES, s, p);
+            rc = launch(tau_kernel<E, D, QB, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
-        return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
-                      OutSmem<E, E2, D, QB, false, NW_OUT, NBUF_OUT>::BYTES, s, p);
+        return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
     }
     static dim3 groups(const Params& p, int nw) {
         const int rows = 32 * QB * nw;
@@ -163,8 +159,7 @@ struct Ops {
             ScopedKernelTime t(EA_TIMER_MASK, s);
             hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
             EA_HIP(hipGetLastError());
-            rc = launch(out_kernel<E, E2, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64,
-                        OutSmem<E, E2, D, QB, true, NW_OUT, NBUF_OUT>::BYTES, s, p);
+            rc = launch(out_kernel<E, E2, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
             if (rc) return rc;
         }
         {
@@ -188,13 +183,11 @@ struct Ops {
         }
         {
             ScopedKernelTime t(EA_TIMER_DQ, s);
-            rc = launch(dq_kernel<E2, E2, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64,
-                        DqSmem<E2, E2, D, QB, NW_DQ, NBUF_DQ>::BYTES, s, p);
+            rc = launch(dq_kernel<E2, E2, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_DKDV, s);
-        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64,
-                      DkdvSmem<E2, E2, D, QB, NW_DKDV, NBUF_DKDV>::BYTES, s, p);
+        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
     }
 };
 

@@ -16,7 +16,6 @@ struct DqSmem {
     static constexpr int MR = (BR + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
     static constexpr int SET = 2 * RBYTES;                   // K, V tiles
-    static constexpr int BYTES = NBUF * SET + 4 * (MR * MAX_W + MAX_T + 4);
 };
 
 template <class E, class E2, int D, int QB, int AM, int NW, int NBUF>
@@ -25,11 +24,12 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
     constexpr int THREADS = NW * 64;
-    extern __shared__ __align__(16) char smem[];
-    char* bufs = smem;                        // set s at bufs + s*SET: K tile, V tile
-    uint32_t* fm = (uint32_t*)(smem + NBUF * SM::SET);
-    int* tl = (int*)(fm + MR * MAX_W);
-    int* tl_count = tl + MAX_T;
+    // buffer sets (K tile, V tile) as separate variables (see stream_tiles); all LDS is static
+    __shared__ __align__(1024) char set0[SM::SET];
+    __shared__ __align__(1024) char set1[NBUF == 2 ? SM::SET : 1024];
+    __shared__ uint32_t fm[MR * MAX_W];
+    __shared__ int tl[MAX_T];
+    __shared__ int tl_count[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -100,17 +100,15 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
     stream_tiles<NBUF>(
-        *tl_count,
-        [&](int it, int set) {
+        *tl_count, set0, NBUF == 2 ? set1 : set0,
+        [&](int it, char* b) {
             const long j = tl[it];
-            char* b = bufs + set * SM::SET;
             issue_rows<E, D, NW>(b, Kh, j * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Vh, j * 64, wave, lane);
         },
-        [&](int it, int set) {
+        [&](int it, const char* kbuf) {
             const int j = tl[it];
             if (!mask_bit(fm, W, myrow, j)) return;
-            const char* kbuf = bufs + set * SM::SET;
             const char* vbuf = kbuf + SM::RBYTES;
             stage1<E, D, QB>(S, kbuf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
@@ -165,7 +163,6 @@ struct DkdvSmem {
     static constexpr int MC = (BC + 63) / 64;
     static constexpr int RBYTES = RowTile<E, D>::BYTES;
     static constexpr int SET = 2 * RBYTES + 4 * 2 * TILE;    // Q, dO tiles, tau, delta
-    static constexpr int BYTES = NBUF * SET + 4 * (MAX_T + 16);
 };
 
 template <class E, class E2, int D, int QB, int AM, int NW, int NBUF>
@@ -175,10 +172,11 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     constexpr int BC = SM::BC, MC = SM::MC;
     constexpr int THREADS = NW * 64;
     static_assert(NW >= 2, "tau and delta rows are fetched by waves 0 and 1");
-    extern __shared__ __align__(16) char smem[];
-    char* bufs = smem;                       // set s: Q tile, dO tile, tau[64], delta[64]
-    int* tl = (int*)(smem + NBUF * SM::SET); // entries: query tile | column flags << 16
-    int* wcnt = tl + MAX_T;                  // per-wave counts, [8] = running total
+    // buffer sets (Q tile, dO tile, tau[64], delta[64]) as separate variables (see stream_tiles)
+    __shared__ __align__(1024) char set0[SM::SET];
+    __shared__ __align__(1024) char set1[NBUF == 2 ? SM::SET : 1024];
+    __shared__ int tl[MAX_T];                // entries: query tile | column flags << 16
+    __shared__ int wcnt[16];                 // per-wave counts, [8] = running total
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -252,21 +250,19 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     unsigned long long ntile_done = 0;
     constexpr int VEC_OFF = 2 * SM::RBYTES;
     stream_tiles<NBUF>(
-        ntl,
-        [&](int it, int set) {
+        ntl, set0, NBUF == 2 ? set1 : set0,
+        [&](int it, char* b) {
             const long i = tl[it] & 0xffff;
-            char* b = bufs + set * SM::SET;
             issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
             // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
             if (wave == 0) load4_to_lds(p.tau + (long)bh * N + i * 64 + lane, b + VEC_OFF);
             if (wave == 1) load4_to_lds(p.delta + (long)bh * N + i * 64 + lane, b + VEC_OFF + 4 * TILE);
         },
-        [&](int it, int set) {
+        [&](int it, const char* qbuf) {
             const int ent = tl[it];
             const long i = ent & 0xffff;
             if (!((ent >> (16 + mycol)) & 1)) return;
-            const char* qbuf = bufs + set * SM::SET;
             const char* gbuf = qbuf + SM::RBYTES;
             const float* tau_s = (const float*)(qbuf + VEC_OFF);
             const float* del_s = tau_s + TILE;

@@ -64,27 +64,35 @@ template <int AM> EA_DEV float pow_r2(float y, float r) {
     else return __builtin_amdgcn_exp2f((r - 2.f) * __builtin_amdgcn_logf(y));
 }
 
-// Walk over `ntiles` streamed tiles.  issue(it, set) starts the direct global->LDS loads of tile
-// `it` into buffer set `set`; compute(it, set) does the math on it.
-// NBUF == 2: the loads of tile it+1 fly under the math of tile it, one barrier per tile.
+// Walk over `ntiles` streamed tiles.  issue(it, buf) starts the direct global->LDS loads of tile
+// `it` into the buffer set at `buf`; compute(it, buf) does the math on it.
+// NBUF == 2: the loads of tile it+1 fly under the math of tile it, one barrier per tile.  The two
+// buffer sets must be two distinct __shared__ variables: the compiler gives each LDS variable its
+// own alias scope, and only then does it refrain from making every LDS read of the tile being
+// worked on wait for the loads in flight into the other set.
 // NBUF == 1: half the LDS; loads and math alternate (other work-groups on the CU fill the gaps).
 template <int NBUF, class IssueF, class ComputeF>
-EA_DEV void stream_tiles(int ntiles, IssueF issue, ComputeF compute) {
+EA_DEV void stream_tiles(int ntiles, char* buf0, char* buf1, IssueF issue, ComputeF compute) {
     if constexpr (NBUF == 2) {
-        if (ntiles > 0) issue(0, 0);
-        for (int it = 0; it < ntiles; ++it) {
+        if (ntiles > 0) issue(0, buf0);
+        for (int it = 0; it < ntiles; it += 2) {
             wait_loads();
             __syncthreads();     // tile `it` has landed for every wave; everyone is done with tile it-1
-            if (it + 1 < ntiles) issue(it + 1, (it + 1) & 1);
-            compute(it, it & 1);
+            if (it + 1 < ntiles) issue(it + 1, buf1);
+            compute(it, buf0);
+            if (it + 1 >= ntiles) break;
+            wait_loads();
+            __syncthreads();
+            if (it + 2 < ntiles) issue(it + 2, buf0);
+            compute(it + 1, buf1);
         }
         __syncthreads();
     } else {
         for (int it = 0; it < ntiles; ++it) {
-            issue(it, 0);
+            issue(it, buf0);
             wait_loads();
             __syncthreads();
-            compute(it, 0);
+            compute(it, buf0);
             __syncthreads();
         }
     }

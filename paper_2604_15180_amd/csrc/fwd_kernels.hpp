@@ -72,10 +72,7 @@ template <class E, int D, int QB, int NB, int NW, int NBUF>
 struct TauSmem {
     static constexpr int BR = 32 * QB * NW;
     static constexpr int MR = (BR + 63) / 64;
-    static constexpr int KBYTES = NBUF * RowTile<E, D>::BYTES;
     static constexpr int HIST_WORDS = BR * (NB + 1);
-    // floats: base, thr, lo, hi, F, G, Hs per row; ints: done, iters per row
-    static constexpr int BYTES = KBYTES + 4 * (HIST_WORDS + 7 * BR + 2 * BR + 2 * MR * MAX_W + MAX_T + 4);
 };
 
 template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
@@ -85,22 +82,16 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     constexpr int THREADS = NW * 64;
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
-    extern __shared__ __align__(16) char smem[];
-    char* kbuf = smem;
-    uint32_t* hist = (uint32_t*)(smem + SM::KBYTES);
-    float* rs_base = (float*)(hist + SM::HIST_WORDS);
-    float* rs_thr = rs_base + BR;
-    float* rs_lo = rs_thr + BR;
-    float* rs_hi = rs_lo + BR;
-    float* rs_F = rs_hi + BR;
-    float* rs_G = rs_F + BR;
-    float* rs_H = rs_G + BR;
-    int* rs_done = (int*)(rs_H + BR);
-    int* rs_iters = rs_done + BR;
-    uint32_t* wm = (uint32_t*)(rs_iters + BR);
-    uint32_t* cand = wm + MR * MAX_W;
-    int* tl = (int*)(cand + MR * MAX_W);
-    int* tl_count = tl + MAX_T;
+    // All LDS is static, and the two K buffers are separate variables (see stream_tiles).
+    __shared__ __align__(1024) char kbuf[KT::BYTES];
+    __shared__ __align__(1024) char kbuf_b[NBUF == 2 ? KT::BYTES : 1024];
+    __shared__ uint32_t hist[SM::HIST_WORDS];
+    __shared__ float rs_base[BR], rs_thr[BR], rs_lo[BR], rs_hi[BR], rs_F[BR], rs_G[BR], rs_H[BR];
+    __shared__ int rs_done[BR], rs_iters[BR];
+    __shared__ uint32_t wm[MR * MAX_W];
+    __shared__ uint32_t cand[MR * MAX_W];
+    __shared__ int tl[MAX_T];
+    __shared__ int tl_count[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -124,9 +115,10 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
 
     f32x16 C[2][QB];
     unsigned long long ntile_done = 0;
-    auto issue_seq = [&](int it, int set) { issue_rows<E, D, NW>(kbuf + set * KT::BYTES, Kh, (long)it * 64, wave, lane); };
-    auto scores = [&](int j, int set) {
-        stage1<E, D, QB>(C, kbuf + set * KT::BYTES, qf, lane);
+    char* const kbuf1 = NBUF == 2 ? kbuf_b : kbuf;
+    auto issue_seq = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); };
+    auto scores = [&](int j, const char* buf) {
+        stage1<E, D, QB>(C, buf, qf, lane);
         if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
         ++ntile_done;
     };
@@ -138,9 +130,9 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     // Besides the running maximum, every (row, key tile) maximum goes to HBM (fp16, rounded up):
     // once the row maxima are final, only tiles holding a score within 1 of its row's maximum
     // (in (alpha-1) s units, Eq. 5-6) can matter to the histogram, to f, or to P.
-    stream_tiles<NBUF>(njt, issue_seq, [&](int j, int set) {
+    stream_tiles<NBUF>(njt, kbuf, kbuf1, issue_seq, [&](int j, const char* buf) {
         if (j >= wjt) return;
-        scores(j, set);
+        scores(j, buf);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float lm = -INFINITY;
@@ -178,13 +170,13 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     }
     __syncthreads();
     build_tile_list(cand, MR, W, tl, tl_count, tid);
-    auto issue_list = [&](int it, int set) { issue_rows<E, D, NW>(kbuf + set * KT::BYTES, Kh, (long)tl[it] * 64, wave, lane); };
+    auto issue_list = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
 
     // ---- Phase 2: per-row histogram of the centred scores in LDS (Eq. 7-8) ---------------
-    stream_tiles<NBUF>(*tl_count, issue_list, [&](int it, int set) {
+    stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) {
         const int j = tl[it];
         if (!mask_bit(cand, W, myrow, j)) return;
-        scores(j, set);
+        scores(j, buf);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float lmax = -INFINITY;
@@ -229,9 +221,9 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             cnt[qb] = 0;
         }
         const bool first = (sweep == 0);
-        auto body = [&](int j, int set) {
+        auto body = [&](int j, const char* buf) {
             if (!mask_bit(first ? cand : wm, W, myrow, j)) return;
-            scores(j, set);
+            scores(j, buf);
             bool hit = false;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
@@ -268,7 +260,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             }
             if (first && hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
         };
-        stream_tiles<NBUF>(*tl_count, issue_list, [&](int it, int set) { body(tl[it], set); });
+        stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) { body(tl[it], buf); });
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
@@ -329,8 +321,7 @@ struct OutSmem {
     static constexpr int MR = (BR + 63) / 64;
     static constexpr int KBYTES = RowTile<E, D>::BYTES;
     static constexpr int VBYTES = MASK_ONLY ? 0 : RowTile<E2, D>::BYTES;
-    static constexpr int SET = KBYTES + VBYTES;              // one buffer set
-    static constexpr int BYTES = NBUF * SET + 4 * (2 * MR * MAX_W + MAX_T + 4);
+    static constexpr int SET = KBYTES + VBYTES;              // one buffer set (static LDS)
 };
 
 // Phase 4.  MASK_ONLY: no V, no O - only the mask at the given tau (used by the backward when
@@ -341,12 +332,13 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     using elem = typename E::elem;
     constexpr int BR = SM::BR, MR = SM::MR;
     constexpr int THREADS = NW * 64;
-    extern __shared__ __align__(16) char smem[];
-    char* kbuf = smem;                       // set s: K tile at kbuf + s*SET, V tile right after it
-    uint32_t* wm = (uint32_t*)(smem + NBUF * SM::SET);
-    uint32_t* fm = wm + MR * MAX_W;
-    int* tl = (int*)(fm + MR * MAX_W);
-    int* tl_count = tl + MAX_T;
+    // buffer sets: K tile, V tile right after it; two separate variables (see stream_tiles)
+    __shared__ __align__(1024) char set0[SM::SET];
+    __shared__ __align__(1024) char set1[NBUF == 2 ? SM::SET : 1024];
+    __shared__ uint32_t wm[MR * MAX_W];
+    __shared__ uint32_t fm[MR * MAX_W];
+    __shared__ int tl[MAX_T];
+    __shared__ int tl_count[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31;
@@ -385,16 +377,16 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     f32x16 C[2][QB];
     unsigned long long ntile_done = 0, npv_done = 0;
     stream_tiles<NBUF>(
-        *tl_count,
-        [&](int it, int set) {
+        *tl_count, set0, NBUF == 2 ? set1 : set0,
+        [&](int it, char* buf) {
             const long j = tl[it];
-            issue_rows<E, D, NW>(kbuf + set * SM::SET, Kh, j * 64, wave, lane);
-            if constexpr (!MASK_ONLY) issue_rows<E2, D, NW>(kbuf + set * SM::SET + SM::KBYTES, Vh, j * 64, wave, lane);
+            issue_rows<E, D, NW>(buf, Kh, j * 64, wave, lane);
+            if constexpr (!MASK_ONLY) issue_rows<E2, D, NW>(buf + SM::KBYTES, Vh, j * 64, wave, lane);
         },
-        [&](int it, int set) {
+        [&](int it, const char* buf) {
             const int j = tl[it];
             if (!mask_bit(wm, W, myrow, j)) return;
-            stage1<E, D, QB>(C, kbuf + set * SM::SET, qf, lane);
+            stage1<E, D, QB>(C, buf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
             float ymax = 0.f;
@@ -411,7 +403,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                     }
             if (!__any(ymax > 0.f)) return;
             if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
-            if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, kbuf + set * SM::SET + SM::KBYTES, C, lane); ++npv_done; }
+            if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, buf + SM::KBYTES, C, lane); ++npv_done; }
         });
 
     if constexpr (!MASK_ONLY)

@@ -151,16 +151,30 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
     if constexpr (E::EPL == 8) {
         // lane half h takes chunk 2s+h of the row: byte (2s+h)*16 ^ sw = ((h*16) ^ sw) ^ (s*32)
         const int lane_off = row * L::ROW_BYTES + ((h * 16) ^ sw);
+        // Request the A fragments of PF k-steps at a time and fence the scheduler there: the MFMAs
+        // then start as the first fragments land, with the rest of the LDS latency behind them
+        // (left alone, the compiler waits for each pair of reads right before its two MFMAs).
+        constexpr int NS = D / E::KSTEP;
+        constexpr int PF = NS < 8 ? NS : 8;
+        typename E::frag a0[PF], a1[PF];
 #pragma unroll
-        for (int s = 0; s < D / E::KSTEP; ++s) {
-            const char* a = lds_tile + (lane_off ^ (s * 32));
-            const typename E::frag a0 = *(const typename E::frag*)a;
-            const typename E::frag a1 = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
+        for (int s0 = 0; s0 < NS; s0 += PF) {
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                C[0][qb] = E::mma(a0, own.f[qb][s], C[0][qb]);
-                C[1][qb] = E::mma(a1, own.f[qb][s], C[1][qb]);
+            for (int s = 0; s < PF; ++s) {
+                const char* a = lds_tile + (lane_off ^ ((s0 + s) * 32));
+                a0[s] = *(const typename E::frag*)a;
+                a1[s] = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
             }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int s = 0; s < PF; ++s) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    C[0][qb] = E::mma(a0[s], own.f[qb][s0 + s], C[0][qb]);
+                    C[1][qb] = E::mma(a1[s], own.f[qb][s0 + s], C[1][qb]);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     } else {
         // one element 2s+h per lane: chunk s/2, word 2(s%2)+h inside it
