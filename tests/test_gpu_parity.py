@@ -106,3 +106,28 @@ def test_degenerate_rows(ea):
     assert (O.cpu() - V.cpu()[:, :, :1]).abs().max() < 1e-5
     m = parity.unpack_mask(mask, N // 64)
     assert m[0, 0].tolist() == [[True, False], [True, False]]
+
+
+def test_c2_shape_two_heads(ea):
+    # configs[1]: alpha=1.5 bf16 B=4 H=16 N=4096 d=64 causal sigma=1.5, on 2 of its 64 heads
+    run_case(ea, 1, 2, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
+
+
+@pytest.mark.parametrize("alpha", [1.25, 2.0])
+def test_c5_shape_one_head(ea, alpha):
+    # configs[4]: alpha sweep, bf16, N=8192, d=64, causal, Q,K ~ N(0,4); one head
+    run_case(ea, 1, 1, 8192, 64, "bf16", True, alpha, 2.0, seed=5000)
+
+
+def test_c4_shape_planted_keys(ea):
+    # configs[3] recipe (planted high-similarity keys, sigma=3) at N=4096, d=128: near-empty masks
+    q, k, v, do = workloads.planted_qkv(1, 2, 4096, 128, "bf16", 3.0, seed=4000)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, 1.5, True, want_iters=True)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, 1.5, True, block_mask=mask)
+    torch.cuda.synchronize()
+    ref, info = parity.check_forward(q, k, v, 1.5, True, O, tau, mask, label="planted")
+    _, ginfo = parity.check_backward(q, k, v, do, 1.5, True, dQ, dK, dV, label="planted")
+    sparsity = 1.0 - (ref["margin"] > 0).sum() / (2 * 64 * 65 / 2)
+    print("  planted: block sparsity", sparsity, info, ginfo, flush=True)
+    assert sparsity > 0.5
