@@ -165,11 +165,8 @@ struct Ops {
         {
             ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
             if (E2::SCALED) {
-                hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
-                                   (long)p.BH * p.N, p.scal, p.scal + 2);
-                EA_HIP(hipGetLastError());
-                hipLaunchKernelGGL((rownorm_kernel<E, D>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.V,
-                                   (long)p.BH * p.N, (unsigned int*)nullptr, p.scal + 3);
+                hipLaunchKernelGGL((amax_kernel<E>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
+                                   (long)p.BH * p.N * D, p.scal);
                 EA_HIP(hipGetLastError());
             }
             if (COPY) {

@@ -62,16 +62,14 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     // The centre e = <dO_r, O_r> = sum_j P_rj dP_rj is the P-weighted mean of dP over the support
     // (delta is the U-weighted one): it keeps XA - (delta - e) XB free of the cancellation that
     // e = 0 would bring when dP is nearly constant over the support.  Without O, e = 0.
-    // |dP_rj| = |<dO_r, V_j>| <= max_r |dO_r| max_j |V_j| =: pb (row 2-norms from rownorm_kernel)
-    // and |e| <= pb (O_r is a convex combination of V rows), so |U (dP - e)| <= 2 pb; with a
-    // narrow-range stage-2 type U (dP - e) / (2 pb) feeds the MFMA.
-    // (With a narrow-range type the whole backward runs on dO / max|dO|; amax undoes it at the end.)
-    float pb = 1.f, inv_pb = 1.f, amax = 1.f;
+    // With a narrow-range stage-2 type the whole backward runs on dO / max|dO| (amax undoes it at
+    // the end): then |dP_rj| = |<dO_r, V_j>| <= sqrt(d) |V_j| and |U (dP - e)| <= 2 sqrt(d) max|V_j|,
+    // far inside fp16's range for any V that itself fits fp16 comfortably, and fp16 keeps 11
+    // significant bits at any magnitude in its normal range, so no further scaling is needed.
+    float amax = 1.f;
     if constexpr (E2::SCALED) {
         amax = __uint_as_float(p.scal[0]);
         if (!(amax > 0.f)) amax = 1.f;
-        pb = 2.f * (__uint_as_float(p.scal[2]) / amax) * __uint_as_float(p.scal[3]);
-        inv_pb = pb > 0.f ? 1.f / pb : 0.f;
     }
     float ctr[QB];
 #pragma unroll
@@ -96,9 +94,9 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
 
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile = 0;
-    float num[QB], den[QB], gmax[QB];
+    float num[QB], den[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = gmax[qb] = 0.f;
+    for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = 0.f;
     stream_tiles<NBUF>(
         *tl_count, set0, NBUF == 2 ? set1 : set0,
         [&](int it, char* b) {
@@ -127,31 +125,24 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
                         const float t = u * (dP[kb][qb][v] - ctr[qb]);
                         num[qb] += t;
                         den[qb] += u;
-                        gmax[qb] = fmaxf(gmax[qb], fabsf(t));
-                        S[kb][qb][v] = t * inv_pb;
+                        S[kb][qb][v] = t;
                         dP[kb][qb][v] = u;
                     }
             stage2<E2, D, QB>(XA, kbuf, S, lane);
             stage2<E2, D, QB>(XB, kbuf, dP, lane);
         });
 
-    // delta, and the bound max|U (dP - e)| + |delta - e| >= |dS| published for the dK/dV kernel
-    float bm = 0.f;
+    // delta (in units of max|dO|) for the dK/dV kernel, and the combination of the two sums
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
         const float dn = xhalf_sum(den[qb]);
         const float drel = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;      // delta - e
         if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = drel + ctr[qb];
-        bm = fmaxf(bm, xhalf_max(gmax[qb]) + fabsf(drel));
-        const float sa = pb * p.inv_sqrt_d * amax, sb = drel * p.inv_sqrt_d * amax;
+        const float sa = p.inv_sqrt_d * amax, sb = drel * p.inv_sqrt_d * amax;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int v = 0; v < 16; ++v) XA[db][qb][v] = sa * XA[db][qb][v] - sb * XB[db][qb][v];
-    }
-    if constexpr (E2::SCALED) {
-        bm = wave_max(bm);
-        if (lane == 0 && active) atomicMax(&p.scal[1], __float_as_uint(bm));
     }
     if (active) store_owned_T<D, QB>(p.dQ + hoff, qw0, XA, 1.f, lane);
     if (lane == 0) atomicAdd(&p.stats[3], ntile * QB);
@@ -189,13 +180,11 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     const long hoff = (long)bh * N * D;
     const elem* Qh = (const elem*)p.Q + hoff;
     const elem* Gh = (const elem*)p.dO + hoff;
-    // dO is used divided by max|dO| throughout, and dS is divided by the dq kernel's largest bound
-    float go_amax = 1.f, ds_bound = 1.f, ds_inv = 1.f;
+    // dO is used divided by max|dO| throughout (see dq_kernel)
+    float go_amax = 1.f;
     if constexpr (E2::SCALED) {
         go_amax = __uint_as_float(p.scal[0]);
         if (!(go_amax > 0.f)) go_amax = 1.f;
-        ds_bound = __uint_as_float(p.scal[1]);
-        ds_inv = ds_bound > 0.f ? 1.f / ds_bound : 0.f;
     }
     const int mycol = (wave * 32 * QB) / 64;  // my mask column within the group
     const int jc0 = J * MC;                   // first mask column of the group
@@ -274,17 +263,23 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = trow(kb, v, h);
-                    const float tq = tau_s[row], dq = del_s[row] * ds_inv;
+                for (int v4 = 0; v4 < 16; v4 += 4) {
+                    // registers v4..v4+3 are four consecutive tile rows: one 16-byte read each
+                    const int row = trow(kb, v4, h);
+                    const f32x4 tq4 = *(const f32x4*)(tau_s + row), dq4 = *(const f32x4*)(del_s + row);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) {
-                        const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
-                        float u;
-                        if constexpr (AM == ALPHA_15) u = yp;
-                        else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
-                        S[kb][qb][v] = u * yp;
-                        dP[kb][qb][v] = u * fmaf(dP[kb][qb][v], ds_inv, -dq);
+                    for (int e = 0; e < 4; ++e) {
+                        const int v = v4 + e;
+                        const float tq = tq4[e], dq = dq4[e];
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb) {
+                            const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
+                            float u;
+                            if constexpr (AM == ALPHA_15) u = yp;
+                            else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
+                            S[kb][qb][v] = u * yp;
+                            dP[kb][qb][v] = u * (dP[kb][qb][v] - dq);
+                        }
                     }
                 }
             stage2<E2, D, QB>(XV, gbuf, S, lane);
@@ -292,7 +287,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         });
     if (active) {
         store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
-        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, ds_bound * p.inv_sqrt_d * go_amax, lane);
+        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax, lane);
     }
     if (lane == 0) atomicAdd(&p.stats[4], ntile_done * QB);
 }

@@ -21,8 +21,7 @@ struct Params {
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
-    // scal[0] = max |dO| (dO is used divided by it), scal[1] = max over rows of the bound on |dS|
-    // (see dq_kernel), scal[2] = max row 2-norm of dO, scal[3] = max row 2-norm of V
+    // scal[0] = max |dO| (the backward uses dO divided by it)
     unsigned int* scal;
     int BH, N, T, W;
     int causal;

@@ -452,30 +452,17 @@ __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int
     if (scal && threadIdx.x < 4) scal[threadIdx.x] = 0u;
 }
 
-// Per row of a [rows][D] matrix: max |x| -> amax_bits (nullable) and max row 2-norm -> norm_bits,
-// both by atomicMax on the float's bit pattern (non-negative floats order as unsigned ints).
-template <class E, int D>
-__global__ __launch_bounds__(256) void rownorm_kernel(const typename E::elem* x, long rows, unsigned int* amax_bits,
-                                                          unsigned int* norm_bits) {
-    const int lane = threadIdx.x & 63;
-    float am = 0.f, nm = 0.f;
-    for (long row = blockIdx.x * 4L + (threadIdx.x >> 6); row < rows; row += (long)gridDim.x * 4) {
-        float ss = 0.f;
+// max |x| over a tensor -> atomicMax on the float's bit pattern (non-negative floats order as
+// unsigned ints); n is a multiple of 8
+template <class E>
+__global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
+    float m = 0.f;
+    for (long i = (blockIdx.x * 256L + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
 #pragma unroll
-        for (int e = 0; e < D / 64; ++e) {
-            const float v = (float)x[row * D + e * 64 + lane];
-            ss = fmaf(v, v, ss);
-            am = fmaxf(am, fabsf(v));
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off);
-        nm = fmaxf(nm, ss);
+        for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)x[i + e]));
     }
-    am = wave_max(am);
-    if (lane == 0) {
-        if (amax_bits) atomicMax(amax_bits, __float_as_uint(am));
-        atomicMax(norm_bits, __float_as_uint(sqrtf(nm) * 1.0001f));
-    }
+    m = wave_max(m);
+    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
 }
 
 }  // namespace ea
