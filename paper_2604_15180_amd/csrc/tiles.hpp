@@ -82,8 +82,19 @@ EA_DEV int perm_row(int m) {
 // swz makes the 16 rows that one ds_read_b128 phase touches land in 16 distinct bank groups.
 // The loading lane simply fetches the global chunk that belongs at its LDS position.
 template <int CPR> EA_DEV int swz(int row) {   // CPR = 16-byte chunks per row (8, 16 or 32)
-    if constexpr (CPR == 8) return (row >> 1) & 7;
-    else return row & 15;
+    // Two access patterns must both be conflict-free:
+    //  (1) stage 1, ds_read_b128: 16 lanes read the same chunk of 16 different rows of a 16-row block;
+    //  (2) stage 2, ds_read_b64_tr_b16: 32 lanes read a patch of 4 consecutive rows x 4 chunks.
+    // A bit rotation of the row index does both: consecutive rows move by 4 chunks (pattern 2),
+    // and the map is still one-to-one over 16 rows (pattern 1).
+    if constexpr (CPR == 8) {                  // two rows per 256-byte bank sweep: use row / 2
+        const int x = (row >> 1) & 7;
+        return ((x & 1) << 2) | (x >> 1);
+    } else if constexpr (CPR == 16) {
+        return ((row & 3) << 2) | ((row >> 2) & 3);
+    } else {
+        return row & 15;
+    }
 }
 template <class E, int D> struct RowTile {      // 64 rows x D elements, row-major
     static constexpr int ROW_BYTES = D * (int)sizeof(typename E::elem);
@@ -135,7 +146,7 @@ EA_DEV void load_owned(Owned<E, D, QB>& o, const typename E::elem* g, long row0,
 }
 
 // ---- stage 1: C[kb][qb] = tile(64 x D, LDS row-major, swizzled) . owned^T -----------------------
-template <class E, int D, int QB>
+template <class E, int D, int QB, bool FENCE = true>
 EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, QB>& own, int lane) {
     using L = RowTile<E, D>;
     constexpr int ES = (int)sizeof(typename E::elem);
@@ -165,7 +176,7 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
                 a0[s] = *(const typename E::frag*)a;
                 a1[s] = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
             }
-            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int s = 0; s < PF; ++s) {
 #pragma unroll
@@ -174,7 +185,7 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
                     C[1][qb] = E::mma(a1[s], own.f[qb][s0 + s], C[1][qb]);
                 }
             }
-            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
         }
     } else {
         // one element 2s+h per lane: chunk s/2, word 2(s%2)+h inside it
