@@ -59,7 +59,7 @@ void timer_begin_call() {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, d, delta, mask, wmask, tmax, total;
+    size_t stats, a, b, c, d, delta, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, total;
 };
 
 // element size of the stage-2 copies
@@ -73,6 +73,10 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.a = off; off += align256(BH * N * d * t_elem(t));          // V in the stage-2 type
     L.wmask = off; off += align256(BH * T * W * 4);
     L.tmax = off; off += align256(BH * T * (size_t)N * 2);       // per-row key-tile maxima, fp16
+    L.rs_lo = off; off += align256(BH * N * 4);                  // solver state between the two kernels
+    L.rs_hi = off; off += align256(BH * N * 4);
+    L.rs_f1 = off; off += align256(BH * N * 4);
+    L.rs_state = off; off += align256(BH * N * 4);
     L.total = off;
     return L;
 }
@@ -260,6 +264,7 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.V2 = (t == EA_BF16) ? (const void*)(ws + L.a) : V;
     p.wmask = (int32_t*)(ws + L.wmask);
     p.tmax = (_Float16*)(ws + L.tmax);
+    p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(64), 0, s, p.stats, EA_STATS_WORDS, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
     timer_begin_call();

@@ -18,6 +18,7 @@ struct Params {
     int32_t* mask;        // exported / final mask   [BH][T][W]
     int32_t* wmask;       // working mask (superset) [BH][T][W]
     int32_t* iters;       // nullable
+    float* rs_lo; float* rs_hi; float* rs_f1; int* rs_state;   // [BH][N] solver state handed from tau_kernel to out_kernel
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):

@@ -1,8 +1,9 @@
 // Forward kernels (Alg. 1 of the AdaSplash-2 paper), re-cut for CDNA4:
 //   tau_kernel : Phase 1 (row max, plus per-row tile maxima -> candidate tiles), Phase 2 (LDS
-//                histogram over the candidates -> tau_0), Phase 3 (safeguarded Halley/Newton
-//                refinement to convergence + working block mask at tau_0)
-//   out_kernel : Phase 4 (O = P V over the working mask) + the exported mask at the final tau
+//                histogram over the candidates -> tau_0), first Phase-3 sweep (f, f', f'' at tau_0,
+//                one safeguarded Halley/Newton step, working block mask at tau_0)
+//   out_kernel : Phase 4 (O = P V over the working mask), which is also the next evaluation of f;
+//                further refinement only for rows that fail it; exported mask at the final tau
 // One work-group = 128*QB query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
 // B operands in registers; 64-key tiles of K (and V) stream through LDS.
 #pragma once
@@ -66,6 +67,67 @@ EA_DEV float solve_histogram(const uint32_t* H, float r) {
         }
         return tau;
     }
+}
+
+// ---- pieces of the refinement (Sec. 3.2, Phase 3 of Alg. 1) shared by both forward kernels ----
+// Accumulate sum y^r, sum y^(r-1), sum y^(r-2) over the scores of one sub-tile that lie above tau
+// (alpha = 1.5: the last one is a count; alpha = 2: the middle one is).  Returns whether any did.
+template <int AM, int QB>
+EA_DEV bool eval_scores(const f32x16 (&C)[2][QB], const float (&thr)[QB], float c, float r, float (&F)[QB],
+                        float (&G)[QB], float (&Hs)[QB], int (&cnt)[QB]) {
+    bool hit = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        float lmax = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lmax = fmaxf(lmax, C[kb][qb][v]);
+        if (__any(fmaf(c, lmax, -thr[qb]) > 0.f)) {
+            hit = true;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float y = fmaf(c, C[kb][qb][v], -thr[qb]);
+                    if constexpr (AM == ALPHA_15) {
+                        const float yp = fmaxf(y, 0.f);
+                        F[qb] = fmaf(yp, yp, F[qb]);
+                        G[qb] += yp;
+                        cnt[qb] += (y > 0.f);
+                    } else if constexpr (AM == ALPHA_20) {
+                        F[qb] += fmaxf(y, 0.f);
+                        cnt[qb] += (y > 0.f);
+                    } else {
+                        if (y > 0.f) {
+                            const float p2 = pow_r2<AM>(y, r);
+                            Hs[qb] += p2;
+                            G[qb] = fmaf(p2, y, G[qb]);
+                            F[qb] = fmaf(p2 * y, y, F[qb]);
+                        }
+                    }
+                }
+        }
+    }
+    return hit;
+}
+
+// One safeguarded hybrid step from (tau, f = F - 1) with G = sum y^(r-1), Hs = sum y^(r-2):
+// Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2, the bracket's midpoint whenever the
+// proposed point leaves (lo, hi).  Updates the bracket; returns the proposed threshold.
+EA_DEV float hybrid_step(float tau, float f, float G, float Hs, float r, float alpha, float& lo, float& hi) {
+    if (f > 0.f) lo = tau; else hi = tau;
+    const float f1 = -r * G;
+    float delta;
+    if (alpha <= 1.5f) {
+        const float f2 = r * (r - 1.f) * Hs;
+        delta = -2.f * f * f1 / (2.f * f1 * f1 - f * f2);
+    } else {
+        delta = -f / f1;
+    }
+    float cand = tau + delta;
+    if (!(cand > lo && cand < hi)) cand = 0.5f * (lo + hi);
+    return cand;
 }
 
 template <class E, int D, int QB, int NB, int NW, int NBUF>
@@ -210,7 +272,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
 
     // ---- Phase 3: refinement sweeps; the first also records the working mask --------------
     int nsweeps = 0;
-    for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
+    for (int sweep = 0; sweep < 1; ++sweep) {     // later evaluations ride on Phase 4 (out_kernel)
         ++nsweeps;
         float thr[QB], F[QB], G[QB], Hs[QB];
         int cnt[QB];      // number of scores above tau (alpha = 1.5: f'' sum; alpha = 2: f' sum)
@@ -224,40 +286,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
         auto body = [&](int j, const char* buf) {
             if (!mask_bit(first ? cand : wm, W, myrow, j)) return;
             scores(j, buf);
-            bool hit = false;
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb) {
-                float lmax = -INFINITY;
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) lmax = fmaxf(lmax, C[kb][qb][v]);
-                if (__any(fmaf(c, lmax, -thr[qb]) > 0.f)) {
-                    hit = true;
-#pragma unroll
-                    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const float y = fmaf(c, C[kb][qb][v], -thr[qb]);
-                            if constexpr (AM == ALPHA_15) {
-                                const float yp = fmaxf(y, 0.f);
-                                F[qb] = fmaf(yp, yp, F[qb]);
-                                G[qb] += yp;
-                                cnt[qb] += (y > 0.f);
-                            } else if constexpr (AM == ALPHA_20) {
-                                F[qb] += fmaxf(y, 0.f);
-                                cnt[qb] += (y > 0.f);
-                            } else {
-                                if (y > 0.f) {
-                                    const float p2 = pow_r2<AM>(y, r);
-                                    Hs[qb] += p2;
-                                    G[qb] = fmaf(p2, y, G[qb]);
-                                    F[qb] = fmaf(p2 * y, y, F[qb]);
-                                }
-                            }
-                        }
-                }
-            }
+            const bool hit = eval_scores<AM, QB>(C, thr, c, r, F, G, Hs, cnt);
             if (first && hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
         };
         stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) { body(tl[it], buf); });
@@ -272,27 +301,15 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             }
         }
         __syncthreads();
-        // hybrid update (Sec. 3.2): Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2,
-        // bisection whenever the proposed point leaves the bracket
         int pending = 0;
         if (tid < BR && !rs_done[tid]) {
             const float tau = rs_thr[tid];
             const float f = rs_F[tid] - 1.f;
-            const float f1 = -r * rs_G[tid];
             rs_iters[tid] += 1;
             bool done = fabsf(f) <= p.tol;
             if (!done) {
                 float lo = rs_lo[tid], hi = rs_hi[tid];
-                if (f > 0.f) lo = tau; else hi = tau;
-                float delta;
-                if (p.alpha <= 1.5f) {
-                    const float f2 = r * (r - 1.f) * rs_H[tid];
-                    delta = -2.f * f * f1 / (2.f * f1 * f1 - f * f2);
-                } else {
-                    delta = -f / f1;
-                }
-                float cand = tau + delta;
-                if (!(cand > lo && cand < hi)) cand = 0.5f * (lo + hi);
+                const float cand = hybrid_step(tau, f, rs_G[tid], rs_H[tid], r, p.alpha, lo, hi);
                 done = fabsf(cand - tau) < p.tol;
                 rs_thr[tid] = cand; rs_lo[tid] = lo; rs_hi[tid] = hi;
             }
@@ -300,14 +317,19 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             pending = !done;
         }
         const int left = __syncthreads_count(pending);
-        if (first) build_tile_list(wm, MR, W, tl, tl_count, tid);
         if (left == 0) break;
     }
 
     // ---- results ------------------------------------------------------------------------
+    // threshold after the sweeps run here, its bracket, and (iterations | done << 16): the output
+    // kernel evaluates f again while it forms O and finishes the rows that still need it
     if (tid < BR && q0 + tid < N) {
-        p.tau[(long)bh * N + q0 + tid] = rs_thr[tid];
-        if (p.iters) p.iters[(long)bh * N + q0 + tid] = rs_iters[tid];
+        const long g = (long)bh * N + q0 + tid;
+        p.tau[g] = rs_thr[tid];
+        p.rs_lo[g] = rs_lo[tid];
+        p.rs_hi[g] = rs_hi[tid];
+        p.rs_state[g] = rs_iters[tid] | (rs_done[tid] << 16);
+        p.rs_f1[g] = -r * rs_G[tid];          // f' at the point evaluated here
     }
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
@@ -362,28 +384,47 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
-    float thr[QB];
+    // per-row solver state, held by both lanes of a row
+    constexpr bool REFINE = !MASK_ONLY;
+    float thr[QB], lo[QB], hi[QB], f1_prev[QB];
+    int done[QB], iters[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) thr[qb] = active ? p.tau[(long)bh * N + qw0 + 32 * qb + n] : 0.f;
+    for (int qb = 0; qb < QB; ++qb) {
+        const long g = (long)bh * N + qw0 + 32 * qb + n;
+        thr[qb] = active ? p.tau[g] : 0.f;
+        lo[qb] = hi[qb] = 0.f; done[qb] = 1; iters[qb] = 0; f1_prev[qb] = -1.f;
+        if (REFINE && active) {
+            lo[qb] = p.rs_lo[g]; hi[qb] = p.rs_hi[g]; f1_prev[qb] = p.rs_f1[g];
+            const int st = p.rs_state[g];
+            iters[qb] = st & 0xffff; done[qb] = st >> 16;
+        }
+    }
 
     f32x16 X[D / 32][QB];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
-
     f32x16 C[2][QB];
-    unsigned long long ntile_done = 0, npv_done = 0;
-    stream_tiles<NBUF>(
-        *tl_count, set0, NBUF == 2 ? set1 : set0,
-        [&](int it, char* buf) {
-            const long j = tl[it];
-            issue_rows<E, D, NW>(buf, Kh, j * 64, wave, lane);
-            if constexpr (!MASK_ONLY) issue_rows<E2, D, NW>(buf + SM::KBYTES, Vh, j * 64, wave, lane);
-        },
-        [&](int it, const char* buf) {
+    unsigned long long ntile_done = 0, npv_done = 0, nstat_done = 0;
+    auto issue_kv = [&](int it, char* buf) {
+        const long j = tl[it];
+        issue_rows<E, D, NW>(buf, Kh, j * 64, wave, lane);
+        if constexpr (!MASK_ONLY) issue_rows<E2, D, NW>(buf + SM::KBYTES, Vh, j * 64, wave, lane);
+    };
+    auto issue_k = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
+
+    // Phase 4 doubles as the next evaluation of f: the row sums of P are f(tau) + 1.  A row is
+    // finished when |f| <= tol, or when the step -f / f' (with f' from its previous evaluation: a
+    // chord step) is shorter than tol; it then takes that step, and O, computed less than tol away
+    // in tau, stands.  Only when some row fails both, a scores-only sweep gathers f', f'' at the
+    // same tau, the hybrid step moves those rows, and Phase 4 runs again.
+    auto pv_pass = [&](float (&rowsum)[QB]) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) X[db][qb][v] = 0.f;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) rowsum[qb] = 0.f;
+        stream_tiles<NBUF>(*tl_count, set0, NBUF == 2 ? set1 : set0, issue_kv, [&](int it, const char* buf) {
             const int j = tl[it];
             if (!mask_bit(wm, W, myrow, j)) return;
             stage1<E, D, QB>(C, buf, qf, lane);
@@ -398,13 +439,91 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                     for (int v = 0; v < 16; ++v) {
                         const float yp = fmaxf(fmaf(c, C[kb][qb][v], -thr[qb]), 0.f);
                         ymax = fmaxf(ymax, yp);
-                        if constexpr (AM == ALPHA_GEN) C[kb][qb][v] = (yp > 0.f) ? pow_r<AM>(yp, r) : 0.f;
-                        else C[kb][qb][v] = pow_r<AM>(yp, r);
+                        float pr;
+                        if constexpr (AM == ALPHA_GEN) pr = (yp > 0.f) ? pow_r<AM>(yp, r) : 0.f;
+                        else pr = pow_r<AM>(yp, r);
+                        if constexpr (REFINE) rowsum[qb] += pr;
+                        C[kb][qb][v] = pr;
                     }
             if (!__any(ymax > 0.f)) return;
             if (lane == 0) atomicOr(&fm[myrow * W + (j >> 5)], 1u << (j & 31));
             if constexpr (!MASK_ONLY) { stage2<E2, D, QB>(X, buf + SM::KBYTES, C, lane); ++npv_done; }
         });
+    };
+
+    float rowsum[QB];
+    pv_pass(rowsum);
+    if constexpr (REFINE) {
+        int need = 0;
+        float fval[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            fval[qb] = xhalf_sum(rowsum[qb]) - 1.f;
+            if (!done[qb]) {
+                iters[qb] += 1;
+                const float chord = -fval[qb] / f1_prev[qb];
+                if (fabsf(fval[qb]) <= p.tol) done[qb] = 1;
+                else if (fabsf(chord) < p.tol && f1_prev[qb] < 0.f) {
+                    thr[qb] = fminf(fmaxf(thr[qb] + chord, lo[qb]), hi[qb]);
+                    done[qb] = 1;
+                } else need = 1;
+            }
+        }
+        if (__syncthreads_count(need) != 0) {
+            // rare: finish those rows with scores-only sweeps over the tiles that held some P > 0
+            // (a superset of the support at any larger tau), then form O once more
+            bool have_f = true;          // the first sweep runs at the tau whose f is already known
+            for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
+                float F[QB], G[QB], Hs[QB];
+                int cnt[QB];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) { F[qb] = G[qb] = Hs[qb] = 0.f; cnt[qb] = 0; }
+                stream_tiles<NBUF>(*tl_count, set0, NBUF == 2 ? set1 : set0, issue_k, [&](int it, const char* buf) {
+                    const int j = tl[it];
+                    if (!mask_bit(fm, W, myrow, j)) return;
+                    stage1<E, D, QB>(C, buf, qf, lane);
+                    if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
+                    ++nstat_done;
+                    eval_scores<AM, QB>(C, thr, c, r, F, G, Hs, cnt);
+                });
+                int pending = 0;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
+                    if constexpr (AM == ALPHA_20) G[qb] = (float)cnt[qb];
+                    const float g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
+                    const float f = have_f ? fval[qb] : xhalf_sum(F[qb]) - 1.f;
+                    if (!done[qb]) {
+                        if (!have_f) iters[qb] += 1;
+                        if (!have_f && fabsf(f) <= p.tol) done[qb] = 1;
+                        else {
+                            const float cand = hybrid_step(thr[qb], f, g, hs, r, p.alpha, lo[qb], hi[qb]);
+                            if (fabsf(cand - thr[qb]) < p.tol) done[qb] = 1;
+                            thr[qb] = cand;
+                        }
+                        pending |= !done[qb];
+                    }
+                }
+                have_f = false;
+                if (__syncthreads_count(pending) == 0) break;
+            }
+            __syncthreads();
+            for (int i = tid; i < MR * W; i += THREADS) fm[i] = 0u;
+            __syncthreads();
+            float unused[QB];
+            pv_pass(unused);
+        }
+    }
+    if constexpr (REFINE) {
+        if (active && (lane >> 5) == 0) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const long g = (long)bh * N + qw0 + 32 * qb + n;
+                p.tau[g] = thr[qb];
+                if (p.iters) p.iters[g] = iters[qb];
+            }
+        }
+    }
 
     if constexpr (!MASK_ONLY)
         if (active) store_owned_T<D, QB>(p.O + (long)bh * N * D, qw0, X, 1.f, lane);
@@ -413,6 +532,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     if (lane == 0) {
         atomicAdd(&p.stats[MASK_ONLY ? 6 : 1], ntile_done * QB);
         if (!MASK_ONLY) atomicAdd(&p.stats[7], npv_done * QB);
+        if (!MASK_ONLY) atomicAdd(&p.stats[0], nstat_done * QB);
     }
 }
 
