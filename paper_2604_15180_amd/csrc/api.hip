@@ -19,8 +19,7 @@ constexpr int QB = 1;        // 32*QB owned rows per wave
 constexpr int NW_TAU = 4, NBUF_TAU = 2;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
 constexpr int NW_DQ = 2, NBUF_DQ = 2;
-constexpr int NW_DKDV = 2, NBUF_DKDV = 1;
-constexpr bool USE_DKDV2 = false;   // two query tiles per iteration (see dkdv2_kernel)
+constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
 constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
 constexpr int MAX_SWEEPS = 12;
 
@@ -189,10 +188,8 @@ struct Ops {
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_DKDV, s);
-        if constexpr (USE_DKDV2 && E2::EPL == 8)
-            return launch(dkdv2_kernel<E2, D, AM>, dim3(p.BH * (p.N / 64)), 128, s, p);
-        else
-        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NBUF_DKDV>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
+        constexpr int NB2 = (E2::EPL == 8) ? NBUF_DKDV : 1;     // fp32 tiles are twice as large
+        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
     }
 };
 

@@ -292,146 +292,4 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     if (lane == 0) atomicAdd(&p.stats[4], ntile_done * QB);
 }
 
-// dK/dV for one mask column (64 keys, two waves of 32) per work-group, two query tiles per loop
-// iteration.  The two tiles' work is laid out as one straight-line block
-//     scores(A); scores(B) | per-score math(A); products(A) | per-score math(B); products(B)
-// so that the instruction scheduler can run the vector-ALU work of one tile under the MFMAs of
-// the other: with one wave per SIMD (the accumulators need the whole register file) nothing else
-// hides it.  The diagonal tile, the only one that needs the causal select, is peeled off.
-template <class E, int D>
-struct Dkdv2Smem {
-    static constexpr int RBYTES = RowTile<E, D>::BYTES;
-    static constexpr int SLOT = 2 * RBYTES + 4 * 2 * TILE;     // Q tile, dO tile, tau[64], delta[64]
-};
-
-template <class E, int D, int AM>
-__global__ __launch_bounds__(128) void dkdv2_kernel(Params p) {
-    using SM = Dkdv2Smem<E, D>;
-    using elem = typename E::elem;
-    constexpr int NW = 2, QB = 1, BC = 64, THREADS = 128;
-    __shared__ __align__(1024) char slot0[SM::SLOT];
-    __shared__ __align__(1024) char slot1[SM::SLOT];
-    __shared__ int tl[MAX_T];
-    __shared__ int wcnt[16];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int h = lane >> 5;
-    const int N = p.N, T = p.T, W = p.W;
-    int bh, J;
-    map_block(blockIdx.x, p.BH, N / BC, bh, J);
-    J = N / BC - 1 - J;                        // causal: the first key tiles have the longest columns
-    const long kw0 = (long)J * BC + wave * 32;
-    const long hoff = (long)bh * N * D;
-    const elem* Qh = (const elem*)p.Q + hoff;
-    const elem* Gh = (const elem*)p.dO + hoff;
-    const float c = p.c, r = p.r;
-    float go_amax = 1.f;
-    if constexpr (E::SCALED) {
-        go_amax = __uint_as_float(p.scal[0]);
-        if (!(go_amax > 0.f)) go_amax = 1.f;
-    }
-
-    // column walk of the row-packed mask: ascending list of query tiles whose bit J is set
-    if (tid == 0) wcnt[8] = 0;
-    __syncthreads();
-    for (int base = p.causal ? J : 0; base < T; base += THREADS) {
-        const int i = base + tid;
-        const bool on = i < T && (((uint32_t)p.mask[((long)bh * T + i) * W + (J >> 5)] >> (J & 31)) & 1u);
-        const unsigned long long bal = __ballot(on);
-        if (lane == 0) wcnt[wave] = __popcll(bal);
-        __syncthreads();
-        const int off = wcnt[8] + (wave ? wcnt[0] : 0) + __popcll(bal & ((1ull << lane) - 1ull));
-        if (on) tl[off] = i;
-        __syncthreads();
-        if (tid == 0) wcnt[8] += wcnt[0] + wcnt[1];
-        __syncthreads();
-    }
-    const int ntl = wcnt[8];
-
-    Owned<E, D, QB> kf, vf;
-    load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, kw0, lane);
-    load_owned<E, D, QB>(vf, (const elem*)p.V + hoff, kw0, lane);
-    f32x16 XV[D / 32][QB], XK[D / 32][QB];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { XV[db][0][v] = 0.f; XK[db][0][v] = 0.f; }
-
-    constexpr int VEC_OFF = 2 * SM::RBYTES;
-    auto issue = [&](int it, char* slot) {
-        const long i = tl[it];
-        issue_rows<E, D, NW>(slot, Qh, i * 64, wave, lane);
-        issue_rows<E, D, NW>(slot + SM::RBYTES, Gh, i * 64, wave, lane);
-        if (wave == 0) load4_to_lds(p.tau + (long)bh * N + i * 64 + lane, slot + VEC_OFF);
-        if (wave == 1) load4_to_lds(p.delta + (long)bh * N + i * 64 + lane, slot + VEC_OFF + 4 * TILE);
-    };
-    auto scores = [&](f32x16 (&S)[2][QB], f32x16 (&dP)[2][QB], const char* slot) {
-        stage1<E, D, QB, false>(S, slot, kf, lane);
-        stage1<E, D, QB, false>(dP, slot + SM::RBYTES, vf, lane);
-    };
-    auto per_score = [&](f32x16 (&S)[2][QB], f32x16 (&dP)[2][QB], const char* slot) {
-        const float* tau_s = (const float*)(slot + VEC_OFF);
-        const float* del_s = tau_s + TILE;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v4 = 0; v4 < 16; v4 += 4) {
-                const int row = trow(kb, v4, h);       // registers v4..v4+3 are consecutive tile rows
-                const f32x4 tq4 = *(const f32x4*)(tau_s + row), dq4 = *(const f32x4*)(del_s + row);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = v4 + e;
-                    const float yp = fmaxf(fmaf(c, S[kb][0][v], -tq4[e]), 0.f);
-                    float u;
-                    if constexpr (AM == ALPHA_15) u = yp;
-                    else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
-                    S[kb][0][v] = u * yp;
-                    dP[kb][0][v] = u * (dP[kb][0][v] - dq4[e]);
-                }
-            }
-    };
-    auto products = [&](const f32x16 (&S)[2][QB], const f32x16 (&dP)[2][QB], const char* slot) {
-        stage2<E, D, QB>(XV, slot + SM::RBYTES, S, lane);
-        stage2<E, D, QB>(XK, slot, dP, lane);
-    };
-
-    f32x16 SA[2][QB], PA[2][QB], SB[2][QB], PB[2][QB];
-    int it = 0;
-    if (ntl > 0 && p.causal && tl[0] == J) {          // diagonal tile: hide key > query
-        issue(0, slot0);
-        wait_loads();
-        __syncthreads();
-        scores(SA, PA, slot0);
-        causal_hide<QB, false>(SA, J * 64, (int)kw0, lane);
-        per_score(SA, PA, slot0);
-        products(SA, PA, slot0);
-        __syncthreads();
-        it = 1;
-    }
-    for (; it + 1 < ntl; it += 2) {
-        issue(it, slot0);
-        issue(it + 1, slot1);
-        wait_loads();
-        __syncthreads();
-        scores(SA, PA, slot0);
-        scores(SB, PB, slot1);
-        per_score(SA, PA, slot0);
-        products(SA, PA, slot0);
-        per_score(SB, PB, slot1);
-        products(SB, PB, slot1);
-        __syncthreads();
-    }
-    if (it < ntl) {
-        issue(it, slot0);
-        wait_loads();
-        __syncthreads();
-        scores(SA, PA, slot0);
-        per_score(SA, PA, slot0);
-        products(SA, PA, slot0);
-    }
-    store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
-    store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax, lane);
-    if (lane == 0) atomicAdd(&p.stats[4], (unsigned long long)ntl);
-}
-
 }  // namespace ea
