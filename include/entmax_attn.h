@@ -48,8 +48,10 @@ enum {
     EA_ERR_HIP = -6         /* a HIP call failed; see entmax_attn_last_hip_error() */
 };
 
-/* Number of 64-bit counters at the start of the workspace (see entmax_attn_fwd). */
+/* The workspace starts with EA_STATS_COPIES copies of EA_STATS_WORDS 64-bit counters
+ * ([copy][counter]); the value of a counter is the sum over the copies (see entmax_attn_fwd). */
 #define EA_STATS_WORDS 16
+#define EA_STATS_COPIES 64
 enum {
     /* units: 64x32 score sub-tiles (64 streamed rows x 32 register-resident rows), the piece one
      * wavefront computes per MFMA block pair; one matmul on a sub-tile is 2*64*32*d flops */
@@ -81,8 +83,9 @@ size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, i
  *   iters       out  [B,H,N] int32, may be NULL: number of refinement iterations the row
  *                    needed; one iteration = one evaluation of f, f', f'' over the true scores
  *                    followed by one update (Sec. 3.3 Phase 3)
- * The first EA_STATS_WORDS uint64 of `workspace` are zeroed by the call and then hold the
- * executed-tile counters of this call (EA_STAT_*), readable after the stream has drained.
+ * The first EA_STATS_COPIES * EA_STATS_WORDS uint64 of `workspace` are zeroed by the call and
+ * then hold the executed-tile counters of this call (EA_STAT_*, summed over the copies),
+ * readable after the stream has drained.
  */
 int entmax_attn_fwd(const void* Q, const void* K, const void* V,
                     float* O, float* tau, int32_t* block_mask, int32_t* iters,

@@ -14,6 +14,7 @@ _lib = None
 
 EA_F32, EA_BF16 = 0, 1
 EA_STATS_WORDS = 16
+EA_STATS_COPIES = 64
 STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
               "sweeps", "mask_subtiles", "out_pv_subtiles")
 EA_TIMER_SLOTS = 8
@@ -167,5 +168,5 @@ def entmax_attn_timer_read():
 
 def read_stats(workspace):
     """Executed-tile counters of the last call that used `workspace` (synchronises)."""
-    vals = workspace[: EA_STATS_WORDS * 8].view(torch.int64).cpu().tolist()
-    return dict(zip(STAT_NAMES, vals))
+    copies = workspace[: EA_STATS_COPIES * EA_STATS_WORDS * 8].view(torch.int64).view(EA_STATS_COPIES, EA_STATS_WORDS)
+    return dict(zip(STAT_NAMES, copies.cpu().sum(0).tolist()))

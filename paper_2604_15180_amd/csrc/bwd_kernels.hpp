@@ -30,6 +30,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     __shared__ uint32_t fm[MR * MAX_W];
     __shared__ int tl[MAX_T];
     __shared__ int tl_count[4];
+    __shared__ unsigned long long blk_stats[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -145,7 +146,11 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
             for (int v = 0; v < 16; ++v) XA[db][qb][v] = sa * XA[db][qb][v] - sb * XB[db][qb][v];
     }
     if (active) store_owned_T<D, QB>(p.dQ + hoff, qw0, XA, 1.f, lane);
-    if (lane == 0) atomicAdd(&p.stats[3], ntile * QB);
+    {
+        const int slot[1] = {3};
+        const unsigned long long val[1] = {ntile * QB};
+        flush_counters<1>(blk_stats, p.stats, slot, val, tid, lane);
+    }
 }
 
 template <class E, class E2, int D, int QB, int NW, int NBUF>
@@ -168,6 +173,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     __shared__ __align__(1024) char set1[NBUF == 2 ? SM::SET : 1024];
     __shared__ int tl[MAX_T];                // entries: query tile | column flags << 16
     __shared__ int wcnt[16];                 // per-wave counts, [8] = running total
+    __shared__ unsigned long long blk_stats[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -289,7 +295,11 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
         store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax, lane);
     }
-    if (lane == 0) atomicAdd(&p.stats[4], ntile_done * QB);
+    {
+        const int slot[1] = {4};
+        const unsigned long long val[1] = {ntile_done * QB};
+        flush_counters<1>(blk_stats, p.stats, slot, val, tid, lane);
+    }
 }
 
 }  // namespace ea

@@ -98,6 +98,29 @@ EA_DEV void stream_tiles(int ntiles, char* buf0, char* buf1, IssueF issue, Compu
     }
 }
 
+// Executed-work counters.  The workspace starts with STATS_COPIES copies of the STATS_WORDS
+// counters (a counter's value is the sum over the copies).  The waves of a group first add into
+// LDS; one thread per counter then issues one global atomic, aimed at the copy picked by the
+// block id, so that the atomics of groups finishing together fall on different cache lines
+// (tens of thousands of atomics on one line cost more than a small kernel's whole run time).
+constexpr int STATS_WORDS = 16, STATS_COPIES = 64;
+template <int K>
+EA_DEV void flush_counters(unsigned long long* blk, unsigned long long* stats, const int (&slot)[K],
+                           const unsigned long long (&val)[K], int tid, int lane) {
+    __syncthreads();
+    if (tid < K) blk[tid] = 0ull;
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (val[k]) atomicAdd(&blk[k], val[k]);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < K; ++k)
+        if (tid == k && blk[k]) atomicAdd(&stats[(blockIdx.x & (STATS_COPIES - 1)) * STATS_WORDS + slot[k]], blk[k]);
+}
+
 // Union of `rows` mask rows (LDS, `W` words each) -> ascending list of tile indices in LDS.
 // Called by all threads; the first wave does the work.  Uses one wave-wide exclusive scan of
 // the per-word popcounts (W <= 64).

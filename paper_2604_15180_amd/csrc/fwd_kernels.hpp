@@ -154,6 +154,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     __shared__ uint32_t cand[MR * MAX_W];
     __shared__ int tl[MAX_T];
     __shared__ int tl_count[4];
+    __shared__ unsigned long long blk_stats[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -333,8 +334,11 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     }
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
-    if (lane == 0) atomicAdd(&p.stats[0], ntile_done * QB);
-    if (tid == 0) atomicAdd(&p.stats[5], (unsigned long long)nsweeps);
+    {
+        const int slot[2] = {0, 5};
+        const unsigned long long val[2] = {ntile_done * QB, wave == 0 ? (unsigned long long)nsweeps : 0ull};
+        flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
+    }
 }
 
 template <class E, class E2, int D, int QB, bool MASK_ONLY, int NW, int NBUF>
@@ -361,6 +365,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     __shared__ uint32_t fm[MR * MAX_W];
     __shared__ int tl[MAX_T];
     __shared__ int tl_count[4];
+    __shared__ unsigned long long blk_stats[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31;
@@ -529,15 +534,15 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
         if (active) store_owned_T<D, QB>(p.O + (long)bh * N * D, qw0, X, 1.f, lane);
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)fm[i];
-    if (lane == 0) {
-        atomicAdd(&p.stats[MASK_ONLY ? 6 : 1], ntile_done * QB);
-        if (!MASK_ONLY) atomicAdd(&p.stats[7], npv_done * QB);
-        if (!MASK_ONLY) atomicAdd(&p.stats[0], nstat_done * QB);
+    {
+        const int slot[3] = {MASK_ONLY ? 6 : 1, 7, 0};
+        const unsigned long long val[3] = {ntile_done * QB, npv_done * QB, nstat_done * QB};
+        flush_counters<3>(blk_stats, p.stats, slot, val, tid, lane);
     }
 }
 
 // All causally visible tiles set: the working mask handed to out_kernel<MASK_ONLY>.
-__global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, int causal) {
+static __global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, int causal) {
     const long total = (long)BH * T * W;
     for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
         const int m = (int)(i % W), row = (int)((i / W) % T);
@@ -567,8 +572,8 @@ __global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* 
     }
 }
 
-__global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int* scal) {
-    if ((int)threadIdx.x < n) stats[threadIdx.x] = 0ull;
+static __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int* scal) {
+    for (int i = threadIdx.x; i < n; i += blockDim.x) stats[i] = 0ull;
     if (scal && threadIdx.x < 4) scal[threadIdx.x] = 0u;
 }
 

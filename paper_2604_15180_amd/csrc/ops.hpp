@@ -1,0 +1,118 @@
+// Kernel sequences of one forward / backward call, templated on the element types, the head
+// dim and the alpha mode.  Included by the per-type translation units only.
+#pragma once
+#include <type_traits>
+
+#include "bwd_kernels.hpp"
+#include "fwd_kernels.hpp"
+#include "launch.hpp"
+
+namespace ea {
+
+constexpr int QB = 1;        // 32*QB owned rows per wave
+// waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
+constexpr int NW_TAU = 4, NBUF_TAU = 2;
+constexpr int NW_OUT = 4, NBUF_OUT = 2;
+constexpr int NW_DQ = 2, NBUF_DQ = 2;
+constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
+
+inline int alpha_mode(float alpha) {
+    if (alpha == 1.5f) return ALPHA_15;
+    if (alpha == 2.0f) return ALPHA_20;
+    return ALPHA_GEN;
+}
+
+#define EA_HIP(expr)                                              \
+    do {                                                          \
+        hipError_t e_ = (expr);                                   \
+        if (e_ != hipSuccess) { set_last_hip_error((int)e_); return EA_ERR_HIP; } \
+    } while (0)
+
+template <class K>
+int launch(K kernel, dim3 grid, int threads, hipStream_t s, Params p) {
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), 0, s, p);   // all LDS is static
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
+template <class Ein, class Eout>
+int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, hipStream_t s) {
+    hipLaunchKernelGGL((convert_kernel<Ein, Eout>), dim3(2048), dim3(256), 0, s, (const typename Ein::elem*)in,
+                       (typename Eout::elem*)out, n, amax_bits);
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
+// E: input element type; E2: element type of every second-stage product and of the whole backward
+// (for bf16 inputs: fp16; the copies are made by convert_kernel)
+template <class E, class E2, int D, int AM>
+struct Ops {
+    static constexpr bool COPY = !std::is_same<E, E2>::value;
+    static int fwd(Params p, hipStream_t s) {
+        int rc;
+        {
+            ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
+            if (COPY) {
+                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr, s);
+                if (rc) return rc;
+            }
+        }
+        {
+            ScopedKernelTime t(EA_TIMER_TAU, s);
+            rc = launch(tau_kernel<E, D, QB, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64, s, p);
+            if (rc) return rc;
+        }
+        ScopedKernelTime t(EA_TIMER_OUT, s);
+        return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
+    }
+    static dim3 groups(const Params& p, int nw) {
+        const int rows = 32 * QB * nw;
+        return dim3(p.BH * ((p.N + rows - 1) / rows));
+    }
+    // `copies`: workspace room for K, Q, V, dO in E2 (used when COPY)
+    static int bwd(Params p, bool rebuild_mask, void* const copies[4], hipStream_t s) {
+        int rc;
+        if (rebuild_mask) {
+            ScopedKernelTime t(EA_TIMER_MASK, s);
+            hipLaunchKernelGGL(full_mask_kernel, dim3(256), dim3(256), 0, s, p.wmask, p.BH, p.T, p.W, p.causal);
+            EA_HIP(hipGetLastError());
+            rc = launch(out_kernel<E, E2, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
+            if (rc) return rc;
+        }
+        {
+            ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
+            if (E2::SCALED) {
+                hipLaunchKernelGGL((amax_kernel<E>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
+                                   (long)p.BH * p.N * D, p.scal);
+                EA_HIP(hipGetLastError());
+            }
+            if (COPY) {
+                const long n = (long)p.BH * p.N * D;
+                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, s))) return rc;
+                p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
+            }
+        }
+        {
+            ScopedKernelTime t(EA_TIMER_DQ, s);
+            rc = launch(dq_kernel<E2, E2, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64, s, p);
+            if (rc) return rc;
+        }
+        ScopedKernelTime t(EA_TIMER_DKDV, s);
+        constexpr int NB2 = (E2::EPL == 8) ? NBUF_DKDV : 1;     // fp32 tiles are twice as large
+        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
+    }
+};
+
+template <class E, class E2, int D>
+int dispatch_alpha(bool is_bwd, Params p, bool rebuild, void* const copies[4], hipStream_t s) {
+    switch (alpha_mode(p.alpha)) {
+        case ALPHA_15: return is_bwd ? Ops<E, E2, D, ALPHA_15>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_15>::fwd(p, s);
+        case ALPHA_20: return is_bwd ? Ops<E, E2, D, ALPHA_20>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_20>::fwd(p, s);
+        default: return is_bwd ? Ops<E, E2, D, ALPHA_GEN>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_GEN>::fwd(p, s);
+    }
+}
+
+}  // namespace ea
