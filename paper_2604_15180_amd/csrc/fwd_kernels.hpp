@@ -11,17 +11,20 @@
 
 namespace ea {
 
-// ---- histogram solve (App. C.3), one thread per row, centred units ------------------------
-// Returns the root tau_h of f_h(tau) = -1 + sum_k H_k [k/NB - tau]_+^r  (Eq. 9).
-template <int AM, int NB>
-EA_DEV float solve_histogram(const uint32_t* H, float r) {
-    constexpr float h = 1.f / NB;
+// ---- histogram solve (App. C.3), one thread per row ------------------------------------------
+// The row's histogram is a window of SLOTS consecutive bins of an absolute grid of width h,
+// kept in a circular buffer: bin k of the window (left edge k h above the window's origin) is
+// H[(rot + k) % SLOTS].  Returns the root tau_h of f_h(tau) = -1 + sum_k H_k [k h - tau]_+^r
+// (Eq. 9) in units above the origin; -h for an empty histogram.
+template <int AM, int SLOTS>
+EA_DEV float solve_histogram(const uint32_t* H, int rot, float h, float r) {
+    auto count = [&](int k) { return (float)H[(rot + k) & (SLOTS - 1)]; };
     if constexpr (AM == ALPHA_15 || AM == ALPHA_20) {
         // descending scan keeping S0, S1, S2 of the active bins; the active set is the largest
         // one whose closed-form root lies below the left edge of its lowest non-empty bin
         float S0 = 0.f, S1 = 0.f, S2 = 0.f, best = -h;
-        for (int k = NB - 1; k >= 0; --k) {
-            const float cnt = (float)H[k];
+        for (int k = SLOTS - 1; k >= 0; --k) {
+            const float cnt = count(k);
             if (cnt == 0.f) continue;
             const float e = k * h;
             S0 += cnt; S1 += cnt * e; S2 += cnt * e * e;
@@ -37,14 +40,14 @@ EA_DEV float solve_histogram(const uint32_t* H, float r) {
         }
         return best;
     } else {
-        // general alpha: bisection of f_h on [-h, (NB-1)/NB], then Newton from the left end
+        // general alpha: bisection of f_h on [-h, (SLOTS-1) h], then Newton from the left end
         // (f_h is convex and decreasing for alpha <= 2, so Newton from the left is monotone)
         auto eval = [&](float tau, float& f1) {
             float f = -1.f; f1 = 0.f;
-            for (int k = NB - 1; k >= 0; --k) {
+            for (int k = SLOTS - 1; k >= 0; --k) {
                 const float y = k * h - tau;
                 if (y <= 0.f) break;
-                const float cnt = (float)H[k];
+                const float cnt = count(k);
                 if (cnt == 0.f) continue;
                 const float pr1 = pow_r1<AM>(y, r);
                 f += cnt * pr1 * y;
@@ -52,7 +55,7 @@ EA_DEV float solve_histogram(const uint32_t* H, float r) {
             }
             return f;
         };
-        float lo = -h, hi = (NB - 1) * h, d1;
+        float lo = -h, hi = (SLOTS - 1) * h, d1;
         for (int i = 0; i < 12; ++i) {
             const float mid = 0.5f * (lo + hi);
             if (eval(mid, d1) >= 0.f) lo = mid; else hi = mid;
@@ -134,7 +137,12 @@ template <class E, int D, int QB, int NB, int NW, int NBUF>
 struct TauSmem {
     static constexpr int BR = 32 * QB * NW;
     static constexpr int MR = (BR + 63) / 64;
-    static constexpr int HIST_WORDS = BR * (NB + 1);
+    // A row's histogram: NB bins per unit of (alpha-1) s on an absolute grid, of which the NB+1
+    // bins that reach from one unit below the running maximum up to it are live, in a circular
+    // buffer of SLOTS = NB+1 words (a power of two, so NB = 63).
+    static constexpr int SLOTS = NB + 1;
+    static_assert((SLOTS & (SLOTS - 1)) == 0 && SLOTS * 4 <= 256, "circular index is taken with a byte mask");
+    static constexpr int HIST_WORDS = BR * SLOTS;
 };
 
 template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
@@ -143,13 +151,13 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     using KT = RowTile<E, D>;
     constexpr int THREADS = NW * 64;
     using elem = typename E::elem;
-    constexpr int BR = SM::BR, MR = SM::MR;
+    constexpr int BR = SM::BR, MR = SM::MR, SLOTS = SM::SLOTS;
     // All LDS is static, and the two K buffers are separate variables (see stream_tiles).
     __shared__ __align__(1024) char kbuf[KT::BYTES];
     __shared__ __align__(1024) char kbuf_b[NBUF == 2 ? KT::BYTES : 1024];
-    __shared__ uint32_t hist[SM::HIST_WORDS];
+    __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
     __shared__ float rs_base[BR], rs_thr[BR], rs_lo[BR], rs_hi[BR], rs_F[BR], rs_G[BR], rs_H[BR];
-    __shared__ int rs_done[BR], rs_iters[BR];
+    __shared__ int rs_alo[BR], rs_done[BR], rs_iters[BR];
     __shared__ uint32_t wm[MR * MAX_W];
     __shared__ uint32_t cand[MR * MAX_W];
     __shared__ int tl[MAX_T];
@@ -186,90 +194,128 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
         ++ntile_done;
     };
 
-    // ---- Phase 1: row maximum -----------------------------------------------------------
-    float rmax[QB];
+    // ---- Phases 1 and 2 in one dense sweep: row maximum and histogram -------------------------
+    // The histogram of Eq. 7-8 is centred on the row maximum, which a single sweep only knows at
+    // its end.  Here the bins lie on an absolute grid instead (bin a holds NB x in [a, a+1), x =
+    // (alpha-1) s), and a row keeps the window of bins from one unit below its running maximum
+    // up to it: every score that can exceed tau* >= max - 1 (Eq. 5) is inside the window when it
+    // is met, and stays inside as the maximum grows.  Prop. 1 only uses that a bin's left edge is
+    // at most h below its scores, so its bounds hold on this grid as well.  When the maximum
+    // moves up by k bins, the k slots that pass from the bottom of the window to its top are
+    // cleared (by the row's first lane; LDS operations of one wave execute in program order).
+    //
+    // A score's slot, times 4, is the integer part of rel = 4 NB c s + k4 taken modulo 256, with
+    // k4 = 4 (rot - a_lo): a_lo is the window's lowest bin and rot = a_lo mod SLOTS its slot.
+    // The score is inside the window iff rel >= 4 rot.
+    const float cb = c * NB, c4 = 4.f * cb;
+    float run[QB], k4[QB], thr4[QB];
+    int a_top[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) rmax[qb] = -INFINITY;
+    for (int qb = 0; qb < QB; ++qb) { run[qb] = -INFINITY; k4[qb] = 0.f; thr4[qb] = INFINITY; a_top[qb] = INT_MIN; }
     // Besides the running maximum, every (row, key tile) maximum goes to HBM (fp16, rounded up):
-    // once the row maxima are final, only tiles holding a score within 1 of its row's maximum
-    // (in (alpha-1) s units, Eq. 5-6) can matter to the histogram, to f, or to P.
+    // once tau_0 is known, only tiles holding a score above it can matter to f or to P.
     stream_tiles<NBUF>(njt, kbuf, kbuf1, issue_seq, [&](int j, const char* buf) {
         if (j >= wjt) return;
         scores(j, buf);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            float lm = -INFINITY;
+            float gm[4];                            // maxima of the four groups of 8 registers
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int g = 0; g < 4; ++g) {
+                gm[g] = C[g >> 1][qb][8 * (g & 1)];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) lm = fmaxf(lm, C[kb][qb][v]);
-            rmax[qb] = fmaxf(rmax[qb], lm);
+                for (int v = 1; v < 8; ++v) gm[g] = fmaxf(gm[g], C[g >> 1][qb][8 * (g & 1) + v]);
+            }
+            const float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
             const float tm = xhalf_max(lm);
             if (h == 0) tmax_g[(long)j * N + qw0 + 32 * qb + n] = (_Float16)(tm + fabsf(tm) * (1.f / 1024.f) + 1e-7f);
+            const int row0 = wave * 32 * QB + 32 * qb;
+            char* hrow = (char*)(hist + (row0 + n) * SLOTS);
+            const bool rise = tm > run[qb];
+            if (__any(rise)) {                      // some row's maximum moves up
+                int first = 0, last = -1;           // bins to clear: first..last (none)
+                if (rise) {
+                    run[qb] = tm;
+                    int nt = (int)floorf(fminf(fmaxf(cb * tm, -1e9f), 1e9f));
+                    int a_lo = nt - (SLOTS - 1), rot = a_lo & (SLOTS - 1);
+                    float kk = 4.f * (float)(rot - a_lo);
+                    // the maximum itself must land in the window's top slot, not wrap past it
+                    if ((int)fmaf(c4, tm, kk) >= 4 * rot + 4 * SLOTS) {
+                        nt += 1; a_lo += 1; rot = a_lo & (SLOTS - 1); kk = 4.f * (float)(rot - a_lo);
+                    }
+                    if (a_top[qb] != INT_MIN) { first = max(a_top[qb], nt - SLOTS) + 1; last = nt; }
+                    a_top[qb] = nt; k4[qb] = kk; thr4[qb] = 4.f * (float)rot;
+                }
+                // the whole wave clears the slots of one rising row at a time: lane i takes slot i
+                unsigned long long todo = __ballot(h == 0 && last >= first);
+                while (todo) {
+                    const int src = __ffsll((long long)todo) - 1;
+                    todo &= todo - 1;
+                    const int f0 = __builtin_amdgcn_readlane(first, src);
+                    const int cnt = __builtin_amdgcn_readlane(last - first, src);
+                    if (((lane - f0) & (SLOTS - 1)) <= cnt) hist[(row0 + src) * SLOTS + lane] = 0u;
+                }
+            }
+            if (__any(fmaf(c4, lm, k4[qb]) >= thr4[qb])) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    if (!__any(fmaf(c4, gm[g], k4[qb]) >= thr4[qb])) continue;
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) {
+                        const float rel = fmaf(c4, C[g >> 1][qb][8 * (g & 1) + v], k4[qb]);
+                        if (rel >= thr4[qb]) atomicAdd((uint32_t*)(hrow + ((int)rel & (4 * SLOTS - 4))), 1u);
+                    }
+                }
+            }
         }
     });
-    float base[QB];   // m - 1 in raw units: z = x - base (Eq. 6)
+    // tau_0 = max(tau_h, max - 1) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1, Eq. 5), raw units
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        rmax[qb] = xhalf_max(rmax[qb]);
-        base[qb] = fmaf(c, rmax[qb], -1.f);
-        if (h == 0) rs_base[wave * 32 * QB + 32 * qb + n] = base[qb];
-    }
-    // candidate tiles of this wave's rows: lanes 0-31 test tile j0, lanes 32-63 tile j0+1
-    __threadfence();
-    for (int j0 = 0; j0 < wjt; j0 += 2) {
-        const int j = j0 + h;
-        bool cnd = false;
-        if (j < wjt) {
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-                cnd |= fmaf(c, (float)tmax_g[(long)j * N + qw0 + 32 * qb + n], -base[qb]) >= 0.f;
+    for (int qb = 0; qb < QB; ++qb)
+        if (h == 0) {
+            rs_base[wave * 32 * QB + 32 * qb + n] = fmaf(c, run[qb], -1.f);
+            rs_alo[wave * 32 * QB + 32 * qb + n] = a_top[qb] == INT_MIN ? 0 : a_top[qb] - (SLOTS - 1);
         }
-        const unsigned long long bal = __ballot(cnd);
-        if (lane == 0) {
-            if (bal & 0xffffffffull) atomicOr(&cand[myrow * W + (j0 >> 5)], 1u << (j0 & 31));
-            if (bal >> 32) atomicOr(&cand[myrow * W + ((j0 + 1) >> 5)], 1u << ((j0 + 1) & 31));
+    __syncthreads();
+    if (tid < BR) {
+        constexpr float hb = 1.f / NB;
+        const int a_lo = rs_alo[tid];
+        const float origin = (float)a_lo * hb;                        // left edge of the window
+        const float tau_h = solve_histogram<AM, SLOTS>(hist + tid * SLOTS, a_lo & (SLOTS - 1), hb, r) + origin;
+        const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
+        const float t0 = fmaxf(tau_h - slack, rs_base[tid]);
+        rs_thr[tid] = t0;
+        rs_lo[tid] = t0;
+        rs_hi[tid] = tau_h + hb + slack;
+        rs_done[tid] = (q0 + tid < N) ? 0 : 1;
+        rs_iters[tid] = 0;
+    }
+    __syncthreads();
+    // candidate tiles of this wave's rows, those holding a score above tau_0: lanes 0-31 test
+    // tile j0, lanes 32-63 tile j0+1
+    {
+        float t0[QB];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) t0[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
+        __threadfence();
+        for (int j0 = 0; j0 < wjt; j0 += 2) {
+            const int j = j0 + h;
+            bool cnd = false;
+            if (j < wjt) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    cnd |= fmaf(c, (float)tmax_g[(long)j * N + qw0 + 32 * qb + n], -t0[qb]) >= 0.f;
+            }
+            const unsigned long long bal = __ballot(cnd);
+            if (lane == 0) {
+                if (bal & 0xffffffffull) atomicOr(&cand[myrow * W + (j0 >> 5)], 1u << (j0 & 31));
+                if (bal >> 32) atomicOr(&cand[myrow * W + ((j0 + 1) >> 5)], 1u << ((j0 + 1) & 31));
+            }
         }
     }
     __syncthreads();
     build_tile_list(cand, MR, W, tl, tl_count, tid);
     auto issue_list = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
-
-    // ---- Phase 2: per-row histogram of the centred scores in LDS (Eq. 7-8) ---------------
-    stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) {
-        const int j = tl[it];
-        if (!mask_bit(cand, W, myrow, j)) return;
-        scores(j, buf);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            float lmax = -INFINITY;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) lmax = fmaxf(lmax, C[kb][qb][v]);
-            if (__any(fmaf(c, lmax, -base[qb]) >= 0.f)) {
-                uint32_t* hrow = hist + (wave * 32 * QB + 32 * qb + n) * (NB + 1);
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float z = fmaf(c, C[kb][qb][v], -base[qb]);
-                        if (z >= 0.f) atomicAdd(&hrow[min((int)(z * NB), NB - 1)], 1u);
-                    }
-            }
-        }
-    });
-    // tau_0 = max(tau_h, 0) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1), in raw units
-    if (tid < BR) {
-        const float tau_h = solve_histogram<AM, NB>(hist + tid * (NB + 1), r);
-        const float t0 = fmaxf(tau_h - 1e-6f, 0.f);
-        rs_thr[tid] = t0 + rs_base[tid];
-        rs_lo[tid] = t0 + rs_base[tid];
-        rs_hi[tid] = tau_h + 1.f / NB + 1e-6f + rs_base[tid];
-        rs_done[tid] = (q0 + tid < N) ? 0 : 1;
-        rs_iters[tid] = 0;
-    }
-    __syncthreads();
 
     // ---- Phase 3: refinement sweeps; the first also records the working mask --------------
     int nsweeps = 0;

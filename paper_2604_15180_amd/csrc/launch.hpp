@@ -9,7 +9,7 @@
 
 namespace ea {
 
-constexpr int NBINS = 64;    // histogram bins B (Sec. 3.1): bracket width 1/64 after Phase 2
+constexpr int NBINS = 63;    // histogram bins B per unit (Sec. 3.1): bracket width 1/63 after the histogram solve
 constexpr int MAX_SWEEPS = 12;
 
 void set_last_hip_error(int e);
