@@ -55,6 +55,26 @@ def gaussian_qkv(B, H, N, d, dtype, sigma, seed, block_rho=0.0, block=64):
     return tuple(_finish(t, dtype) for t in (q, k, v, do))
 
 
+def ramp_qkv(B, H, N, d, dtype, rise_per_tile, seed, noise=0.3, block=64):
+    """Keys whose similarity to every query drifts with the key index: all queries share a
+    direction u (plus noise), key j carries t_j u (plus noise) with t_j linear in j, so that
+    (alpha-1) s at alpha = 1.5 moves by `rise_per_tile` per 64 keys.  Positive: each row's
+    running maximum keeps climbing as keys stream by; negative: it is met at the first keys.
+    Not a workload of the paper; it drives a single-sweep maximum through many updates."""
+    g = _gen(seed)
+    u = torch.randn(B, H, 1, d, generator=g)
+    u = u / u.norm(dim=-1, keepdim=True)
+    q = math.sqrt(d) * u + noise * torch.randn(B, H, N, d, generator=g)
+    slope = 2.0 * rise_per_tile / block
+    t = slope * torch.arange(N, dtype=torch.float32).view(1, 1, N, 1)
+    if rise_per_tile < 0:
+        t = t - t.min()
+    k = t * u + noise * torch.randn(B, H, N, d, generator=g)
+    v = torch.randn(B, H, N, d, generator=g)
+    do = torch.randn(B, H, N, d, generator=g)
+    return tuple(_finish(x, dtype) for x in (q, k, v, do))
+
+
 def planted_qkv(B, H, N, d, dtype, sigma, seed, n_planted=32, strength=None, block=64):
     """Long-context recipe: Gaussian Q, K plus, for every 64-row query tile I > 0, a unit
     direction g_I added (scaled by `a`) to all 64 query rows and to `n_planted` key rows
