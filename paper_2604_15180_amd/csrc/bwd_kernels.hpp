@@ -129,9 +129,13 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
                         S[kb][qb][v] = t;
                         dP[kb][qb][v] = u;
                     }
-            stage2<E2, D, QB>(XA, kbuf, S, lane);
-            stage2<E2, D, QB>(XB, kbuf, dP, lane);
+            stage2<E2, D, QB, true>(XA, kbuf, S, lane);
+            stage2<E2, D, QB, true>(XB, kbuf, dP, lane);
         });
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) { settle_acc(XA[db][qb]); settle_acc(XB[db][qb]); }
 
     // delta (in units of max|dO|) for the dK/dV kernel, and the combination of the two sums
 #pragma unroll
@@ -247,12 +251,12 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     stream_tiles<NBUF>(
         ntl, set0, NBUF == 2 ? set1 : set0,
         [&](int it, char* b) {
-            const long i = tl[it] & 0xffff;
+            const long i = __builtin_amdgcn_readfirstlane(tl[it] & 0xffff);
             issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
             // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
-            if (wave == 0) load4_to_lds(p.tau + (long)bh * N + i * 64 + lane, b + VEC_OFF);
-            if (wave == 1) load4_to_lds(p.delta + (long)bh * N + i * 64 + lane, b + VEC_OFF + 4 * TILE);
+            if (wave == 0) load4_to_lds(p.tau + ((long)bh * N + i * 64) + (uint32_t)lane, b + VEC_OFF);
+            if (wave == 1) load4_to_lds(p.delta + ((long)bh * N + i * 64) + (uint32_t)lane, b + VEC_OFF + 4 * TILE);
         },
         [&](int it, const char* qbuf) {
             const int ent = tl[it];
@@ -288,9 +292,13 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
                         }
                     }
                 }
-            stage2<E2, D, QB>(XV, gbuf, S, lane);
-            stage2<E2, D, QB>(XK, qbuf, dP, lane);
+            stage2<E2, D, QB, true>(XV, gbuf, S, lane);
+            stage2<E2, D, QB, true>(XK, qbuf, dP, lane);
         });
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) { settle_acc(XV[db][qb]); settle_acc(XK[db][qb]); }
     if (active) {
         store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
         store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax, lane);

@@ -41,6 +41,7 @@ struct Bf16 {
     static EA_DEV f32x16 mma(frag a, frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
+    static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
     static EA_DEV elem from_float(float x) { return (__bf16)x; }
 };
 struct F16 {
@@ -53,6 +54,16 @@ struct F16 {
     static EA_DEV f32x16 mma(frag a, frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
     }
+    // c += a b with the accumulator pinned to the accumulation registers (AGPRs).  The long-lived
+    // stage-2 accumulators are touched by nothing but these MFMAs until the kernel's epilogue;
+    // pinned there they cost no vector registers and no copies, which leaves the 256 ordinary
+    // registers to the operands the vector ALUs work on.  The compiler does not know that this
+    // statement is an MFMA, so what it would otherwise schedule around one is spelled out: two
+    // idle cycles ahead of it (operands written by the vector ALU just before), and
+    // settle_acc() before anything else reads the accumulator.
+    static EA_DEV void mma_acc(frag a, frag b, f32x16& c) {
+        asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    }
     static EA_DEV elem from_float(float x) { return (_Float16)x; }
 };
 struct F32 {
@@ -64,8 +75,12 @@ struct F32 {
     static EA_DEV f32x16 mma(frag a, frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
     }
+    static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
     static EA_DEV elem from_float(float x) { return x; }
 };
+
+// After the last mma_acc on `c` and before its first other use: outlasts the MFMA pipeline.
+EA_DEV void settle_acc(f32x16& c) { asm volatile("s_nop 15\n\ts_nop 7" : "+a"(c)); }
 
 // tile row held by accumulator register v (0..15) of block kb in lane half h
 EA_DEV int trow(int kb, int v, int h) { return 32 * kb + 16 * (v >> 3) + 8 * h + (v & 7); }
@@ -120,12 +135,18 @@ template <class E, int D, int NW>
 EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave, int lane) {
     using L = RowTile<E, D>;
     static_assert(L::NINST % NW == 0, "loads must divide evenly over the waves");
-    const char* base = (const char*)g + row0 * (long)L::ROW_BYTES;
+    // scalar 64-bit base + unsigned 32-bit lane offset: the form the load takes without any
+    // 64-bit vector address arithmetic (the tile's first row is the same for all lanes)
+    const char* base = (const char*)g + (long)__builtin_amdgcn_readfirstlane((int)row0) * L::ROW_BYTES;
 #pragma unroll
     for (int i = 0; i < L::NINST / NW; ++i) {
         const int t = i * NW + wave;              // wave is wave-uniform (an SGPR)
         const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
-        load16_to_lds(base + row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16), lds + t * 1024);
+        uint32_t off = (uint32_t)(row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16));
+        // keep the widening of `off` next to the load: hoisted out of a loop as a 64-bit value it
+        // would cost a 64-bit vector add per load
+        asm volatile("" : "+v"(off));
+        load16_to_lds(base + off, lds + t * 1024);
     }
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
@@ -211,7 +232,7 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
 // m = 16(g%2)..+15 (tile columns 32db+m) of lane half h = g/2, whose contraction slots t = 0..7
 // are tile rows R+t, R = 32kb+16s2+8h.  Lane r = 4e+q passes &tile[R+e][32db+16(g%2)+4q], so lane
 // i receives tile[R+0..3][32db+m]: slots 0..3.  A second read from rows R+4.. gives slots 4..7.
-template <class E2, int D, int QB>
+template <class E2, int D, int QB, bool PINNED = false>
 EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tile, const f32x16 (&Y)[2][QB], int lane) {
     using L = RowTile<E2, D>;
     constexpr int ES = (int)sizeof(typename E2::elem);
@@ -244,7 +265,10 @@ EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tile, const f32x16 (
                     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     const typename E2::frag a = __builtin_bit_cast(typename E2::frag, both);
 #pragma unroll
-                    for (int qb = 0; qb < QB; ++qb) X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
+                    for (int qb = 0; qb < QB; ++qb) {
+                        if constexpr (PINNED) E2::mma_acc(a, b[qb], X[db][qb]);
+                        else X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
+                    }
                 }
             }
     } else {
