@@ -263,12 +263,13 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
 #pragma unroll
                     for (int v = 0; v < 8; ++v) {
                         const float rel = fmaf(c4, C[g >> 1][qb][8 * (g & 1) + v], k4[qb]);
-                        if (rel >= thr4[qb]) atomicAdd((uint32_t*)(hrow + ((int)rel & (4 * SLOTS - 4))), 1u);
+                        if (rel >= thr4[qb]) lds_inc_u32(hrow + ((int)rel & (4 * SLOTS - 4)));
                     }
                 }
             }
         }
     });
+    lds_settle();
     // tau_0 = max(tau_h, max - 1) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1, Eq. 5), raw units
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -291,25 +292,37 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
         rs_iters[tid] = 0;
     }
     __syncthreads();
-    // candidate tiles of this wave's rows, those holding a score above tau_0: lanes 0-31 test
-    // tile j0, lanes 32-63 tile j0+1
+    // candidate tiles of this wave's rows: those holding a score above tau_0.  64 tiles per
+    // round: lane (n, h) looks at tiles j0 + 2u + h, u = 0..31, of row n, with all 32 loads in
+    // flight together (one load at a time would string up to T/2 memory round trips).
     {
         float t0[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) t0[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
         __threadfence();
-        for (int j0 = 0; j0 < wjt; j0 += 2) {
-            const int j = j0 + h;
-            bool cnd = false;
-            if (j < wjt) {
+        for (int j0 = 0; j0 < wjt; j0 += 64) {
+            _Float16 tm[32][QB];
 #pragma unroll
-                for (int qb = 0; qb < QB; ++qb)
-                    cnd |= fmaf(c, (float)tmax_g[(long)j * N + qw0 + 32 * qb + n], -t0[qb]) >= 0.f;
+            for (int u = 0; u < 32; ++u) {
+                const int j = min(j0 + 2 * u + h, wjt - 1);        // clamped: tested against wjt below
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) tm[u][qb] = tmax_g[(long)j * N + qw0 + 32 * qb + n];
             }
-            const unsigned long long bal = __ballot(cnd);
+            unsigned long long bits = 0;
+#pragma unroll
+            for (int u = 0; u < 32; ++u) {
+                bool cnd = false;
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) cnd |= fmaf(c, (float)tm[u][qb], -t0[qb]) >= 0.f;
+                cnd = cnd && (j0 + 2 * u + h < wjt);
+                const unsigned long long bal = __ballot(cnd);
+                if (bal & 0xffffffffull) bits |= 1ull << (2 * u);
+                if (bal >> 32) bits |= 1ull << (2 * u + 1);
+            }
             if (lane == 0) {
-                if (bal & 0xffffffffull) atomicOr(&cand[myrow * W + (j0 >> 5)], 1u << (j0 & 31));
-                if (bal >> 32) atomicOr(&cand[myrow * W + ((j0 + 1) >> 5)], 1u << ((j0 + 1) & 31));
+                const int w0 = j0 >> 5;
+                if ((uint32_t)bits) atomicOr(&cand[myrow * W + w0], (uint32_t)bits);
+                if (bits >> 32) atomicOr(&cand[myrow * W + w0 + 1], (uint32_t)(bits >> 32));
             }
         }
     }
