@@ -16,9 +16,13 @@ namespace ea {
 // kept in a circular buffer: bin k of the window (left edge k h above the window's origin) is
 // H[(rot + k) % SLOTS].  Returns the root tau_h of f_h(tau) = -1 + sum_k H_k [k h - tau]_+^r
 // (Eq. 9) in units above the origin; -h for an empty histogram.
-template <int AM, int SLOTS>
-EA_DEV float solve_histogram(const uint32_t* H, int rot, float h, float r) {
-    auto count = [&](int k) { return (float)H[(rot + k) & (SLOTS - 1)]; };
+template <int AM, int SLOTS, int BITS>
+EA_DEV float solve_histogram(const uint32_t* H, int rot, int shift, float h, float r) {
+    // counters of BITS bits at bit `shift` of each word (two rows share a word when BITS == 16)
+    auto count = [&](int k) {
+        const uint32_t w = H[(rot + k) & (SLOTS - 1)] >> shift;
+        return (float)(BITS == 32 ? w : (w & ((1u << (BITS & 31)) - 1u)));
+    };
     if constexpr (AM == ALPHA_15 || AM == ALPHA_20) {
         // descending scan keeping S0, S1, S2 of the active bins; the active set is the largest
         // one whose closed-form root lies below the left edge of its lowest non-empty bin
@@ -142,7 +146,12 @@ struct TauSmem {
     // buffer of SLOTS = NB+1 words (a power of two, so NB = 63).
     static constexpr int SLOTS = NB + 1;
     static_assert((SLOTS & (SLOTS - 1)) == 0 && SLOTS * 4 <= 256, "circular index is taken with a byte mask");
-    static constexpr int HIST_WORDS = BR * SLOTS;
+    // QB == 2: the two rows of a lane (n and n + 32 of its wave) share the words of one buffer,
+    // 16 bits each, so the histograms of 256 rows take the LDS of 128; a bin then holds up to
+    // 65535 keys, which the host guarantees by using this variant only while N < 65536.
+    static_assert(QB == 1 || QB == 2, "one or two rows per lane");
+    static constexpr int CBITS = 32 / QB;
+    static constexpr int HIST_WORDS = 32 * NW * SLOTS;
 };
 
 template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
@@ -156,8 +165,6 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     __shared__ __align__(1024) char kbuf[KT::BYTES];
     __shared__ __align__(1024) char kbuf_b[NBUF == 2 ? KT::BYTES : 1024];
     __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
-    __shared__ float rs_base[BR], rs_thr[BR], rs_lo[BR], rs_hi[BR], rs_F[BR], rs_G[BR], rs_H[BR];
-    __shared__ int rs_alo[BR], rs_done[BR], rs_iters[BR];
     __shared__ uint32_t wm[MR * MAX_W];
     __shared__ uint32_t cand[MR * MAX_W];
     __shared__ int tl[MAX_T];
@@ -230,7 +237,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             const float tm = xhalf_max(lm);
             if (h == 0) tmax_g[(long)j * N + qw0 + 32 * qb + n] = (_Float16)(tm + fabsf(tm) * (1.f / 1024.f) + 1e-7f);
             const int row0 = wave * 32 * QB + 32 * qb;
-            char* hrow = (char*)(hist + (row0 + n) * SLOTS);
+            char* hrow = (char*)(hist + (wave * 32 + n) * SLOTS);
             const bool rise = tm > run[qb];
             if (__any(rise)) {                      // some row's maximum moves up
                 int first = 0, last = -1;           // bins to clear: first..last (none)
@@ -253,7 +260,11 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
                     todo &= todo - 1;
                     const int f0 = __builtin_amdgcn_readlane(first, src);
                     const int cnt = __builtin_amdgcn_readlane(last - first, src);
-                    if (((lane - f0) & (SLOTS - 1)) <= cnt) hist[(row0 + src) * SLOTS + lane] = 0u;
+                    if (((lane - f0) & (SLOTS - 1)) <= cnt) {
+                        uint32_t* word = hist + (wave * 32 + src) * SLOTS + lane;
+                        if constexpr (QB == 1) *word = 0u;
+                        else lds_and_b32(word, qb == 0 ? 0xffff0000u : 0x0000ffffu);
+                    }
                 }
             }
             if (__any(fmaf(c4, lm, k4[qb]) >= thr4[qb])) {
@@ -263,42 +274,46 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
 #pragma unroll
                     for (int v = 0; v < 8; ++v) {
                         const float rel = fmaf(c4, C[g >> 1][qb][8 * (g & 1) + v], k4[qb]);
-                        if (rel >= thr4[qb]) lds_inc_u32(hrow + ((int)rel & (4 * SLOTS - 4)));
+                        if (rel >= thr4[qb]) lds_add_u32(hrow + ((int)rel & (4 * SLOTS - 4)), 1u << (SM::CBITS * qb & 31));
                     }
                 }
             }
         }
     });
     lds_settle();
-    // tau_0 = max(tau_h, max - 1) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1, Eq. 5), raw units
-#pragma unroll
-    for (int qb = 0; qb < QB; ++qb)
-        if (h == 0) {
-            rs_base[wave * 32 * QB + 32 * qb + n] = fmaf(c, run[qb], -1.f);
-            rs_alo[wave * 32 * QB + 32 * qb + n] = a_top[qb] == INT_MIN ? 0 : a_top[qb] - (SLOTS - 1);
-        }
-    __syncthreads();
-    if (tid < BR) {
+    // tau_0 = max(tau_h, max - 1) and the bracket [tau_0, tau_h + 1/NB] (Prop. 1, Eq. 5), raw units.
+    // A wave reads only the histograms it filled itself: no barrier.  Lane (n, h) solves row block
+    // qb = h of row n (with one row per lane, lane half 0 does), then the two lanes of a row swap.
+    float thr[QB], blo[QB], bhi[QB];
+    {
         constexpr float hb = 1.f / NB;
-        const int a_lo = rs_alo[tid];
+        const int sq = (QB == 2) ? h : 0;
+        int top = a_top[0];
+        float mx = run[0];
+        if constexpr (QB == 2) { if (h) { top = a_top[1]; mx = run[1]; } }
+        const int a_lo = top == INT_MIN ? 0 : top - (SLOTS - 1);
         const float origin = (float)a_lo * hb;                        // left edge of the window
-        const float tau_h = solve_histogram<AM, SLOTS>(hist + tid * SLOTS, a_lo & (SLOTS - 1), hb, r) + origin;
+        const float tau_h = solve_histogram<AM, SLOTS, SM::CBITS>(hist + (wave * 32 + n) * SLOTS, a_lo & (SLOTS - 1),
+                                                                  SM::CBITS * sq & 31, hb, r) + origin;
         const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
-        const float t0 = fmaxf(tau_h - slack, rs_base[tid]);
-        rs_thr[tid] = t0;
-        rs_lo[tid] = t0;
-        rs_hi[tid] = tau_h + hb + slack;
-        rs_done[tid] = (q0 + tid < N) ? 0 : 1;
-        rs_iters[tid] = 0;
+        const float my_t0 = fmaxf(tau_h - slack, fmaf(c, mx, -1.f));
+        const float my_hi = tau_h + hb + slack;
+        const float o_t0 = __shfl_xor(my_t0, 32), o_hi = __shfl_xor(my_hi, 32);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const bool mine = (h == (QB == 2 ? qb : 0));
+            thr[qb] = mine ? my_t0 : o_t0;
+            blo[qb] = thr[qb];
+            bhi[qb] = mine ? my_hi : o_hi;
+        }
     }
-    __syncthreads();
     // candidate tiles of this wave's rows: those holding a score above tau_0.  64 tiles per
     // round: lane (n, h) looks at tiles j0 + 2u + h, u = 0..31, of row n, with all 32 loads in
     // flight together (one load at a time would string up to T/2 memory round trips).
     {
         float t0[QB];
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) t0[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
+        for (int qb = 0; qb < QB; ++qb) t0[qb] = thr[qb];
         __threadfence();
         for (int j0 = 0; j0 < wjt; j0 += 64) {
             _Float16 tm[32][QB];
@@ -331,71 +346,51 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     auto issue_list = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
 
     // ---- Phase 3: refinement sweeps; the first also records the working mask --------------
-    int nsweeps = 0;
-    for (int sweep = 0; sweep < 1; ++sweep) {     // later evaluations ride on Phase 4 (out_kernel)
-        ++nsweeps;
-        float thr[QB], F[QB], G[QB], Hs[QB];
+    // One evaluation of f, f', f'' at tau_0 over the candidate tiles and one safeguarded step;
+    // the tiles that hold a score above tau_0 form the working mask.  Later evaluations ride on
+    // Phase 4 (out_kernel).
+    {
+        float F[QB], G[QB], Hs[QB];
         int cnt[QB];      // number of scores above tau (alpha = 1.5: f'' sum; alpha = 2: f' sum)
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-            thr[qb] = rs_thr[wave * 32 * QB + 32 * qb + n];
-            F[qb] = G[qb] = Hs[qb] = 0.f;
-            cnt[qb] = 0;
-        }
-        const bool first = (sweep == 0);
-        auto body = [&](int j, const char* buf) {
-            if (!mask_bit(first ? cand : wm, W, myrow, j)) return;
+        for (int qb = 0; qb < QB; ++qb) { F[qb] = G[qb] = Hs[qb] = 0.f; cnt[qb] = 0; }
+        stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) {
+            const int j = tl[it];
+            if (!mask_bit(cand, W, myrow, j)) return;
             scores(j, buf);
             const bool hit = eval_scores<AM, QB>(C, thr, c, r, F, G, Hs, cnt);
-            if (first && hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
-        };
-        stream_tiles<NBUF>(*tl_count, kbuf, kbuf1, issue_list, [&](int it, const char* buf) { body(tl[it], buf); });
+            if (hit && lane == 0) atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31));
+        });
+        // threshold after this step, its bracket, f' at the point evaluated, and
+        // (iterations | done << 16), for the output kernel; both lanes of a row compute the same
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
             if constexpr (AM == ALPHA_20) G[qb] = (float)cnt[qb];
-            const float f = xhalf_sum(F[qb]), g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
-            if (h == 0) {
-                const int row = wave * 32 * QB + 32 * qb + n;
-                rs_F[row] = f; rs_G[row] = g; rs_H[row] = hs;
-            }
-        }
-        __syncthreads();
-        int pending = 0;
-        if (tid < BR && !rs_done[tid]) {
-            const float tau = rs_thr[tid];
-            const float f = rs_F[tid] - 1.f;
-            rs_iters[tid] += 1;
+            const float f = xhalf_sum(F[qb]) - 1.f, g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
             bool done = fabsf(f) <= p.tol;
+            float tau = thr[qb];
             if (!done) {
-                float lo = rs_lo[tid], hi = rs_hi[tid];
-                const float cand = hybrid_step(tau, f, rs_G[tid], rs_H[tid], r, p.alpha, lo, hi);
-                done = fabsf(cand - tau) < p.tol;
-                rs_thr[tid] = cand; rs_lo[tid] = lo; rs_hi[tid] = hi;
+                const float cand_tau = hybrid_step(tau, f, g, hs, r, p.alpha, blo[qb], bhi[qb]);
+                done = fabsf(cand_tau - tau) < p.tol;
+                tau = cand_tau;
             }
-            rs_done[tid] = done;
-            pending = !done;
+            if (active && h == 0) {
+                const long gi = (long)bh * N + qw0 + 32 * qb + n;
+                p.tau[gi] = tau;
+                p.rs_lo[gi] = blo[qb];
+                p.rs_hi[gi] = bhi[qb];
+                p.rs_state[gi] = 1 | ((int)done << 16);
+                p.rs_f1[gi] = -r * g;
+            }
         }
-        const int left = __syncthreads_count(pending);
-        if (left == 0) break;
     }
-
-    // ---- results ------------------------------------------------------------------------
-    // threshold after the sweeps run here, its bracket, and (iterations | done << 16): the output
-    // kernel evaluates f again while it forms O and finishes the rows that still need it
-    if (tid < BR && q0 + tid < N) {
-        const long g = (long)bh * N + q0 + tid;
-        p.tau[g] = rs_thr[tid];
-        p.rs_lo[g] = rs_lo[tid];
-        p.rs_hi[g] = rs_hi[tid];
-        p.rs_state[g] = rs_iters[tid] | (rs_done[tid] << 16);
-        p.rs_f1[g] = -r * rs_G[tid];          // f' at the point evaluated here
-    }
+    __syncthreads();
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
     {
         const int slot[2] = {0, 5};
-        const unsigned long long val[2] = {ntile_done * QB, wave == 0 ? (unsigned long long)nsweeps : 0ull};
+        const unsigned long long val[2] = {ntile_done * QB, wave == 0 ? 1ull : 0ull};
         flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
     }
 }

@@ -11,7 +11,7 @@ namespace ea {
 
 constexpr int QB = 1;        // 32*QB owned rows per wave
 // waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
-constexpr int NW_TAU = 4, NBUF_TAU = 2;
+constexpr int NW_TAU = 4, NBUF_TAU = 2, QB_TAU = 2;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
 constexpr int NW_DQ = 2, NBUF_DQ = 2;
 constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
@@ -59,14 +59,18 @@ struct Ops {
         }
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
-            rc = launch(tau_kernel<E, D, QB, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64, s, p);
+            // two rows per lane (packed 16-bit histogram counters) while a bin cannot overflow
+            if (QB_TAU == 2 && E::EPL == 8 && p.N < 65536)
+                rc = launch(tau_kernel<E, D, QB_TAU, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU, QB_TAU), NW_TAU * 64, s, p);
+            else
+                rc = launch(tau_kernel<E, D, 1, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64, s, p);
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
         return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
     }
-    static dim3 groups(const Params& p, int nw) {
-        const int rows = 32 * QB * nw;
+    static dim3 groups(const Params& p, int nw, int qb = QB) {
+        const int rows = 32 * qb * nw;
         return dim3(p.BH * ((p.N + rows - 1) / rows));
     }
     // `copies`: workspace room for K, Q, V, dO in E2 (used when COPY)

@@ -151,14 +151,18 @@ EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
 
-// LDS counter += 1 without a returned value.  Written as an instruction of its own because the
+// LDS word += v, &= v without a returned value.  Written as instructions of their own because the
 // compiler makes an LDS atomic wait for every direct global->LDS load in flight (it cannot tell
 // that they target another array), which would stall a histogram update until the next tile has
 // landed.  LDS operations of one wave execute in issue order; lds_settle() before other waves
 // read the counters.
-EA_DEV void lds_inc_u32(const void* p) {
+EA_DEV void lds_add_u32(const void* p, uint32_t v) {
     const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-    asm volatile("ds_add_u32 %0, %1" : : "v"(addr), "v"(1u) : "memory");
+    asm volatile("ds_add_u32 %0, %1" : : "v"(addr), "v"(v) : "memory");
+}
+EA_DEV void lds_and_b32(const void* p, uint32_t v) {
+    const uint32_t addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+    asm volatile("ds_and_b32 %0, %1" : : "v"(addr), "v"(v) : "memory");
 }
 EA_DEV void lds_settle() { __builtin_amdgcn_s_waitcnt(0xc07f); }   // lgkmcnt(0) only (gfx9 encoding)
 
