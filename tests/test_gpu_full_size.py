@@ -49,3 +49,33 @@ def test_c3_full_size_sampled_heads(ea, sigma):
         ref, info = parity.check_forward(qs, ks, vs, alpha, causal, O[sl], tau[sl], mask[sl], label=label)
         _, ginfo = parity.check_backward(qs, ks, vs, dos, alpha, causal, dQ[sl], dK[sl], dV[sl], label=label)
         print("  ", info, ginfo, flush=True)
+
+
+def test_c4_full_size_one_head(ea):
+    # configs[3]: B=1, H=8, N=65536, d=128, bf16, causal, sigma=3 plus planted keys.  N is past
+    # the range in which a 16-bit histogram counter cannot overflow, so this runs the kernel
+    # variant with one row per lane and 32-bit counters.
+    cfg = workloads.CONFIGS["c4_bf16_n64k"]
+    B, H, N, d, alpha, causal = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["alpha"], cfg["causal"]
+    print("case c4 full size", flush=True)
+    q, k, v, do = workloads.planted_qkv(B, H, N, d, "bf16", cfg["sigma"], seed=4001)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask)
+    torch.cuda.synchronize()
+    assert torch.isfinite(O).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all() and torch.isfinite(dV).all()
+    lhs = dV.double().sum(2)
+    rhs = do.double().sum(2).cuda()
+    assert (lhs - rhs).abs().max().item() < 1.0, (lhs - rhs).abs().max().item()
+    T = N // 64
+    bits = parity.unpack_mask(mask, T)
+    sparsity = 1.0 - bits.sum() / (B * H * T * (T + 1) / 2)
+    print("  block sparsity", sparsity, "mean iters", iters.float().mean().item(), flush=True)
+    assert sparsity > 0.9
+    assert iters.max().item() <= 12
+    sl = (slice(0, 1), slice(5, 6))
+    qs, ks, vs, dos = (t[sl] for t in (q, k, v, do))
+    print("  oracle on head (0,5)", flush=True)
+    ref, info = parity.check_forward(qs, ks, vs, alpha, causal, O[sl], tau[sl], mask[sl], label="c4 head=(0,5)")
+    _, ginfo = parity.check_backward(qs, ks, vs, dos, alpha, causal, dQ[sl], dK[sl], dV[sl], label="c4 head=(0,5)")
+    print("  ", info, ginfo, flush=True)
