@@ -24,6 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak (published)
+# HBM bytes per launch (fetched + written) on the default workload, from the FETCH_SIZE / WRITE_SIZE
+# passes summarised in profiles/bench_c3_n16k_counters.md (scaled by the library's own copy kernel)
+HBM_TRAFFIC_BYTES = {"tau": 1.04e9, "out": 1.29e9, "dq": 1.78e9, "dkdv": 1.60e9}
 METRIC = "effective fwd+bwd TFLOP/s vs block sparsity at N=16k; mean τ iterations/row"
 
 
@@ -158,7 +161,9 @@ def main():
     dom_flops_per_launch = exec_total[dom] / len(points)
     achieved = dom_flops_per_launch / (dom_avg_ms * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dom + "_kernel", achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4), traffic=None,
+                    unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4),
+                    traffic=(HBM_TRAFFIC_BYTES.get(dom) if (args.sigmas == "1,2,3,4" and not args.small
+                                                           and args.block_rho == 0.0) else None),
                     avg_launch_ms=round(dom_avg_ms, 3),
                     kernels={k: dict(avg_ms=round(v[0] / v[1], 3), launches=v[1],
                                      tflops=(round(exec_total[k] / len(points) / (v[0] / v[1] * 1e-3) / 1e12, 1)
