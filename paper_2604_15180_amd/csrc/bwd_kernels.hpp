@@ -255,8 +255,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
             issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
             issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
             // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
-            if (wave == 0) load4_to_lds(p.tau + ((long)bh * N + i * 64) + (uint32_t)lane, b + VEC_OFF);
-            if (wave == 1) load4_to_lds(p.delta + ((long)bh * N + i * 64) + (uint32_t)lane, b + VEC_OFF + 4 * TILE);
+            if (wave == 0) load4_to_lds(uniform_address(p.tau + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF));
+            if (wave == 1) load4_to_lds(uniform_address(p.delta + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF + 4 * TILE));
         },
         [&](int it, const char* qbuf) {
             const int ent = tl[it];

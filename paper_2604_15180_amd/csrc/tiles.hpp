@@ -118,35 +118,49 @@ template <class E, int D> struct RowTile {      // 64 rows x D elements, row-maj
     static constexpr int NINST = BYTES / 1024;   // wave-wide load instructions per tile
 };
 
-EA_DEV void load16_to_lds(const void* g, char* lds_wave_base) {
-    // LDS address = wave-uniform base + lane * 16 (the instruction offset stays 0: it would be
-    // added to the global address as well)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+// Direct global->LDS loads, written as instructions of their own: LDS address = M0 (wave-uniform
+// base) + lane * 16 (or * 4), global address = scalar base + 32-bit lane offset.  As a compiler
+// builtin the load is a "flat access that may touch LDS", and while one is in flight the compiler
+// turns every wait into a wait for ALL outstanding LDS reads (and loads) - with a tile always
+// being prefetched, no MFMA could start before the last of its sixteen fragments had arrived.
+// Hidden from it, the loads cost no such waits; the tile is handed over by an explicit wait
+// (wait_loads) followed by a barrier, and the compiler moves no memory access across either.
+// (M0 is reserved to the compiler, which uses it for nothing else in these kernels; naming it as
+// clobbered is still the honest description of the statement.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+EA_DEV uint64_t uniform_address(const void* p) {      // the same value in scalar registers
+    const uint64_t a = (uint64_t)(uintptr_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return ((uint64_t)hi << 32) | lo;
 }
-
-EA_DEV void load4_to_lds(const void* g, char* lds_wave_base) {   // LDS address = base + lane * 4
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                     (__attribute__((address_space(3))) void*)lds_wave_base, 4, 0, 0);
+EA_DEV uint32_t lds_address(const void* p) {          // LDS byte address of a pointer into LDS, scalar
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p);
 }
+EA_DEV void load16_to_lds(uint64_t base_uniform, uint32_t lane_off, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 : : "v"(lane_off), "s"(base_uniform), "s"(lds_wave_base) : "memory", "m0");
+}
+EA_DEV void load4_to_lds(uint64_t base_uniform, uint32_t lane_off, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+                 : : "v"(lane_off), "s"(base_uniform), "s"(lds_wave_base) : "memory", "m0");
+}
+#pragma clang diagnostic pop
 
 // rows row0..row0+63 of a row-major [.., D] matrix -> LDS tile; the NW waves share the NINST loads
 template <class E, int D, int NW>
 EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave, int lane) {
     using L = RowTile<E, D>;
     static_assert(L::NINST % NW == 0, "loads must divide evenly over the waves");
-    // scalar 64-bit base + unsigned 32-bit lane offset: the form the load takes without any
-    // 64-bit vector address arithmetic (the tile's first row is the same for all lanes)
-    const char* base = (const char*)g + (long)__builtin_amdgcn_readfirstlane((int)row0) * L::ROW_BYTES;
+    // scalar 64-bit base (the tile's first row is the same for all lanes) + 32-bit lane offset
+    const uint64_t base = uniform_address((const char*)g + row0 * (long)L::ROW_BYTES);
+    const uint32_t lds0 = lds_address(lds);
 #pragma unroll
     for (int i = 0; i < L::NINST / NW; ++i) {
         const int t = i * NW + wave;              // wave is wave-uniform (an SGPR)
         const int p = 64 * t + lane, row = p / L::CPR, pos = p % L::CPR;
-        uint32_t off = (uint32_t)(row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16));
-        // keep the widening of `off` next to the load: hoisted out of a loop as a 64-bit value it
-        // would cost a 64-bit vector add per load
-        asm volatile("" : "+v"(off));
-        load16_to_lds(base + off, lds + t * 1024);
+        const uint32_t off = (uint32_t)(row * L::ROW_BYTES + ((pos ^ swz<L::CPR>(row)) * 16));
+        load16_to_lds(base, off, lds0 + t * 1024);
     }
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
