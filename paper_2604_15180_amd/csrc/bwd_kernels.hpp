@@ -77,10 +77,23 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     for (int qb = 0; qb < QB; ++qb) {
         float acc = 0.f;
         if (p.O && active) {
-            const float* orow = p.O + hoff + (qw0 + 32 * qb + n) * (long)D + h * (D / 2);
+            // lane half h takes half of the row; 16-byte loads, all in flight together
+            const f32x4* orow = (const f32x4*)(p.O + hoff + (qw0 + 32 * qb + n) * (long)D + h * (D / 2));
             const elem* grow = (const elem*)p.dO + hoff + (qw0 + 32 * qb + n) * (long)D + h * (D / 2);
-#pragma unroll 8
-            for (int e = 0; e < D / 2; ++e) acc = fmaf(orow[e], (float)grow[e], acc);
+            f32x4 ov[D / 8];
+#pragma unroll
+            for (int e = 0; e < D / 8; ++e) ov[e] = orow[e];
+            if constexpr (sizeof(elem) == 2) {
+                typedef elem ex8 __attribute__((ext_vector_type(8)));
+                ex8 gv[D / 16];
+#pragma unroll
+                for (int e = 0; e < D / 16; ++e) gv[e] = ((const ex8*)grow)[e];
+#pragma unroll
+                for (int e = 0; e < D / 2; ++e) acc = fmaf(ov[e / 4][e % 4], (float)gv[e / 8][e % 8], acc);
+            } else {
+#pragma unroll
+                for (int e = 0; e < D / 2; ++e) acc = fmaf(ov[e / 4][e % 4], (float)grow[e], acc);
+            }
         }
         ctr[qb] = xhalf_sum(acc);
     }

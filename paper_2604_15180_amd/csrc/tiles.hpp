@@ -41,7 +41,7 @@ struct Bf16 {
     static EA_DEV f32x16 mma(frag a, frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
     }
-    static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
+    template <bool FRESH_B = true> static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
     static EA_DEV elem from_float(float x) { return (__bf16)x; }
 };
 struct F16 {
@@ -59,10 +59,12 @@ struct F16 {
     // pinned there they cost no vector registers and no copies, which leaves the 256 ordinary
     // registers to the operands the vector ALUs work on.  The compiler does not know that this
     // statement is an MFMA, so what it would otherwise schedule around one is spelled out: two
-    // idle cycles ahead of it (operands written by the vector ALU just before), and
-    // settle_acc() before anything else reads the accumulator.
+    // idle cycles ahead of it when its B operand may have been written by the vector ALU just
+    // before (FRESH_B), and settle_acc() before anything else reads the accumulator.
+    template <bool FRESH_B = true>
     static EA_DEV void mma_acc(frag a, frag b, f32x16& c) {
-        asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+        if constexpr (FRESH_B) asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+        else asm("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
     }
     static EA_DEV elem from_float(float x) { return (_Float16)x; }
 };
@@ -75,7 +77,7 @@ struct F32 {
     static EA_DEV f32x16 mma(frag a, frag b, f32x16 c) {
         return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
     }
-    static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
+    template <bool FRESH_B = true> static EA_DEV void mma_acc(frag a, frag b, f32x16& c) { c = mma(a, b, c); }
     static EA_DEV elem from_float(float x) { return x; }
 };
 
@@ -196,7 +198,10 @@ EA_DEV void load_owned(Owned<E, D, QB>& o, const typename E::elem* g, long row0,
 }
 
 // ---- stage 1: C[kb][qb] = tile(64 x D, LDS row-major, swizzled) . owned^T -----------------------
-template <class E, int D, int QB, bool FENCE = true>
+#ifndef EA_FENCE
+#define EA_FENCE true
+#endif
+template <class E, int D, int QB, bool FENCE = EA_FENCE>
 EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, QB>& own, int lane) {
     using L = RowTile<E, D>;
     constexpr int ES = (int)sizeof(typename E::elem);
@@ -295,8 +300,11 @@ EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tile, const f32x16 (
                     const typename E2::frag a = __builtin_bit_cast(typename E2::frag, both);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        if constexpr (PINNED) E2::mma_acc(a, b[qb], X[db][qb]);
-                        else X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
+                        // (every pinned MFMA carries its own idle cycles: the compiler may reorder
+                        // these statements, so any of them can end up right behind the conversion
+                        // that writes its B fragment)
+                        if constexpr (!PINNED) X[db][qb] = E2::mma(a, b[qb], X[db][qb]);
+                        else E2::template mma_acc<true>(a, b[qb], X[db][qb]);
                     }
                 }
             }
