@@ -54,6 +54,46 @@ def block_sparsity(mask, T, causal):
     return 1.0 - set_bits / visible
 
 
+def context_scaling(ea, workloads, dev, args):
+    """Second workload (Sec. 4.2 "Context scaling"): forward+backward time against context length
+    at a fixed token budget.  The paper drives this with block-sparsity ratios learned by its 1B
+    model (Fig. 6), which are not available; the planted-key recipe of the 64k configuration stands
+    in (each 64-row query tile attends to 32 planted keys plus Gaussian background, sigma = 3), and
+    the measured block sparsity is reported per length.  d = 64, bf16, causal, alpha = 1.5."""
+    tokens, d, alpha, causal = 1 << 18, 64, 1.5, True
+    rows = []
+    for N in (4096, 8192, 16384, 32768, 65536, 131072):
+        H = tokens // N
+        q, k, v, do = workloads.planted_qkv(1, H, N, d, "bf16", 3.0, seed=7000 + N // 4096)
+        Q, K, V, dO = (t.to(dev) for t in (q, k, v, do))
+        ws_f = torch.empty(ea.entmax_attn_workspace_bytes(1, H, N, d, "bf16", causal, False), dtype=torch.uint8, device=dev)
+        ws_b = torch.empty(ea.entmax_attn_workspace_bytes(1, H, N, d, "bf16", causal, True), dtype=torch.uint8, device=dev)
+        fwd_ms, bwd_ms = [], []
+        for it in range(args.warmup + args.steps):
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=ws_f)
+            e1.record()
+            ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws_b)
+            e2.record()
+            torch.cuda.synchronize()
+            if it >= args.warmup:
+                fwd_ms.append(e0.elapsed_time(e1)); bwd_ms.append(e1.elapsed_time(e2))
+        f, b = float(np.median(fwd_ms)), float(np.median(bwd_ms))
+        dense = 14.0 * H * N * N * d * 0.5
+        rows.append(dict(N=N, heads=H, block_sparsity=round(block_sparsity(mask, N // 64, causal), 4),
+                         mean_tau_iters=round(float(iters.float().mean().item()), 3), fwd_ms=round(f, 3), bwd_ms=round(b, 3),
+                         effective_tflops=round(dense / ((f + b) * 1e-3) / 1e12, 1)))
+        log(rows[-1])
+        del Q, K, V, dO, ws_f, ws_b, O, tau, mask, iters
+        torch.cuda.empty_cache()
+    print(json.dumps(dict(metric="fwd+bwd ms vs context length at 256k tokens (planted-key stand-in for learned sparsity)",
+                          unit="ms", n_gpus=1, steps=args.steps, warmup=args.warmup, dtype="bf16", data="synthetic",
+                          config=dict(workload="context scaling: alpha=1.5 bf16 d=64 causal, B*H*N = 262144 tokens, "
+                                               "planted keys (32 per query tile) + N(0, 9) background"),
+                          lengths=rows)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +104,9 @@ def main():
                     help="block-correlated query variant of the generator (0 = i.i.d. rows as in the config)")
     ap.add_argument("--small", action="store_true", help="N=2048 instead of 16384 (plumbing check only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["sparsity", "context"], default="sparsity",
+                    help="sparsity: the sigma sweep at N=16k the metric is quoted on (default); "
+                         "context: forward+backward time against context length 4K..128K at a fixed token budget")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; heads would shard over GPUs with no communication, "
@@ -78,6 +121,9 @@ def main():
 
     ea.lib()
     dev = torch.device("cuda:0")
+    if args.workload == "context":
+        context_scaling(ea, workloads, dev, args)
+        return
     cfg = dict(workloads.CONFIGS["c3_bf16_n16k"])
     if args.small:
         cfg["N"] = 2048
