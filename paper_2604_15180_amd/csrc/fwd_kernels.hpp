@@ -632,16 +632,20 @@ static __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsig
 }
 
 // max |x| over a tensor -> atomicMax on the float's bit pattern (non-negative floats order as
-// unsigned ints); n is a multiple of 8
+// unsigned ints); n is a multiple of 8.  One atomic per block: thousands of them on one word
+// would take longer than reading the tensor.
 template <class E>
 __global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
+    __shared__ float part[4];
     float m = 0.f;
     for (long i = (blockIdx.x * 256L + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)x[i + e]));
     }
     m = wave_max(m);
-    if ((threadIdx.x & 63) == 0) atomicMax(out_bits, __float_as_uint(m));
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]))));
 }
 
 }  // namespace ea

@@ -86,7 +86,7 @@ struct Ops {
         {
             ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
             if (E2::SCALED) {
-                hipLaunchKernelGGL((amax_kernel<E>), dim3(2048), dim3(256), 0, s, (const typename E::elem*)p.dO,
+                hipLaunchKernelGGL((amax_kernel<E>), dim3(1024), dim3(256), 0, s, (const typename E::elem*)p.dO,
                                    (long)p.BH * p.N * D, p.scal);
                 EA_HIP(hipGetLastError());
             }
