@@ -1,8 +1,8 @@
 // Backward kernels (Sec. 3.3 "Backward pass", Alg. 2-3 of the AdaSplash-2 paper):
-//   dq_kernel   : per 128*QB query rows, over the set bits of their mask rows, in one sweep:
+//   dq_kernel   : per 32*QB*NW query rows, over the set bits of their mask rows, in one sweep:
 //                 delta_r = sum_j U_rj dP_rj / sum_j U_rj,  U = P^(2-alpha), dP = dO V^T
 //                 dQ = [ (U o dP) K - delta (U K) ] / sqrt(d)  ( = dS K / sqrt(d), Alg. 3)
-//   dkdv_kernel : per 128*QB keys, over the set bits of their mask columns:
+//   dkdv_kernel : per 32*QB*NW keys, over the set bits of their mask columns:
 //                 dV += P^T dO,  dK += dS^T Q / sqrt(d)                               (Alg. 2)
 // With y = (alpha-1) s - tau on the support:  P = y^r,  U = y^(r-1),  r = 1/(alpha-1).
 #pragma once

@@ -1,10 +1,11 @@
 // Forward kernels (Alg. 1 of the AdaSplash-2 paper), re-cut for CDNA4:
-//   tau_kernel : Phase 1 (row max, plus per-row tile maxima -> candidate tiles), Phase 2 (LDS
-//                histogram over the candidates -> tau_0), first Phase-3 sweep (f, f', f'' at tau_0,
-//                one safeguarded Halley/Newton step, working block mask at tau_0)
+//   tau_kernel : Phases 1 and 2 in one dense sweep (row maximum, LDS histogram of the scores within
+//                one unit of the running maximum, per-row tile maxima), histogram solve -> tau_0,
+//                candidate tiles (those holding a score above tau_0), first Phase-3 sweep over them
+//                (f, f', f'' at tau_0, one safeguarded Halley/Newton step, working mask at tau_0)
 //   out_kernel : Phase 4 (O = P V over the working mask), which is also the next evaluation of f;
 //                further refinement only for rows that fail it; exported mask at the final tau
-// One work-group = 128*QB query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
+// One work-group = 32*QB*NW query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
 // B operands in registers; 64-key tiles of K (and V) stream through LDS.
 #pragma once
 #include "common.hpp"
