@@ -10,6 +10,108 @@
 
 namespace ea {
 
+// Two floats -> one register of two fp16 values (round to nearest even).
+EA_DEV uint32_t pack_f16x2(float a, float b) {
+    typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+    h2 v;
+    v[0] = (_Float16)a; v[1] = (_Float16)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+EA_DEV f16x8 frag_of(const uint32_t (&w)[8], int s2) {
+    u32x4 v;
+    v[0] = w[4 * s2]; v[1] = w[4 * s2 + 1]; v[2] = w[4 * s2 + 2]; v[3] = w[4 * s2 + 3];
+    return __builtin_bit_cast(f16x8, v);
+}
+
+// One 64-key tile of the dQ sweep for a wave's 32 rows, 16-bit operands, every statement placed by
+// hand.  A wave with 128 accumulator registers runs alone on its SIMD, so nothing but its own
+// instruction order lets the vector ALUs work while the matrix pipe is busy.  The tile is cut into
+// its two 32-key halves and the work on them is staggered:
+//     stage 1, half 0                                    (matrix pipe only)
+//     stage 1, half 1    with the score math of half 0   (one or two scores after every MFMA)
+//     stage 2, half 0    with the score math of half 1
+//     stage 2, half 1                                    (matrix pipe only)
+// LDS reads run PF steps ahead of the MFMAs that use them.  An MFMA lasts 32 cycles and a vector
+// instruction 4, so up to 7 vector instructions fit behind each MFMA at no cost.
+template <class E, class E2, int D, int AM>
+EA_DEV void dq_tile_staggered(const char* kbuf, const char* vbuf, const Owned<E, D, 1>& qf, const Owned<E, D, 1>& gf,
+                              f32x16 (&XA)[D / 32][1], f32x16 (&XB)[D / 32][1], float thr, float ctr, float c, float r,
+                              float& num, float& den, const Frag1<E, D>& f1, const Frag2<E2, D>& f2) {
+    constexpr int NS = D / 16, ND = D / 32;
+    constexpr int N1 = 2 * NS;            // stage-1 steps (kb, s): two MFMAs each (scores, dP)
+    constexpr int N2 = 4 * ND;            // stage-2 steps (kb, s2, db): two MFMAs each (XA, XB)
+    constexpr int PF = 4;                 // steps the LDS reads run ahead
+    constexpr int EPM = 8 / NS;           // scores handled after each MFMA of an overlapped phase
+    static_assert(8 % NS == 0 && 4 % ND == 0 && EPM == 4 / ND, "halves must divide evenly over the MFMAs");
+    using frag = typename E::frag;
+    using frag2 = typename E2::frag;
+    f32x16 S[2], P[2];
+    uint32_t tp[2][8], up[2][8];          // t = u (dP - e) and u as fp16 pairs: the stage-2 B operands
+    frag ak[N1], av[N1];
+    frag2 at[N2];
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    auto score_math = [&](int kb, int e) {
+        const float y = fmaf(c, S[kb][e], -thr);
+        float u;
+        if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
+        else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+        const float t = u * (P[kb][e] - ctr);
+        num += t;
+        den += u;
+        S[kb][e] = t;
+        P[kb][e] = u;
+        if (e & 1) {
+            tp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
+            up[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
+        }
+    };
+    auto read2 = [&](int i2) { at[i2] = f2(kbuf, i2 / (2 * ND), (i2 / ND) & 1, i2 % ND); };
+
+#pragma unroll
+    for (int i = 0; i < PF; ++i) { ak[i] = f1(kbuf, i / NS, i % NS); av[i] = f1(vbuf, i / NS, i % NS); }
+    sched_fence();
+#pragma unroll
+    for (int i = 0; i < N1; ++i) {
+        const int kb = i / NS, s = i % NS;
+        if (i + PF < N1) { ak[i + PF] = f1(kbuf, (i + PF) / NS, (i + PF) % NS); av[i + PF] = f1(vbuf, (i + PF) / NS, (i + PF) % NS); }
+        else read2(i + PF - N1);
+        S[kb] = E::mma(ak[i], qf.f[0][s], s == 0 ? zero : S[kb]);
+        sched_fence();
+        if (kb == 1) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(0, 2 * EPM * s + k);
+        }
+        sched_fence();
+        P[kb] = E::mma(av[i], gf.f[0][s], s == 0 ? zero : P[kb]);
+        sched_fence();
+        if (kb == 1) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(0, 2 * EPM * s + EPM + k);
+        }
+        sched_fence();
+    }
+#pragma unroll
+    for (int i = 0; i < N2; ++i) {
+        const int kb = i / (2 * ND), s2 = (i / ND) & 1, db = i % ND, j = i % (2 * ND);
+        if (i + PF < N2) read2(i + PF);
+        E2::template mma_acc<false>(at[i], frag_of(tp[kb], s2), XA[db][0]);
+        sched_fence();
+        if (kb == 0) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + k);
+        }
+        sched_fence();
+        E2::template mma_acc<false>(at[i], frag_of(up[kb], s2), XB[db][0]);
+        sched_fence();
+        if (kb == 0) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + EPM + k);
+        }
+        sched_fence();
+    }
+}
+
 template <class E, class E2, int D, int QB, int NW, int NBUF>
 struct DqSmem {
     static constexpr int BR = 32 * QB * NW;
@@ -108,43 +210,61 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
 
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile = 0;
+    const Frag1<E, D> frag1(lane);
+    const Frag2<E2, D> frag2(lane);
     float num[QB], den[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) num[qb] = den[qb] = 0.f;
-    stream_tiles<NBUF>(
-        *tl_count, set0, NBUF == 2 ? set1 : set0,
-        [&](int it, char* b) {
-            const long j = tl[it];
-            issue_rows<E, D, NW>(b, Kh, j * 64, wave, lane);
-            issue_rows<E, D, NW>(b + SM::RBYTES, Vh, j * 64, wave, lane);
-        },
-        [&](int it, const char* kbuf) {
-            const int j = tl[it];
-            if (!mask_bit(fm, W, myrow, j)) return;
-            const char* vbuf = kbuf + SM::RBYTES;
-            stage1<E, D, QB>(S, kbuf, qf, lane);
-            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
-            stage1<E, D, QB>(dP, vbuf, gf, lane);
-            ++ntile;
+    auto issue_kv = [&](int it, char* b) {
+        const long j = tl[it];
+        issue_rows<E, D, NW>(b, Kh, j * 64, wave, lane);
+        issue_rows<E, D, NW>(b + SM::RBYTES, Vh, j * 64, wave, lane);
+    };
+    // any tile, statements left to the compiler's order
+    auto tile_plain_order = [&](int it, const char* kbuf) {
+        const int j = tl[it];
+        if (!mask_bit(fm, W, myrow, j)) return;
+        const char* vbuf = kbuf + SM::RBYTES;
+        ++ntile;
+        stage1<E, D, QB>(S, kbuf, qf, lane);
+        if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(S, j * 64, (int)qw0, lane);
+        stage1<E, D, QB>(dP, vbuf, gf, lane);
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
-                        float u;
-                        if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
-                        else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
-                        const float t = u * (dP[kb][qb][v] - ctr[qb]);
-                        num[qb] += t;
-                        den[qb] += u;
-                        S[kb][qb][v] = t;
-                        dP[kb][qb][v] = u;
-                    }
-            stage2<E2, D, QB, true>(XA, kbuf, S, lane);
-            stage2<E2, D, QB, true>(XB, kbuf, dP, lane);
-        });
+                for (int v = 0; v < 16; ++v) {
+                    const float y = fmaf(c, S[kb][qb][v], -thr[qb]);
+                    float u;
+                    if constexpr (AM == ALPHA_15) u = fmaxf(y, 0.f);
+                    else u = (y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                    const float t = u * (dP[kb][qb][v] - ctr[qb]);
+                    num[qb] += t;
+                    den[qb] += u;
+                    S[kb][qb][v] = t;
+                    dP[kb][qb][v] = u;
+                }
+        stage2<E2, D, QB, true>(XA, kbuf, S, lane);
+        stage2<E2, D, QB, true>(XB, kbuf, dP, lane);
+    };
+    if constexpr (E::EPL == 8 && QB == 1 && NBUF == 2) {
+        // tiles wholly below the diagonal (the head of the ascending list) take the staggered body;
+        // the one or two on it, and one more when that makes the head's length even, the plain one
+        const int nt = *tl_count;
+        int ndiag = 0;
+        if (p.causal)
+            while (ndiag < nt && (long)tl[nt - 1 - ndiag] * 64 + 63 > q0) ++ndiag;
+        stream_tiles_split((nt - ndiag) & ~1, nt, set0, set1, issue_kv,
+            [&](int it, const char* kbuf) {
+                if (!mask_bit(fm, W, myrow, tl[it])) return;
+                ++ntile;
+                dq_tile_staggered<E, E2, D, AM>(kbuf, kbuf + SM::RBYTES, qf, gf, XA, XB, thr[0], ctr[0], c, r, num[0], den[0], frag1, frag2);
+            },
+            tile_plain_order);
+    } else {
+        stream_tiles<NBUF>(*tl_count, set0, NBUF == 2 ? set1 : set0, issue_kv, tile_plain_order);
+    }
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -167,6 +287,97 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
         const int slot[1] = {3};
         const unsigned long long val[1] = {ntile * QB};
         flush_counters<1>(blk_stats, p.stats, slot, val, tid, lane);
+    }
+}
+
+// One 64-query tile of the dK/dV walk for a wave's 32 keys, staggered like dq_tile_staggered:
+// stage 1 = (Q tile . K_owned^T, dO tile . V_owned^T), score math P = u y, dS = u (dP - delta) with
+// the tile's thresholds and deltas read from LDS four rows at a time, stage 2 = (dV^T += dO^T P,
+// dK^T += Q^T dS).
+template <class E, class E2, int D, int AM>
+EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float* tau_s, const float* del_s,
+                                const Owned<E, D, 1>& kf, const Owned<E, D, 1>& vf, f32x16 (&XV)[D / 32][1],
+                                f32x16 (&XK)[D / 32][1], float c, float r, int h, const Frag1<E, D>& f1,
+                                const Frag2<E2, D>& f2) {
+    constexpr int NS = D / 16, ND = D / 32;
+    constexpr int N1 = 2 * NS, N2 = 4 * ND, PF = 4, EPM = 8 / NS;
+    static_assert(8 % NS == 0 && 4 % ND == 0 && EPM == 4 / ND, "halves must divide evenly over the MFMAs");
+    using frag = typename E::frag;
+    using frag2 = typename E2::frag;
+    f32x16 S[2], P[2];
+    uint32_t pp[2][8], sp[2][8];          // P and dS as fp16 pairs: the stage-2 B operands
+    frag aq[N1], ag[N1];
+    frag2 tg[N2], tq[N2];
+    f32x4 tau4[2], del4[2];               // thresholds / deltas of two groups of four registers (rows)
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+    // group G = 4 kb + e / 4 holds registers 4 (e / 4) .. + 3 of half kb: four consecutive tile rows
+    auto read_vec = [&](int G) {
+        const int row = trow(G >> 2, 4 * (G & 3), h);
+        tau4[G & 1] = *(const f32x4*)(tau_s + row);
+        del4[G & 1] = *(const f32x4*)(del_s + row);
+    };
+    auto score_math = [&](int kb, int e) {
+        const int G = 4 * kb + (e >> 2);
+        if ((e & 3) == 0 && G < 7) read_vec(G + 1);       // one group ahead
+        const float yp = fmaxf(fmaf(c, S[kb][e], -tau4[G & 1][e & 3]), 0.f);
+        float u;
+        if constexpr (AM == ALPHA_15) u = yp;
+        else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
+        S[kb][e] = u * yp;
+        P[kb][e] = u * (P[kb][e] - del4[G & 1][e & 3]);
+        if (e & 1) {
+            pp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
+            sp[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
+        }
+    };
+    auto read2 = [&](int i2) {
+        tg[i2] = f2(gbuf, i2 / (2 * ND), (i2 / ND) & 1, i2 % ND);
+        tq[i2] = f2(qbuf, i2 / (2 * ND), (i2 / ND) & 1, i2 % ND);
+    };
+
+#pragma unroll
+    for (int i = 0; i < PF; ++i) { aq[i] = f1(qbuf, i / NS, i % NS); ag[i] = f1(gbuf, i / NS, i % NS); }
+    sched_fence();
+#pragma unroll
+    for (int i = 0; i < N1; ++i) {
+        const int kb = i / NS, s = i % NS;
+        if (i + PF < N1) { aq[i + PF] = f1(qbuf, (i + PF) / NS, (i + PF) % NS); ag[i + PF] = f1(gbuf, (i + PF) / NS, (i + PF) % NS); }
+        else read2(i + PF - N1);
+        if (i == NS - 1) read_vec(0);
+        S[kb] = E::mma(aq[i], kf.f[0][s], s == 0 ? zero : S[kb]);
+        sched_fence();
+        if (kb == 1) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(0, 2 * EPM * s + k);
+        }
+        sched_fence();
+        P[kb] = E::mma(ag[i], vf.f[0][s], s == 0 ? zero : P[kb]);
+        sched_fence();
+        if (kb == 1) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(0, 2 * EPM * s + EPM + k);
+        }
+        sched_fence();
+    }
+#pragma unroll
+    for (int i = 0; i < N2; ++i) {
+        const int kb = i / (2 * ND), s2 = (i / ND) & 1, db = i % ND, j = i % (2 * ND);
+        if (i + PF < N2) read2(i + PF);
+        E2::template mma_acc<false>(tg[i], frag_of(pp[kb], s2), XV[db][0]);
+        sched_fence();
+        if (kb == 0) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + k);
+        }
+        sched_fence();
+        E2::template mma_acc<false>(tq[i], frag_of(sp[kb], s2), XK[db][0]);
+        sched_fence();
+        if (kb == 0) {
+#pragma unroll
+            for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + EPM + k);
+        }
+        sched_fence();
     }
 }
 
@@ -261,53 +472,70 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     f32x16 S[2][QB], dP[2][QB];
     unsigned long long ntile_done = 0;
     constexpr int VEC_OFF = 2 * SM::RBYTES;
-    stream_tiles<NBUF>(
-        ntl, set0, NBUF == 2 ? set1 : set0,
-        [&](int it, char* b) {
-            const long i = __builtin_amdgcn_readfirstlane(tl[it] & 0xffff);
-            issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
-            issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
-            // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
-            if (wave == 0) load4_to_lds(uniform_address(p.tau + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF));
-            if (wave == 1) load4_to_lds(uniform_address(p.delta + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF + 4 * TILE));
-        },
-        [&](int it, const char* qbuf) {
-            const int ent = tl[it];
-            const long i = ent & 0xffff;
-            if (!((ent >> (16 + mycol)) & 1)) return;
-            const char* gbuf = qbuf + SM::RBYTES;
-            const float* tau_s = (const float*)(qbuf + VEC_OFF);
-            const float* del_s = tau_s + TILE;
-            stage1<E, D, QB>(S, qbuf, kf, lane);
-            // streamed rows are queries here: hide key > query
-            if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, (int)i * 64, (int)kw0, lane);
-            stage1<E, D, QB>(dP, gbuf, vf, lane);
-            ++ntile_done;
+    auto issue_qg = [&](int it, char* b) {
+        const long i = __builtin_amdgcn_readfirstlane(tl[it] & 0xffff);
+        issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
+        issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
+        // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
+        if (wave == 0) load4_to_lds(uniform_address(p.tau + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF));
+        if (wave == 1) load4_to_lds(uniform_address(p.delta + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF + 4 * TILE));
+    };
+    // any tile, statements left to the compiler's order
+    auto tile_plain_order = [&](int it, const char* qbuf) {
+        const int ent = tl[it];
+        const long i = ent & 0xffff;
+        if (!((ent >> (16 + mycol)) & 1)) return;
+        const char* gbuf = qbuf + SM::RBYTES;
+        const float* tau_s = (const float*)(qbuf + VEC_OFF);
+        const float* del_s = tau_s + TILE;
+        stage1<E, D, QB>(S, qbuf, kf, lane);
+        // streamed rows are queries here: hide key > query
+        if (p.causal && i * 64 < kw0 + 32 * QB - 1) causal_hide<QB, false>(S, (int)i * 64, (int)kw0, lane);
+        stage1<E, D, QB>(dP, gbuf, vf, lane);
+        ++ntile_done;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int v4 = 0; v4 < 16; v4 += 4) {
-                    // registers v4..v4+3 are four consecutive tile rows: one 16-byte read each
-                    const int row = trow(kb, v4, h);
-                    const f32x4 tq4 = *(const f32x4*)(tau_s + row), dq4 = *(const f32x4*)(del_s + row);
+            for (int v4 = 0; v4 < 16; v4 += 4) {
+                // registers v4..v4+3 are four consecutive tile rows: one 16-byte read each
+                const int row = trow(kb, v4, h);
+                const f32x4 tq4 = *(const f32x4*)(tau_s + row), dq4 = *(const f32x4*)(del_s + row);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int v = v4 + e;
-                        const float tq = tq4[e], dq = dq4[e];
+                for (int e = 0; e < 4; ++e) {
+                    const int v = v4 + e;
+                    const float tq = tq4[e], dq = dq4[e];
 #pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) {
-                            const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
-                            float u;
-                            if constexpr (AM == ALPHA_15) u = yp;
-                            else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
-                            S[kb][qb][v] = u * yp;
-                            dP[kb][qb][v] = u * (dP[kb][qb][v] - dq);
-                        }
+                    for (int qb = 0; qb < QB; ++qb) {
+                        const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
+                        float u;
+                        if constexpr (AM == ALPHA_15) u = yp;
+                        else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
+                        S[kb][qb][v] = u * yp;
+                        dP[kb][qb][v] = u * (dP[kb][qb][v] - dq);
                     }
                 }
-            stage2<E2, D, QB, true>(XV, gbuf, S, lane);
-            stage2<E2, D, QB, true>(XK, qbuf, dP, lane);
-        });
+            }
+        stage2<E2, D, QB, true>(XV, gbuf, S, lane);
+        stage2<E2, D, QB, true>(XK, qbuf, dP, lane);
+    };
+    if constexpr (E::EPL == 8 && QB == 1 && NBUF == 2) {
+        // query tiles on the diagonal (the head of the ascending list), and one more when that makes
+        // their number even, take the plain body; all tiles wholly below it the staggered one
+        int ndiag = 0;
+        if (p.causal)
+            while (ndiag < ntl && (long)(tl[ndiag] & 0xffff) * 64 < k0 + BC - 1) ++ndiag;
+        const Frag1<E, D> frag1(lane);
+        const Frag2<E2, D> frag2(lane);
+        stream_tiles_split(min(ntl, (ndiag + 1) & ~1), ntl, set0, set1, issue_qg, tile_plain_order,
+            [&](int it, const char* qbuf) {
+                if (!((tl[it] >> (16 + mycol)) & 1)) return;
+                ++ntile_done;
+                const float* tau_s = (const float*)(qbuf + VEC_OFF);
+                dkdv_tile_staggered<E, E2, D, AM>(qbuf, qbuf + SM::RBYTES, tau_s, tau_s + TILE, kf, vf, XV, XK, c, r, h, frag1, frag2);
+            });
+    } else {
+        stream_tiles<NBUF>(ntl, set0, NBUF == 2 ? set1 : set0, issue_qg, tile_plain_order);
+    }
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll

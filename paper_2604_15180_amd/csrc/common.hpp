@@ -98,6 +98,40 @@ EA_DEV void stream_tiles(int ntiles, char* buf0, char* buf1, IssueF issue, Compu
     }
 }
 
+// The same walk with two tile bodies: tiles [0, n1) go to compute1, tiles [n1, n) to compute2
+// (n1 even, or n1 == n), as two loops one after the other that share the double buffer: the first
+// tile of the second loop is loaded under the last tile of the first.  Two loops rather than a
+// choice per tile because accumulators pinned to registers by assembly statements must not meet at
+// a join inside the loop (the compiler then copies all of them on one of the two paths, every tile).
+template <class IssueF, class Compute1, class Compute2>
+EA_DEV void stream_tiles_split(int n1, int n, char* buf0, char* buf1, IssueF issue, Compute1 compute1, Compute2 compute2) {
+    if (n > 0) issue(0, buf0);
+    int it = 0;
+    for (; it < n1; it += 2) {
+        wait_loads();
+        __syncthreads();
+        if (it + 1 < n) issue(it + 1, buf1);
+        compute1(it, buf0);
+        if (it + 1 >= n1) { it = n1; break; }        // only when n1 == n is odd
+        wait_loads();
+        __syncthreads();
+        if (it + 2 < n) issue(it + 2, buf0);
+        compute1(it + 1, buf1);
+    }
+    for (; it < n; it += 2) {
+        wait_loads();
+        __syncthreads();
+        if (it + 1 < n) issue(it + 1, buf1);
+        compute2(it, buf0);
+        if (it + 1 >= n) break;
+        wait_loads();
+        __syncthreads();
+        if (it + 2 < n) issue(it + 2, buf0);
+        compute2(it + 1, buf1);
+    }
+    __syncthreads();
+}
+
 // Executed-work counters.  The workspace starts with STATS_COPIES copies of the STATS_WORDS
 // counters (a counter's value is the sum over the copies).  The waves of a group first add into
 // LDS; one thread per counter then issues one global atomic, aimed at the copy picked by the

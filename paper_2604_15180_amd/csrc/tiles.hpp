@@ -330,6 +330,43 @@ EA_DEV void stage2(f32x16 (&X)[D / 32][QB], const char* lds_tile, const f32x16 (
     }
 }
 
+// ---- fragment readers for hand-ordered tile bodies (16-bit types) -----------------------------
+// The same fragments stage1/stage2 read, one at a time, so that a kernel can place every LDS read,
+// MFMA and vector-ALU statement itself (see sched_fence).
+template <class E, int D> struct Frag1 {          // stage-1 A fragment: MFMA rows = permuted tile rows
+    using L = RowTile<E, D>;
+    int lane_off;
+    EA_DEV explicit Frag1(int lane) {
+        const int m = lane & 31, h = lane >> 5, row = perm_row(m);
+        lane_off = row * L::ROW_BYTES + ((h * 16) ^ (swz<L::CPR>(row) * 16));
+    }
+    // rows 32 kb .. of the tile, contraction elements 16 s ..
+    EA_DEV typename E::frag operator()(const char* tile, int kb, int s) const {
+        return *(const typename E::frag*)(tile + (lane_off ^ (s * 32)) + kb * 32 * L::ROW_BYTES);
+    }
+};
+template <class E2, int D> struct Frag2 {         // stage-2 A fragment: tile^T via the LDS transpose read
+    using L = RowTile<E2, D>;
+    int off_lo, off_hi;
+    EA_DEV explicit Frag2(int lane) {
+        const int g = lane >> 4, i = lane & 15, e = i >> 2, q = i & 3, h = g >> 1;
+        const int r_lo = 8 * h + e, r_hi = r_lo + 4, cc = 2 * (g & 1) + (q >> 1);
+        off_lo = r_lo * L::ROW_BYTES + ((cc ^ swz<L::CPR>(r_lo)) * 16) + (q & 1) * 8;
+        off_hi = r_hi * L::ROW_BYTES + ((cc ^ swz<L::CPR>(r_hi)) * 16) + (q & 1) * 8;
+    }
+    // tile columns 32 db .., contraction over tile rows 32 kb + 16 s2 ..
+    EA_DEV typename E2::frag operator()(const char* tile, int kb, int s2, int db) const {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const char* rows = tile + (32 * kb + 16 * s2) * L::ROW_BYTES;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(rows + (off_lo ^ (db * 64))));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(rows + (off_hi ^ (db * 64))));
+        return __builtin_bit_cast(typename E2::frag, (s16x8)__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
+};
+// Nothing moves across: the statements between two fences are scheduled among themselves only.
+EA_DEV void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
 // Write X^T accumulators (d x owned rows) to a row-major float [.., D] matrix, scaled.
 // Register v of block db in lane (n, h) is element (row0 + 32 qb + n, 32 db + 8(v/4) + 4h + v%4).
 template <int D, int QB>
