@@ -39,7 +39,7 @@ constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, d, delta, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, total;
+    size_t stats, a, b, c, d, delta, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
 };
 
 // element size of the stage-2 copies
@@ -57,6 +57,8 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.rs_hi = off; off += align256(BH * N * 4);
     L.rs_f1 = off; off += align256(BH * N * 4);
     L.rs_state = off; off += align256(BH * N * 4);
+    L.oflag = off; off += align256(BH * T * 4);                  // 64-row blocks whose candidate lists overflowed
+    L.lists = off; off += align256(BH * N * (size_t)(2 * LIST_CAP * 8));   // candidate lists, two per row
     L.total = off;
     return L;
 }
@@ -148,6 +150,8 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.V2 = (t == EA_BF16) ? (const void*)(ws + L.a) : V;
     p.wmask = (int32_t*)(ws + L.wmask);
     p.tmax = (_Float16*)(ws + L.tmax);
+    p.lists = ws + L.lists;
+    p.oflag = (int32_t*)(ws + L.oflag);
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());

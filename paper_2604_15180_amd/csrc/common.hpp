@@ -8,6 +8,7 @@ namespace ea {
 constexpr int MAX_T = 2048;     // N <= 131072
 constexpr int MAX_W = 64;       // mask words per row
 constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
+constexpr int LIST_CAP = 256;   // candidate entries per (row, lane half)
 
 struct Params {
     const void* Q; const void* K; const void* V; const void* dO;
@@ -20,6 +21,8 @@ struct Params {
     int32_t* iters;       // nullable
     float* rs_lo; float* rs_hi; float* rs_f1; int* rs_state;   // [BH][N] solver state handed from tau_kernel to out_kernel
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
+    void* lists;          // [BH][N][2][LIST_CAP] candidate scores (raw score, key tile), 8 bytes each
+    int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
     // scal[0] = max |dO| (the backward uses dO divided by it)

@@ -179,6 +179,13 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
     const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
     const bool active = qw0 < N;          // N is a multiple of 64: the last group may be half empty
+    if (p.oflag) {
+        // run as the fallback of tau_list_kernel: only groups that hold a flagged 64-row block
+        int flagged = 0;
+        for (int i = 0; i < MR; ++i)
+            if (I * MR + i < T) flagged |= p.oflag[(long)bh * T + (long)I * MR + i];
+        if (!flagged) return;
+    }
     _Float16* tmax_g = p.tmax + (long)bh * T * N;      // [T][N] per-row tile maxima, rounded up
     const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + (long)bh * N * D;
@@ -392,6 +399,309 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     {
         const int slot[2] = {0, 5};
         const unsigned long long val[2] = {ntile_done * QB, wave == 0 ? 1ull : 0ull};
+        flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
+    }
+}
+
+// ---- threshold kernel with candidate lists -----------------------------------------------------
+// Phases 1-3 of Alg. 1 from ONE dense sweep.  By Eq. 5, tau* >= max - 1 (in units of (alpha-1) s),
+// and both the maximum and tau* over a prefix of the keys are at most their values over all keys,
+// so a score that lies below a lower bound of the prefix's threshold when it is met can never lie
+// above the final one.  Every other score - a handful per row when attention is sparse - is
+// (a) counted in the row's LDS histogram (Eq. 6-8; absolute bin grid with a sliding window, as in
+// tau_kernel) and (b) appended, with its key tile, to a list private to the lane that computed it
+// (each lane sees 16 of every 32 keys of its row, so a row has two lists; no atomics, no ordering
+// between lanes).  The lower bound starts as (running maximum - 1); each time a list has grown by
+// a fixed number of entries the histogram is solved (Eq. 9) and its root tau_h, a lower bound of the
+// prefix's tau* by Prop. 1, becomes the new bound.  Scores that were skipped lie below the bound and
+// contribute nothing to f at or above it, so f there, and with it Prop. 1, is that of all scores.
+// After the sweep the lists hold a superset of the row's support as exact fp32 scores, and the
+// rest happens on them: the refinement iterations of Sec. 3.2 from tau_0 = tau_h, each an
+// evaluation of f, f', f'' over the listed true scores instead of another sweep of Q K^T.  The key
+// tiles of the entries above tau_0 are the working mask.
+// A list that fills up (attention close to uniform: hundreds of non-zeros per row) flags its 64-row
+// block; flagged blocks are redone by the sweep-based tau_kernel, which runs right after and exits
+// at once everywhere else.
+template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
+__global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
+    using SM = TauSmem<E, D, QB, NB, NW, NBUF>;
+    using KT = RowTile<E, D>;
+    using elem = typename E::elem;
+    constexpr int THREADS = NW * 64, BR = SM::BR, MR = SM::MR, SLOTS = SM::SLOTS;
+    constexpr int GROW = 24;              // list growth (entries per lane) between two histogram solves
+    __shared__ __align__(1024) char kbuf[KT::BYTES];
+    __shared__ __align__(1024) char kbuf_b[NBUF == 2 ? KT::BYTES : 1024];
+    __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
+    __shared__ uint32_t wm[MR * MAX_W];
+    __shared__ int over_s[MR];
+    __shared__ unsigned long long blk_stats[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, h = lane >> 5;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
+    const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
+    const bool active = qw0 < N;
+    const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
+    const elem* Kh = (const elem*)p.K + (long)bh * N * D;
+    const int njt = p.causal ? min((int)((q0 + BR) / 64), T) : T;
+    const int wjt = !active ? 0 : p.causal ? (int)((qw0 + 32 * QB - 1) / 64) + 1 : T;
+    const int myrow = (wave * 32 * QB) / 64;
+    const float c = p.c, r = p.r;
+    constexpr float hb = 1.f / NB;
+
+    Owned<E, D, QB> qf;
+    load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
+    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;
+    for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
+    if (tid < MR) over_s[tid] = 0;
+
+    // this lane's lists: byte offsets inside the head's block of lists (< 2^32: N <= 131072)
+    char* const lists_h = (char*)p.lists + (size_t)bh * N * (2 * LIST_CAP * 8);
+    uint32_t loff[QB];
+    int cnt[QB], trig[QB], a_top[QB], bottom4[QB];
+    float run[QB], lowraw[QB], k4[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        loff[qb] = (uint32_t)(((active ? qw0 : 0) + 32 * qb + n) * 2 + h) * (uint32_t)(LIST_CAP * 8);
+        cnt[qb] = 0; trig[qb] = GROW;
+        run[qb] = -INFINITY; lowraw[qb] = -3.0e38f;
+        k4[qb] = 0.f; bottom4[qb] = 0; a_top[qb] = INT_MIN;
+    }
+    char* const hrow = (char*)(hist + (wave * 32 + n) * SLOTS);
+
+    // Root of the row's histogram (Eq. 9) as it stands: lane (n, h) solves row block qb = h of row n
+    // (with one row per lane, both lanes solve the same), then the two lanes of a row swap.  Returns
+    // per row block tau_0 = max(tau_h, max - 1) less the fp32 slack, and the bracket's upper end.
+    auto histogram_bound = [&](float (&lo)[QB], float (&up)[QB]) {
+        lds_settle();
+        const int sq = (QB == 2) ? h : 0;
+        int top = a_top[0];
+        float mx = run[0];
+        if constexpr (QB == 2) { if (h) { top = a_top[1]; mx = run[1]; } }
+        const int a_lo = top == INT_MIN ? 0 : top - (SLOTS - 1);
+        const float origin = (float)a_lo * hb;                        // left edge of the window
+        const float tau_h = solve_histogram<AM, SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1),
+                                                                  SM::CBITS * sq & 31, hb, r) + origin;
+        const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
+        const float my_lo = fmaxf(tau_h - slack, fmaf(c, mx, -1.f)), my_up = tau_h + hb + slack;
+        const float o_lo = __shfl_xor(my_lo, 32), o_up = __shfl_xor(my_up, 32);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const bool mine = (h == (QB == 2 ? qb : 0));
+            lo[qb] = mine ? my_lo : o_lo;
+            up[qb] = mine ? my_up : o_up;
+        }
+    };
+
+    f32x16 C[2][QB];
+    unsigned long long ntile_done = 0;
+    const float inv_c = 1.f / c, cb = c * NB, c4 = 4.f * cb;
+    char* const kbuf1 = NBUF == 2 ? kbuf_b : kbuf;
+    // Tile body; returns the number of vector-memory instructions (list stores) the wave issued.
+    auto sweep_tile = [&](int j, const char* buf) -> int {
+            if (j >= wjt) return 0;
+            int nstores = 0;
+            stage1<E, D, QB>(C, buf, qf, lane);
+            if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
+            ++ntile_done;
+            bool grown = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                float gm[4];                            // maxima of the four groups of 8 registers
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    gm[g] = C[g >> 1][qb][8 * (g & 1)];
+#pragma unroll
+                    for (int v = 1; v < 8; ++v) gm[g] = fmaxf(gm[g], C[g >> 1][qb][8 * (g & 1) + v]);
+                }
+                const float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
+                const float tm = xhalf_max(lm);
+                // the window of live bins follows the running maximum (see tau_kernel)
+                const bool rise = tm > run[qb];
+                if (__any(rise)) {
+                    int first = 0, last = -1;           // bins to clear: first..last (none)
+                    if (rise) {
+                        run[qb] = tm;
+                        int nt = (int)floorf(fminf(fmaxf(cb * tm, -1e9f), 1e9f));
+                        int a_lo = nt - (SLOTS - 1), rot = a_lo & (SLOTS - 1);
+                        float kk = 4.f * (float)(rot - a_lo);
+                        // the maximum itself must land in the window's top slot, not wrap past it
+                        if ((int)fmaf(c4, tm, kk) >= 4 * rot + 4 * SLOTS) {
+                            nt += 1; a_lo += 1; rot = a_lo & (SLOTS - 1); kk = 4.f * (float)(rot - a_lo);
+                        }
+                        if (a_top[qb] != INT_MIN) { first = max(a_top[qb], nt - SLOTS) + 1; last = nt; }
+                        a_top[qb] = nt; k4[qb] = kk; bottom4[qb] = 4 * rot;
+                    }
+                    // the whole wave clears the slots of one rising row at a time: lane i takes slot i
+                    unsigned long long todo = __ballot(h == 0 && last >= first);
+                    while (todo) {
+                        const int src = __ffsll((long long)todo) - 1;
+                        todo &= todo - 1;
+                        const int f0 = __builtin_amdgcn_readlane(first, src);
+                        const int ncl = __builtin_amdgcn_readlane(last - first, src);
+                        if (((lane - f0) & (SLOTS - 1)) <= ncl) {
+                            uint32_t* word = hist + (wave * 32 + src) * SLOTS + lane;
+                            if constexpr (QB == 1) *word = 0u;
+                            else lds_and_b32(word, qb == 0 ? 0xffff0000u : 0x0000ffffu);
+                        }
+                    }
+                }
+                // candidates: raw scores at or above the row's current lower bound
+                const float low = fmaxf(run[qb] - inv_c, lowraw[qb]);
+                if (!__any(lm >= low)) continue;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    if (!__any(gm[g] >= low)) continue;
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) {
+                        const float sc = C[g >> 1][qb][8 * (g & 1) + v];
+                        const bool hit = sc >= low;
+                        if (!__any(hit)) continue;
+                        ++nstores;
+                        if (hit) {
+                            // slot of the score's bin, times 4 (a score that rounding puts a hair
+                            // below the window goes to its lowest bin)
+                            const int rel = max((int)fmaf(c4, sc, k4[qb]), bottom4[qb]);
+                            lds_add_u32(hrow + (rel & (4 * SLOTS - 4)), 1u << (SM::CBITS * qb & 31));
+                            // a full list keeps overwriting its last entry (its block is redone anyway)
+                            uint2 ent;
+                            ent.x = __float_as_uint(sc); ent.y = (uint32_t)j;
+                            *(uint2*)(lists_h + (loff[qb] + 8u * (uint32_t)min(cnt[qb], LIST_CAP - 1))) = ent;
+                            ++cnt[qb];
+                        }
+                    }
+                }
+                grown |= cnt[qb] >= trig[qb];
+            }
+            if (__any(grown)) {
+                // a better lower bound from the histogram so far
+                float lo[QB], up[QB];
+                histogram_bound(lo, up);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    const float braw = lo[qb] * inv_c;
+                    lowraw[qb] = braw - fabsf(braw) * 1e-6f;
+                    trig[qb] = cnt[qb] <= LIST_CAP ? cnt[qb] + GROW : INT_MAX;
+                }
+            }
+            return nstores;
+    };
+    // The tile walk of stream_tiles<2>, except that the hand-over of a tile waits for its loads only,
+    // not for the list stores issued after them.
+    {
+        auto issue = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); };
+        int later = 0;
+        if (njt > 0) issue(0, kbuf);
+        for (int it = 0; it < njt; it += 2) {
+            wait_loads_then(later);
+            __syncthreads();
+            if (it + 1 < njt) issue(it + 1, kbuf1);
+            later = sweep_tile(it, kbuf);
+            if (it + 1 >= njt) break;
+            wait_loads_then(later);
+            __syncthreads();
+            if (it + 2 < njt) issue(it + 2, kbuf);
+            later = sweep_tile(it + 1, kbuf1);
+        }
+        __syncthreads();
+    }
+    __threadfence();      // the lists are read back below (same lanes, through L2)
+
+    // ---- solve and refinement on the lists -----------------------------------------------------
+    int any_over = 0;
+    if (active) {
+        float thr[QB], blo[QB], bhi[QB];
+        histogram_bound(thr, bhi);
+        int iters[QB], done[QB], mycnt[QB];
+        float f1_last[QB];
+        int nmax = 0;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            any_over |= (cnt[qb] > LIST_CAP);
+            mycnt[qb] = min(cnt[qb], LIST_CAP);
+            nmax = max(nmax, mycnt[qb]);
+            blo[qb] = thr[qb]; iters[qb] = 0; done[qb] = 0; f1_last[qb] = -1.f;
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) nmax = max(nmax, __shfl_xor(nmax, off));
+        // refinement (Sec. 3.2): evaluations of f, f', f'' over the listed scores; each lane walks
+        // its own lists, sixteen entries per row block at a time with all loads in flight together
+        for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
+            float F[QB], G[QB], Hs[QB];
+            uint32_t lastj[QB];
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) { F[qb] = G[qb] = Hs[qb] = 0.f; lastj[qb] = 0xffffffffu; }
+            for (int i0 = 0; i0 < nmax; i0 += 16) {
+                uint4 e[QB][8];
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        e[qb][u] = make_uint4(0u, 0u, 0u, 0u);
+                        if (i0 + 2 * u < mycnt[qb]) e[qb][u] = *(const uint4*)(lists_h + loff[qb] + (i0 + 2 * u) * 8);
+                    }
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        const uint32_t bits = (u & 1) ? e[qb][u >> 1].z : e[qb][u >> 1].x;
+                        const uint32_t j = (u & 1) ? e[qb][u >> 1].w : e[qb][u >> 1].y;
+                        const float y = fmaf(c, __uint_as_float(bits), -thr[qb]);
+                        if (i0 + u < mycnt[qb] && y > 0.f) {
+                            if constexpr (AM == ALPHA_15) { F[qb] = fmaf(y, y, F[qb]); G[qb] += y; Hs[qb] += 1.f; }
+                            else if constexpr (AM == ALPHA_20) { F[qb] += y; G[qb] += 1.f; }
+                            else {
+                                const float p2 = pow_r2<AM>(y, r);
+                                Hs[qb] += p2; G[qb] = fmaf(p2, y, G[qb]); F[qb] = fmaf(p2 * y, y, F[qb]);
+                            }
+                            // first evaluation, at tau_0 <= tau*: its tiles are the working mask
+                            if (sweep == 0 && j != lastj[qb]) { atomicOr(&wm[myrow * W + (j >> 5)], 1u << (j & 31)); lastj[qb] = j; }
+                        }
+                    }
+            }
+            int pending = 0;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const float f = xhalf_sum(F[qb]) - 1.f, g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
+                if (!done[qb]) {
+                    iters[qb] += 1;
+                    f1_last[qb] = -r * g;
+                    if (fabsf(f) <= p.tol) done[qb] = 1;
+                    else {
+                        const float cand_tau = hybrid_step(thr[qb], f, g, hs, r, p.alpha, blo[qb], bhi[qb]);
+                        if (fabsf(cand_tau - thr[qb]) < p.tol) done[qb] = 1;
+                        thr[qb] = cand_tau;
+                    }
+                    pending |= !done[qb];
+                }
+            }
+            if (!__any(pending)) break;
+        }
+        if (h == 0) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const long gi = (long)bh * N + qw0 + 32 * qb + n;
+                p.tau[gi] = thr[qb];
+                p.rs_lo[gi] = blo[qb];
+                p.rs_hi[gi] = bhi[qb];
+                p.rs_state[gi] = iters[qb] | (done[qb] << 16);
+                p.rs_f1[gi] = f1_last[qb];
+            }
+        }
+    }
+    if (__any(any_over) && lane == 0) atomicOr(&over_s[myrow], 1);
+    __syncthreads();
+    for (int i = tid; i < MR * W; i += THREADS)
+        if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
+    if (tid < MR && I * MR + tid < T) p.oflag[(long)bh * T + (long)I * MR + tid] = over_s[tid];
+    {
+        int nover = 0;
+        if (tid == 0)
+            for (int i = 0; i < MR; ++i) nover += over_s[i];
+        const int slot[2] = {0, 8};
+        const unsigned long long val[2] = {ntile_done * QB, (unsigned long long)nover};
         flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
     }
 }

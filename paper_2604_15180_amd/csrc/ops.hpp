@@ -59,6 +59,12 @@ struct Ops {
         }
         {
             ScopedKernelTime t(EA_TIMER_TAU, s);
+            // one dense sweep that lists each row's candidate scores, then histogram, solve and
+            // refinement on the lists
+            constexpr int QBL = (E::EPL == 8) ? QB_TAU : 1;
+            rc = launch(tau_list_kernel<E, D, QBL, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU, QBL), NW_TAU * 64, s, p);
+            if (rc) return rc;
+            // sweep-based fallback for row blocks whose lists overflowed (exits at once elsewhere);
             // two rows per lane (packed 16-bit histogram counters) while a bin cannot overflow
             if (QB_TAU == 2 && E::EPL == 8 && p.N < 65536)
                 rc = launch(tau_kernel<E, D, QB_TAU, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU, QB_TAU), NW_TAU * 64, s, p);

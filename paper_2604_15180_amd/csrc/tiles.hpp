@@ -166,6 +166,28 @@ EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave
     }
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
+// The same hand-over when the wave has issued `later` vector-memory instructions (stores) after the
+// tile's loads: vector-memory operations complete in issue order, so the loads have landed once at
+// most `later` operations are outstanding, and the wave need not sit through the round trip of
+// stores it does not depend on.  (The counter has 6 bits; waiting for fewer than `later` is safe.)
+EA_DEV void wait_loads_then(int later) {
+    if (later >= 16) {
+        if (later >= 48) asm volatile("s_waitcnt vmcnt(48)" ::: "memory");
+        else if (later >= 32) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+        else if (later >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    } else if (later >= 4) {
+        if (later >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        else if (later >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if (later >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    } else {
+        if (later >= 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+        else if (later == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else if (later == 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+}
 
 // LDS word += v, &= v without a returned value.  Written as instructions of their own because the
 // compiler makes an LDS atomic wait for every direct global->LDS load in flight (it cannot tell

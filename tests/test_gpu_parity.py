@@ -135,6 +135,27 @@ def test_drifting_row_maximum(ea, dtype, rise, causal):
     assert iters.max().item() <= 12
 
 
+@pytest.mark.parametrize("dtype,N", [("bf16", 2048), ("f32", 1024)])
+def test_flat_attention_overflows_candidate_lists(ea, dtype, N):
+    # tiny scores: every key lies within one unit of the row maximum, so rows with more visible
+    # keys than their candidate lists hold are flagged and redone by the sweep-based threshold
+    # kernel, while the short first rows of the same head stay on the list path
+    B, H, d, alpha, causal = 1, 2, 64, 1.5, True
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, dtype, 0.3, seed=61)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, dtype, causal, False), dtype=torch.uint8, device="cuda")
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=ws)
+    torch.cuda.synchronize()
+    st = ea.read_stats(ws)
+    print("  flat attention:", {k_: st[k_] for k_ in ("list_overflow_blocks", "tau_subtiles")}, flush=True)
+    assert 0 < st["list_overflow_blocks"] < B * H * (N // 64)
+    _, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="flat")
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask)
+    torch.cuda.synchronize()
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="flat")
+    print("  flat", info, ginfo, "mean iters", iters.float().mean().item(), flush=True)
+
+
 def test_c2_shape_two_heads(ea):
     # configs[1]: alpha=1.5 bf16 B=4 H=16 N=4096 d=64 causal sigma=1.5, on 2 of its 64 heads
     run_case(ea, 1, 2, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
