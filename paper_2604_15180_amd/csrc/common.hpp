@@ -135,6 +135,27 @@ EA_DEV void stream_tiles_split(int n1, int n, char* buf0, char* buf1, IssueF iss
     __syncthreads();
 }
 
+// The walk with NB >= 2 tile buffers in one LDS ring: tiles run NB - 1 ahead of the math, so a tile
+// has NB - 1 tile times to arrive.  LPW = direct loads each wave issues per tile.  Vector-memory
+// operations complete in issue order, so tile `it` has landed once at most the loads of the tiles
+// issued after it are outstanding (other stores a wave issues meanwhile only make the wait longer).
+template <int K> EA_DEV void wait_vm_at_most() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(K) : "memory"); }
+template <int NB, int LPW, class IssueF, class ComputeF>
+EA_DEV void stream_tiles_ring(int n, char* ring, int tile_bytes, IssueF issue, ComputeF compute) {
+    static_assert(NB >= 2 && NB <= 4 && (NB - 2) * LPW < 64, "ring depth");
+    for (int i = 0; i < NB - 1 && i < n; ++i) issue(i, ring + i * tile_bytes);
+    for (int it = 0; it < n; ++it) {
+        const int ahead = min(NB - 2, n - 1 - it);         // tiles issued after tile `it`
+        if (NB >= 4 && ahead == 2) wait_vm_at_most<2 * LPW>();
+        else if (NB >= 3 && ahead == 1) wait_vm_at_most<LPW>();
+        else wait_vm_at_most<0>();
+        __syncthreads();     // tile `it` has landed for every wave; everyone is done with tile it-1
+        if (it + NB - 1 < n) issue(it + NB - 1, ring + ((it + NB - 1) % NB) * tile_bytes);
+        compute(it, ring + (it % NB) * tile_bytes);
+    }
+    __syncthreads();
+}
+
 // Executed-work counters.  The workspace starts with STATS_COPIES copies of the STATS_WORDS
 // counters (a counter's value is the sum over the copies).  The waves of a group first add into
 // LDS; one thread per counter then issues one global atomic, aimed at the copy picked by the

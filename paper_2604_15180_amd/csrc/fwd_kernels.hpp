@@ -306,7 +306,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
         const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
         const float my_t0 = fmaxf(tau_h - slack, fmaf(c, mx, -1.f));
         const float my_hi = tau_h + hb + slack;
-        const float o_t0 = __shfl_xor(my_t0, 32), o_hi = __shfl_xor(my_hi, 32);
+        const float o_t0 = xhalf_other(my_t0, h), o_hi = xhalf_other(my_hi, h);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const bool mine = (h == (QB == 2 ? qb : 0));
@@ -429,12 +429,13 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     using elem = typename E::elem;
     constexpr int THREADS = NW * 64, BR = SM::BR, MR = SM::MR, SLOTS = SM::SLOTS;
     constexpr int GROW = 24;              // list growth (entries per lane) between two histogram solves
-    __shared__ __align__(1024) char kbuf[KT::BYTES];
-    __shared__ __align__(1024) char kbuf_b[NBUF == 2 ? KT::BYTES : 1024];
+    __shared__ __align__(1024) char kring[NBUF * KT::BYTES];
     __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
-    __shared__ uint32_t wm[MR * MAX_W];
-    __shared__ int over_s[MR];
-    __shared__ unsigned long long blk_stats[4];
+    // used only once the sweep is over: they live in the key-tile ring
+    static_assert(MR * MAX_W * 4 + MR * 4 + 64 <= NBUF * KT::BYTES, "post-sweep arrays must fit in the ring");
+    uint32_t* const wm = (uint32_t*)kring;
+    int* const over_s = (int*)(kring + MR * MAX_W * 4);
+    unsigned long long* const blk_stats = (unsigned long long*)(kring + MR * MAX_W * 4 + ((MR * 4 + 7) & ~7));
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -453,9 +454,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
-    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;
     for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
-    if (tid < MR) over_s[tid] = 0;
 
     // this lane's lists: byte offsets inside the head's block of lists (< 2^32: N <= 131072)
     char* const lists_h = (char*)p.lists + (size_t)bh * N * (2 * LIST_CAP * 8);
@@ -486,7 +485,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                                                                   SM::CBITS * sq & 31, hb, r) + origin;
         const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
         const float my_lo = fmaxf(tau_h - slack, fmaf(c, mx, -1.f)), my_up = tau_h + hb + slack;
-        const float o_lo = __shfl_xor(my_lo, 32), o_up = __shfl_xor(my_up, 32);
+        const float o_lo = xhalf_other(my_lo, h), o_up = xhalf_other(my_up, h);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const bool mine = (h == (QB == 2 ? qb : 0));
@@ -498,37 +497,41 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     f32x16 C[2][QB];
     unsigned long long ntile_done = 0;
     const float inv_c = 1.f / c, cb = c * NB, c4 = 4.f * cb;
-    char* const kbuf1 = NBUF == 2 ? kbuf_b : kbuf;
-    // Tile body; returns the number of vector-memory instructions (list stores) the wave issued.
-    auto sweep_tile = [&](int j, const char* buf) -> int {
-            if (j >= wjt) return 0;
-            int nstores = 0;
+    auto sweep_tile = [&](int j, const char* buf) {
+            if (j >= wjt) return;
             stage1<E, D, QB>(C, buf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
-            bool grown = false;
+            // per row block: maxima of the four groups of 8 registers, of the lane, of the row
+            float gm[QB][4], lm[QB], tm[QB];
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
-                float gm[4];                            // maxima of the four groups of 8 registers
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    gm[g] = C[g >> 1][qb][8 * (g & 1)];
+                    gm[qb][g] = C[g >> 1][qb][8 * (g & 1)];
 #pragma unroll
-                    for (int v = 1; v < 8; ++v) gm[g] = fmaxf(gm[g], C[g >> 1][qb][8 * (g & 1) + v]);
+                    for (int v = 1; v < 8; ++v) gm[qb][g] = fmaxf(gm[qb][g], C[g >> 1][qb][8 * (g & 1) + v]);
                 }
-                const float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
-                const float tm = xhalf_max(lm);
-                // the window of live bins follows the running maximum (see tau_kernel)
-                const bool rise = tm > run[qb];
-                if (__any(rise)) {
+                lm[qb] = fmaxf(fmaxf(gm[qb][0], gm[qb][1]), fmaxf(gm[qb][2], gm[qb][3]));
+            }
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) tm[qb] = xhalf_max(lm[qb]);
+            bool rise_any = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) rise_any |= tm[qb] > run[qb];
+            if (__any(rise_any)) {
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    // the window of live bins follows the running maximum (see tau_kernel)
+                    const bool rise = tm[qb] > run[qb];
                     int first = 0, last = -1;           // bins to clear: first..last (none)
                     if (rise) {
-                        run[qb] = tm;
-                        int nt = (int)floorf(fminf(fmaxf(cb * tm, -1e9f), 1e9f));
+                        run[qb] = tm[qb];
+                        int nt = (int)floorf(fminf(fmaxf(cb * tm[qb], -1e9f), 1e9f));
                         int a_lo = nt - (SLOTS - 1), rot = a_lo & (SLOTS - 1);
                         float kk = 4.f * (float)(rot - a_lo);
                         // the maximum itself must land in the window's top slot, not wrap past it
-                        if ((int)fmaf(c4, tm, kk) >= 4 * rot + 4 * SLOTS) {
+                        if ((int)fmaf(c4, tm[qb], kk) >= 4 * rot + 4 * SLOTS) {
                             nt += 1; a_lo += 1; rot = a_lo & (SLOTS - 1); kk = 4.f * (float)(rot - a_lo);
                         }
                         if (a_top[qb] != INT_MIN) { first = max(a_top[qb], nt - SLOTS) + 1; last = nt; }
@@ -548,19 +551,29 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                         }
                     }
                 }
-                // candidates: raw scores at or above the row's current lower bound
-                const float low = fmaxf(run[qb] - inv_c, lowraw[qb]);
-                if (!__any(lm >= low)) continue;
+            }
+            // candidates: raw scores at or above the row's current lower bound; most tiles of a
+            // sparse row block hold none, and leave here
+            float lowv[QB];
+            bool maybe = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                lowv[qb] = fmaxf(run[qb] - inv_c, lowraw[qb]);
+                maybe |= lm[qb] >= lowv[qb];
+            }
+            if (!__any(maybe)) return;
+            bool grown = false;
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                const float low = lowv[qb];
+                if (!__any(lm[qb] >= low)) continue;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    if (!__any(gm[g] >= low)) continue;
+                    if (!__any(gm[qb][g] >= low)) continue;
 #pragma unroll
                     for (int v = 0; v < 8; ++v) {
                         const float sc = C[g >> 1][qb][8 * (g & 1) + v];
-                        const bool hit = sc >= low;
-                        if (!__any(hit)) continue;
-                        ++nstores;
-                        if (hit) {
+                        if (sc >= low) {
                             // slot of the score's bin, times 4 (a score that rounding puts a hair
                             // below the window goes to its lowest bin)
                             const int rel = max((int)fmaf(c4, sc, k4[qb]), bottom4[qb]);
@@ -586,27 +599,12 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                     trig[qb] = cnt[qb] <= LIST_CAP ? cnt[qb] + GROW : INT_MAX;
                 }
             }
-            return nstores;
     };
-    // The tile walk of stream_tiles<2>, except that the hand-over of a tile waits for its loads only,
-    // not for the list stores issued after them.
-    {
-        auto issue = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); };
-        int later = 0;
-        if (njt > 0) issue(0, kbuf);
-        for (int it = 0; it < njt; it += 2) {
-            wait_loads_then(later);
-            __syncthreads();
-            if (it + 1 < njt) issue(it + 1, kbuf1);
-            later = sweep_tile(it, kbuf);
-            if (it + 1 >= njt) break;
-            wait_loads_then(later);
-            __syncthreads();
-            if (it + 2 < njt) issue(it + 2, kbuf);
-            later = sweep_tile(it + 1, kbuf1);
-        }
-        __syncthreads();
-    }
+    stream_tiles_ring<NBUF, KT::NINST / NW>(njt, kring, KT::BYTES,
+        [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); }, sweep_tile);
+    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;      // (the walk ended with a barrier: the ring is free)
+    if (tid < MR) over_s[tid] = 0;
+    __syncthreads();
     __threadfence();      // the lists are read back below (same lanes, through L2)
 
     // ---- solve and refinement on the lists -----------------------------------------------------

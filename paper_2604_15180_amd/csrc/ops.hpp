@@ -12,6 +12,9 @@ namespace ea {
 constexpr int QB = 1;        // 32*QB owned rows per wave
 // waves per work-group (NW) and LDS buffer sets (NBUF) per kernel; a group owns 32*QB*NW rows
 constexpr int NW_TAU = 4, NBUF_TAU = 2, QB_TAU = 2;
+// list-based threshold kernel: 8 waves (512 rows with two rows per lane), one group per CU, a ring
+// of 4 key tiles so that a tile has three tile times to arrive
+constexpr int NW_TAUL = 4, NBUF_TAUL = 3;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
 constexpr int NW_DQ = 2, NBUF_DQ = 2;
 constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
@@ -62,7 +65,8 @@ struct Ops {
             // one dense sweep that lists each row's candidate scores, then histogram, solve and
             // refinement on the lists
             constexpr int QBL = (E::EPL == 8) ? QB_TAU : 1;
-            rc = launch(tau_list_kernel<E, D, QBL, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU, QBL), NW_TAU * 64, s, p);
+            constexpr int NBL = (E::EPL == 8) ? NBUF_TAUL : 2;       // fp32 tiles are twice as large
+            rc = launch(tau_list_kernel<E, D, QBL, AM, NBINS, NW_TAUL, NBL>, groups(p, NW_TAUL, QBL), NW_TAUL * 64, s, p);
             if (rc) return rc;
             // sweep-based fallback for row blocks whose lists overflowed (exits at once elsewhere);
             // two rows per lane (packed 16-bit histogram counters) while a bin cannot overflow

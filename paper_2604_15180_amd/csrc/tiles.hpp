@@ -166,29 +166,6 @@ EA_DEV void issue_rows(char* lds, const typename E::elem* g, long row0, int wave
     }
 }
 EA_DEV void wait_loads() { __builtin_amdgcn_s_waitcnt(0x0f70); }   // vmcnt(0) only (gfx9 encoding)
-// The same hand-over when the wave has issued `later` vector-memory instructions (stores) after the
-// tile's loads: vector-memory operations complete in issue order, so the loads have landed once at
-// most `later` operations are outstanding, and the wave need not sit through the round trip of
-// stores it does not depend on.  (The counter has 6 bits; waiting for fewer than `later` is safe.)
-EA_DEV void wait_loads_then(int later) {
-    if (later >= 16) {
-        if (later >= 48) asm volatile("s_waitcnt vmcnt(48)" ::: "memory");
-        else if (later >= 32) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
-        else if (later >= 24) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    } else if (later >= 4) {
-        if (later >= 12) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-        else if (later >= 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else if (later >= 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    } else {
-        if (later >= 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-        else if (later == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else if (later == 1) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-}
-
 // LDS word += v, &= v without a returned value.  Written as instructions of their own because the
 // compiler makes an LDS atomic wait for every direct global->LDS load in flight (it cannot tell
 // that they target another array), which would stall a histogram update until the next tile has
@@ -423,7 +400,17 @@ EA_DEV float wave_max(float v) {
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
     return v;
 }
-EA_DEV float xhalf_max(float v) { return fmaxf(v, __shfl_xor(v, 32)); }
-EA_DEV float xhalf_sum(float v) { return v + __shfl_xor(v, 32); }
+// Exchange between the two lanes (n, n + 32) of an owned row with v_permlane32_swap, an ALU
+// instruction: as an LDS permute the exchange queues behind every tile read of the CU's other waves.
+// Swapping a register with a copy of itself leaves (low half, low half) in one and (high half,
+// high half) in the other, so any symmetric combination of the two is the row's value in all lanes.
+EA_DEV void xhalf_both(float v, float& lo, float& hi) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    lo = __uint_as_float(r[0]); hi = __uint_as_float(r[1]);
+}
+EA_DEV float xhalf_max(float v) { float a, b; xhalf_both(v, a, b); return fmaxf(a, b); }
+EA_DEV float xhalf_sum(float v) { float a, b; xhalf_both(v, a, b); return a + b; }
+// the value the other lane of the row holds
+EA_DEV float xhalf_other(float v, int h) { float a, b; xhalf_both(v, a, b); return h ? a : b; }
 
 }  // namespace ea
