@@ -46,6 +46,27 @@ def executed_flops(stats, d):
     return parts
 
 
+def sustained_mfma_tflops(ea, dev):
+    """Measured matrix-core ceiling: the library's MFMA probe (independent 32x32x16 fp16 MFMAs from
+    registers, no memory traffic) on N(0,1) operands, timed with events over >= 20 ms so that the
+    clock has settled under the power limit; with one and with two wavefronts per SIMD."""
+    g = torch.Generator(device="cpu").manual_seed(99)
+    data = torch.randn(8192, generator=g).to(torch.float16).to(dev)
+    sink = torch.empty(512 * 256, dtype=torch.float32, device=dev)
+    out = {}
+    for name, groups in (("one_wave_per_simd", 256), ("two_waves_per_simd", 512)):
+        iters = 40000
+        ea.entmax_attn_mfma_probe(data, sink, groups, 2000)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = ea.entmax_attn_mfma_probe(data, sink, groups, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return out
+
+
 def block_sparsity(mask, T, causal):
     m = mask.cpu().numpy().view(np.uint32)
     set_bits = int(np.unpackbits(m.view(np.uint8)).sum())
@@ -214,6 +235,10 @@ def main():
                     kernels={k: dict(avg_ms=round(v[0] / v[1], 3), launches=v[1],
                                      tflops=(round(exec_total[k] / len(points) / (v[0] / v[1] * 1e-3) / 1e12, 1)
                                              if k in exec_total else None)) for k, v in kt.items()})
+
+    # the same matrix cores without any of the kernels' other work, for context: Gaussian operands,
+    # sustained; `peak` above stays the published figure
+    roofline["sustained_mfma_tflops_measured"] = sustained_mfma_tflops(ea, dev)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

@@ -143,6 +143,17 @@ enum {
 int entmax_attn_timer_enable(int on);
 int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);
 
+/*
+ * Matrix-core rate probe (measurement aid: the ceiling the benchmark prices the kernels against
+ * besides the published peak).  Launches `groups` work-groups of 4 wavefronts; every wavefront
+ * issues iters * 32 independent 32x32x16 fp16 MFMAs (32768 flops each) on operands taken from
+ * `data` (device pointer to 8192 fp16 values filled by the caller; the sustained clock depends on
+ * the operand values) and writes one float per thread to `sink` (groups * 256 floats).  256 groups
+ * put one wavefront on every SIMD of an MI355X, 512 two.  The caller times the launch.
+ * Total flops = groups * 4 * iters * 32 * 32768.
+ */
+int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters, void* hip_stream);
+
 /* Histogram bins B and work-group query rows used by the threshold kernel (introspection for
  * tests and the benchmark report). */
 int entmax_attn_histogram_bins(void);

@@ -58,6 +58,8 @@ def lib():
         L.entmax_attn_timer_enable.argtypes = [ci]
         L.entmax_attn_timer_read.restype = ci
         L.entmax_attn_timer_read.argtypes = [ctypes.POINTER(cf), ctypes.POINTER(ci), ci]
+        L.entmax_attn_mfma_probe.restype = ci
+        L.entmax_attn_mfma_probe.argtypes = [vp, vp, ci, ci, vp]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
         L.entmax_attn_strerror.argtypes = [ci]
         _lib = L
@@ -152,6 +154,17 @@ def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspa
     _check(rc)
     entmax_attn_bwd.last_workspace = ws
     return dQ, dK, dV
+
+
+def entmax_attn_mfma_probe(data, sink, groups, iters):
+    """Enqueue the matrix-core rate probe on the current stream (data: >= 8192 fp16 values on the
+    GPU, sink: >= groups * 256 floats). Returns the flops the launch performs."""
+    if not (data.is_cuda and sink.is_cuda and data.dtype == torch.float16 and data.numel() >= 8192
+            and sink.dtype == torch.float32 and sink.numel() >= groups * 256):
+        raise ValueError("entmax_attn_mfma_probe: data = 8192 fp16 values, sink = groups * 256 floats, both on the GPU")
+    _check(lib().entmax_attn_mfma_probe(_ptr(data), _ptr(sink), int(groups), int(iters),
+                                         ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
+    return float(groups) * 4 * iters * 32 * 32768.0
 
 
 def entmax_attn_timer_enable(on):

@@ -112,6 +112,29 @@ Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int caus
 
 }  // namespace
 
+// Matrix-core rate probe: every wave issues `iters` rounds of 32 independent 32x32x16 fp16 MFMAs
+// on operands read from `data` (8192 halves, which the caller fills, e.g. with Gaussian values:
+// the sustained clock of the chip depends on how many operand bits toggle).  No memory traffic in
+// the loop; 4 waves per group, so a grid of 256 (512) groups puts one (two) waves on every SIMD.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const f16x8* data, float* sink, int iters) {
+    f32x16 acc[4];
+    for (int a = 0; a < 4; ++a)
+        for (int v = 0; v < 16; ++v) acc[a][v] = 0.f;
+    f16x8 A[8], B[4];
+    for (int i = 0; i < 8; ++i) A[i] = data[(threadIdx.x + 97 * i) & 1023];
+    for (int i = 0; i < 4; ++i) B[i] = data[(threadIdx.x * 7 + 131 * i + 5) & 1023];
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int a = 0; a < 4; ++a) acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_f16(A[(u + a) & 7], B[a], acc[a], 0, 0, 0);
+    }
+    float t = 0.f;
+    for (int a = 0; a < 4; ++a)
+        for (int v = 0; v < 16; ++v) t += acc[a][v];
+    sink[blockIdx.x * 256 + threadIdx.x] = t;
+}
+
 namespace ea {
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 void timer_mark(int slot, int which, hipStream_t s) {
@@ -213,6 +236,14 @@ int entmax_attn_timer_read(float* ms_sum, int* launches, int slots) {
             launches[k] += 1;
         }
     g_timer.ncalls = 0;
+    return EA_OK;
+}
+
+int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters, void* hip_stream) {
+    if (!data || !sink) return EA_ERR_NULL;
+    if (groups <= 0 || groups > 4096 || iters <= 0) return EA_ERR_SHAPE;
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(groups), dim3(256), 0, (hipStream_t)hip_stream, (const f16x8*)data, sink, iters);
+    EA_HIP(hipGetLastError());
     return EA_OK;
 }
 
