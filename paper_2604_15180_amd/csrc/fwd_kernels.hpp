@@ -25,25 +25,25 @@ EA_DEV float solve_histogram(const uint32_t* H, int rot, int shift, float h, flo
         return (float)(BITS == 32 ? w : (w & ((1u << (BITS & 31)) - 1u)));
     };
     if constexpr (AM == ALPHA_15 || AM == ALPHA_20) {
-        // descending scan keeping S0, S1, S2 of the active bins; the active set is the largest
-        // one whose closed-form root lies below the left edge of its lowest non-empty bin
-        float S0 = 0.f, S1 = 0.f, S2 = 0.f, best = -h;
+        // Descending scan keeping S0, S1, S2 of the bins met so far.  The active set is the largest
+        // one whose root lies below the left edge e of its lowest non-empty bin, i.e. (f_h falls
+        // with tau) the largest one with f_h(e) < 0; f_h(e) is a polynomial in the three sums, so
+        // the scan needs no division, and the root is formed once, from the sums of that set.
+        float S0 = 0.f, S1 = 0.f, S2 = 0.f, B0 = 0.f, B1 = 0.f, B2 = 0.f;
+#pragma unroll 8
         for (int k = SLOTS - 1; k >= 0; --k) {
             const float cnt = count(k);
-            if (cnt == 0.f) continue;
             const float e = k * h;
-            S0 += cnt; S1 += cnt * e; S2 += cnt * e * e;
-            float t;
-            if constexpr (AM == ALPHA_20) {
-                t = (S1 - 1.f) / S0;
-            } else {
-                const float mean = S1 / S0;
-                const float disc = fmaxf(mean * mean - (S2 - 1.f) / S0, 0.f);
-                t = mean - sqrtf(disc);
-            }
-            if (t < e) best = t;
+            S0 += cnt; S1 = fmaf(cnt, e, S1); S2 = fmaf(cnt * e, e, S2);
+            float fe;
+            if constexpr (AM == ALPHA_20) fe = S1 - e * S0 - 1.f;
+            else fe = fmaf(e, fmaf(e, S0, -2.f * S1), S2) - 1.f;
+            if (cnt > 0.f && fe < 0.f) { B0 = S0; B1 = S1; B2 = S2; }
         }
-        return best;
+        if (B0 == 0.f) return -h;
+        if constexpr (AM == ALPHA_20) return (B1 - 1.f) / B0;
+        const float mean = B1 / B0;
+        return mean - sqrtf(fmaxf(mean * mean - (B2 - 1.f) / B0, 0.f));
     } else {
         // general alpha: bisection of f_h on [-h, (SLOTS-1) h], then Newton from the left end
         // (f_h is convex and decreasing for alpha <= 2, so Newton from the left is monotone)
