@@ -456,14 +456,15 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
     for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
 
-    // this lane's lists: byte offsets inside the head's block of lists (< 2^32: N <= 131072)
+    // this lane's lists (per-lane 64-bit addresses: a scalar base would have to be fetched from
+    // spilled scalar registers at every append)
     char* const lists_h = (char*)p.lists + (size_t)bh * N * (2 * LIST_CAP * 8);
-    uint32_t loff[QB];
+    char* lptr[QB];
     int cnt[QB], trig[QB], a_top[QB], bottom4[QB];
     float run[QB], lowraw[QB], k4[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        loff[qb] = (uint32_t)(((active ? qw0 : 0) + 32 * qb + n) * 2 + h) * (uint32_t)(LIST_CAP * 8);
+        lptr[qb] = lists_h + (size_t)(((active ? qw0 : 0) + 32 * qb + n) * 2 + h) * (size_t)(LIST_CAP * 8);
         cnt[qb] = 0; trig[qb] = GROW;
         run[qb] = -INFINITY; lowraw[qb] = -3.0e38f;
         k4[qb] = 0.f; bottom4[qb] = 0; a_top[qb] = INT_MIN;
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                             // a full list keeps overwriting its last entry (its block is redone anyway)
                             uint2 ent;
                             ent.x = __float_as_uint(sc); ent.y = (uint32_t)j;
-                            *(uint2*)(lists_h + (loff[qb] + 8u * (uint32_t)min(cnt[qb], LIST_CAP - 1))) = ent;
+                            *(uint2*)(lptr[qb] + 8u * (uint32_t)min(cnt[qb], LIST_CAP - 1)) = ent;
                             ++cnt[qb];
                         }
                     }
@@ -638,7 +639,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
                         e[qb][u] = make_uint4(0u, 0u, 0u, 0u);
-                        if (i0 + 2 * u < mycnt[qb]) e[qb][u] = *(const uint4*)(lists_h + loff[qb] + (i0 + 2 * u) * 8);
+                        if (i0 + 2 * u < mycnt[qb]) e[qb][u] = *(const uint4*)(lptr[qb] + (i0 + 2 * u) * 8);
                     }
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
@@ -947,7 +948,21 @@ template <class E>
 __global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
     __shared__ float part[4];
     float m = 0.f;
-    for (long i = (blockIdx.x * 256L + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
+    const long stride = (long)gridDim.x * 256 * 8;
+    long i = (blockIdx.x * 256L + threadIdx.x) * 8;
+    if constexpr (sizeof(typename E::elem) == 2) {
+        // four 16-byte loads in flight per thread: one at a time leaves the read latency-bound
+        for (; i + 3 * stride < n; i += 4 * stride) {
+            u32x4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) w[u] = *(const u32x4*)(x + i + u * stride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)((const typename E::elem*)&w[u])[e]));
+        }
+    }
+    for (; i < n; i += stride) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) m = fmaxf(m, fabsf((float)x[i + e]));
     }
