@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak (published)
 # HBM bytes per launch (fetched + written) on the default workload, from the FETCH_SIZE / WRITE_SIZE
 # passes summarised in profiles/bench_c3_n16k_counters.md (scaled by the library's own copy kernel)
-HBM_TRAFFIC_BYTES = {"tau": 1.04e9, "out": 1.29e9, "dq": 1.78e9, "dkdv": 1.60e9}
+HBM_TRAFFIC_BYTES = {"tau": 1.45e9, "out": 1.39e9, "dq": 1.76e9, "dkdv": 1.60e9}
 METRIC = "effective fwd+bwd TFLOP/s vs block sparsity at N=16k; mean τ iterations/row"
 
 

@@ -7,7 +7,8 @@
  *     O = P V                                                          (Eq. 2)
  * with tau solved per row from an on-chip histogram of the scores within one unit of the row
  * maximum (Eq. 6-9, Prop. 1) followed by a safeguarded Halley/Newton refinement (Sec. 3.1-3.3,
- * Alg. 1), and the gradient of
+ * Alg. 1) whose evaluations of f run over the row's candidate scores, listed during the one dense
+ * sweep of Q K^T, and the gradient of
  * sum(O * dO) with respect to Q, K, V (Sec. 3.3 "Backward pass", Alg. 2-3).  Key tiles
  * whose probabilities are all zero are recorded in a bit-packed block mask (App. C.4) and
  * skipped in the output phase and in both backward kernels.
@@ -57,12 +58,12 @@ enum {
 enum {
     /* units: 64x32 score sub-tiles (64 streamed rows x 32 register-resident rows), the piece one
      * wavefront computes per MFMA block pair; one matmul on a sub-tile is 2*64*32*d flops */
-    EA_STAT_TAU_TILES = 0,   /* sub-tiles scored by the maximum+histogram sweep and by scores-only refinement sweeps (1 matmul each) */
+    EA_STAT_TAU_TILES = 0,   /* sub-tiles scored by the dense threshold sweep and by any sweep-based refinement (1 matmul each) */
     EA_STAT_OUT_TILES = 1,   /* sub-tiles scored by the output phase (2 matmuls each where P != 0) */
     EA_STAT_DELTA_TILES = 2, /* unused (delta is found inside the dQ sweep) */
     EA_STAT_DQ_TILES = 3,    /* sub-tiles visited by the dQ kernel (4 matmuls each) */
     EA_STAT_DKDV_TILES = 4,  /* sub-tiles visited by the dK/dV kernel (4 matmuls each) */
-    EA_STAT_SWEEPS = 5,      /* work-groups of the tau kernel (each runs one refinement sweep) */
+    EA_STAT_SWEEPS = 5,      /* work-groups that ran the sweep-based threshold kernel (each runs one refinement sweep) */
     EA_STAT_MASK_TILES = 6,  /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
     EA_STAT_OUT_PV_TILES = 7, /* sub-tiles of the output phase whose P V product was issued */
     EA_STAT_LIST_OVERFLOW = 8 /* 64-row blocks whose candidate lists overflowed (redone by the sweep-based kernel) */
@@ -76,8 +77,9 @@ int entmax_attn_mask_tile(void);
 size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, int causal, int is_bwd);
 
 /*
- * Forward (Alg. 1): row maximum and histogram (one dense sweep) -> first refinement step
- * (+ working mask) -> output, whose row sums serve as the next evaluation of f.
+ * Forward (Alg. 1): row maximum, histogram and candidate lists (one dense sweep) -> histogram
+ * solve and refinement on the lists (+ working mask) -> output, whose row sums check f once more.
+ * Rows with more candidates than a list holds (512 per row) are redone by sweep-based refinement.
  *   Q, K, V     in   [B,H,N,d] of `dtype`
  *   O           out  [B,H,N,d] float32
  *   tau         out  [B,H,N]   float32, raw convention: P = [(alpha-1) S - tau]_+^{1/(alpha-1)}
@@ -86,8 +88,8 @@ size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, i
  *                    bits of tiles above the causal diagonal and padding bits are 0
  *   iters       out  [B,H,N] int32, may be NULL: number of refinement iterations the row
  *                    needed; one iteration = one evaluation of f over the true scores followed
- *                    by one update (Sec. 3.3 Phase 3); the evaluation that the output phase
- *                    yields as its row sums counts as one
+ *                    by one update (Sec. 3.3 Phase 3); the check that the output phase gets
+ *                    from its row sums counts only where it moved tau
  * The first EA_STATS_COPIES * EA_STATS_WORDS uint64 of `workspace` are zeroed by the call and
  * then hold the executed-tile counters of this call (EA_STAT_*, summed over the copies),
  * readable after the stream has drained.
@@ -133,7 +135,7 @@ int entmax_attn_last_hip_error(void);
 #define EA_TIMER_SLOTS 8
 enum {
     EA_TIMER_FWD_PREP = 0,  /* fp16 copy of V (bf16 inputs) */
-    EA_TIMER_TAU = 1,       /* maximum + histogram sweep, histogram solve, first refinement step */
+    EA_TIMER_TAU = 1,       /* dense sweep (maximum, histogram, candidate lists), solve, refinement; fallback kernel */
     EA_TIMER_OUT = 2,       /* phase 4 and the rest of the refinement */
     EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
     EA_TIMER_BWD_PREP = 4,  /* max |dO| and the fp16 copies of K, Q, V, dO (bf16 inputs) */
