@@ -39,7 +39,7 @@ constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, d, delta, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
+    size_t stats, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
 };
 
 // element size of the stage-2 copies
@@ -72,6 +72,7 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.c = off; off += align256(BH * N * d * t_elem(t));
     L.d = off; off += align256(BH * N * d * t_elem(t));
     L.delta = off; off += align256(BH * N * 4);
+    L.ntau = off; off += align256(BH * N * 4);
     L.mask = off; off += align256(BH * T * W * 4);               // rebuilt mask (mask == NULL)
     L.wmask = off; off += align256(BH * T * W * 4);
     L.total = off;
@@ -105,6 +106,12 @@ Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int caus
     p.inv_sqrt_d = 1.f / sqrtf((float)d);
     p.c = (alpha - 1.f) * p.inv_sqrt_d;
     p.r = 1.f / (alpha - 1.f);
+    int ex = 0;
+    const float mant = frexpf(p.c, &ex);          // c = mant * 2^ex, 0.5 <= mant < 1
+    p.kappa = ldexpf(1.f, ex - 1);
+    p.rho = 2.f * mant;
+    p.rho_p = powf(p.rho, p.r);
+    p.rho_u = powf(p.rho, p.r - 1.f);
     p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
     p.max_sweeps = MAX_SWEEPS;
     return p;
@@ -200,6 +207,7 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     p.stats = (unsigned long long*)(ws + L.stats);
     void* const copies[4] = {ws + L.a, ws + L.b, ws + L.c, ws + L.d};
     p.delta = (float*)(ws + L.delta);
+    p.ntau = (float*)(ws + L.ntau);
     p.wmask = (int32_t*)(ws + L.wmask);
     const bool rebuild = (block_mask == nullptr);
     p.mask = rebuild ? (int32_t*)(ws + L.mask) : const_cast<int32_t*>(block_mask);

@@ -275,7 +275,11 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     for (int qb = 0; qb < QB; ++qb) {
         const float dn = xhalf_sum(den[qb]);
         const float drel = dn > 0.f ? xhalf_sum(num[qb]) / dn : 0.f;      // delta - e
-        if (h == 0 && active) p.delta[(long)bh * N + qw0 + 32 * qb + n] = drel + ctr[qb];
+        if (h == 0 && active) {
+            // for the dK/dV kernel, as the biases its two stage-1 products start from
+            p.delta[(long)bh * N + qw0 + 32 * qb + n] = -(drel + ctr[qb]);
+            p.ntau[(long)bh * N + qw0 + 32 * qb + n] = -thr[qb] / p.rho;
+        }
         const float sa = p.inv_sqrt_d * amax, sb = drel * p.inv_sqrt_d * amax;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
@@ -291,13 +295,17 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
 }
 
 // One 64-query tile of the dK/dV walk for a wave's 32 keys, staggered like dq_tile_staggered:
-// stage 1 = (Q tile . K_owned^T, dO tile . V_owned^T), score math P = u y, dS = u (dP - delta) with
-// the tile's thresholds and deltas read from LDS four rows at a time, stage 2 = (dV^T += dO^T P,
-// dK^T += Q^T dS).
+// stage 1 = (Q tile . K_owned^T, dO tile . V_owned^T), score math, stage 2 = (dV^T += dO^T P,
+// dK^T += Q^T dS).  The thresholds and deltas of the tile's 64 query rows vary along the
+// accumulator registers, so they cost no arithmetic at all: the accumulators of the two stage-1
+// products start from -tau / rho and -delta (read from LDS, four rows per 16-byte read) instead of
+// zero.  With the owned keys scaled by kappa the first product is then y / rho, y = (alpha-1) s -
+// tau, and the second dP - delta; P = y^r and dS = y^(r-1) (dP - delta) come out in units of
+// rho^r and rho^(r-1), which the kernel's epilogue multiplies back in.
 template <class E, class E2, int D, int AM>
-EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float* tau_s, const float* del_s,
+EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float* ntau_s, const float* ndel_s,
                                 const Owned<E, D, 1>& kf, const Owned<E, D, 1>& vf, f32x16 (&XV)[D / 32][1],
-                                f32x16 (&XK)[D / 32][1], float c, float r, int h, const Frag1<E, D>& f1,
+                                f32x16 (&XK)[D / 32][1], float r, int h, const Frag1<E, D>& f1,
                                 const Frag2<E2, D>& f2) {
     constexpr int NS = D / 16, ND = D / 32;
     constexpr int N1 = 2 * NS, N2 = 4 * ND, PF = 4, EPM = 8 / NS;
@@ -308,24 +316,25 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
     uint32_t pp[2][8], sp[2][8];          // P and dS as fp16 pairs: the stage-2 B operands
     frag aq[N1], ag[N1];
     frag2 tg[N2], tq[N2];
-    f32x4 tau4[2], del4[2];               // thresholds / deltas of two groups of four registers (rows)
-    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-    // group G = 4 kb + e / 4 holds registers 4 (e / 4) .. + 3 of half kb: four consecutive tile rows
-    auto read_vec = [&](int G) {
-        const int row = trow(G >> 2, 4 * (G & 3), h);
-        tau4[G & 1] = *(const f32x4*)(tau_s + row);
-        del4[G & 1] = *(const f32x4*)(del_s + row);
+    // registers 4 g .. 4 g + 3 of half kb are four consecutive tile rows
+    auto bias = [&](const float* vec, int kb) {
+        f32x16 b;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 t = *(const f32x4*)(vec + trow(kb, 4 * g, h));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) b[4 * g + e] = t[e];
+        }
+        return b;
     };
     auto score_math = [&](int kb, int e) {
-        const int G = 4 * kb + (e >> 2);
-        if ((e & 3) == 0 && G < 7) read_vec(G + 1);       // one group ahead
-        const float yp = fmaxf(fmaf(c, S[kb][e], -tau4[G & 1][e & 3]), 0.f);
+        const float yp = fmaxf(S[kb][e], 0.f);
         float u;
         if constexpr (AM == ALPHA_15) u = yp;
         else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
         S[kb][e] = u * yp;
-        P[kb][e] = u * (P[kb][e] - del4[G & 1][e & 3]);
+        P[kb][e] = u * P[kb][e];
         if (e & 1) {
             pp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
             sp[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
@@ -338,21 +347,22 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
 
 #pragma unroll
     for (int i = 0; i < PF; ++i) { aq[i] = f1(qbuf, i / NS, i % NS); ag[i] = f1(gbuf, i / NS, i % NS); }
+    S[0] = bias(ntau_s, 0); P[0] = bias(ndel_s, 0);
     sched_fence();
 #pragma unroll
     for (int i = 0; i < N1; ++i) {
         const int kb = i / NS, s = i % NS;
         if (i + PF < N1) { aq[i + PF] = f1(qbuf, (i + PF) / NS, (i + PF) % NS); ag[i + PF] = f1(gbuf, (i + PF) / NS, (i + PF) % NS); }
         else read2(i + PF - N1);
-        if (i == NS - 1) read_vec(0);
-        S[kb] = E::mma(aq[i], kf.f[0][s], s == 0 ? zero : S[kb]);
+        if (i == NS - 2) { S[1] = bias(ntau_s, 1); P[1] = bias(ndel_s, 1); }
+        S[kb] = E::mma(aq[i], kf.f[0][s], S[kb]);
         sched_fence();
         if (kb == 1) {
 #pragma unroll
             for (int k = 0; k < EPM; ++k) score_math(0, 2 * EPM * s + k);
         }
         sched_fence();
-        P[kb] = E::mma(ag[i], vf.f[0][s], s == 0 ? zero : P[kb]);
+        P[kb] = E::mma(ag[i], vf.f[0][s], P[kb]);
         sched_fence();
         if (kb == 1) {
 #pragma unroll
@@ -459,6 +469,11 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 
     Owned<E, D, QB> kf, vf;
     load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, active ? kw0 : 0, lane);
+    // keys scaled by kappa, a power of two: exact, and the scores come out as kappa <q, k>
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int s = 0; s < D / E::KSTEP; ++s) kf.f[qb][s] = kf.f[qb][s] * (elem)p.kappa;
     load_owned<E, D, QB>(vf, (const elem*)p.V + hoff, active ? kw0 : 0, lane);
 
     f32x16 XV[D / 32][QB], XK[D / 32][QB];
@@ -476,8 +491,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         const long i = __builtin_amdgcn_readfirstlane(tl[it] & 0xffff);
         issue_rows<E, D, NW>(b, Qh, i * 64, wave, lane);
         issue_rows<E, D, NW>(b + SM::RBYTES, Gh, i * 64, wave, lane);
-        // the tile's 64 thresholds (wave 0) and 64 deltas (wave 1), one float per lane
-        if (wave == 0) load4_to_lds(uniform_address(p.tau + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF));
+        // the tile's 64 values of -tau / rho (wave 0) and of -delta (wave 1), one float per lane
+        if (wave == 0) load4_to_lds(uniform_address(p.ntau + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF));
         if (wave == 1) load4_to_lds(uniform_address(p.delta + ((long)bh * N + i * 64)), 4u * lane, lds_address(b + VEC_OFF + 4 * TILE));
     };
     // any tile, statements left to the compiler's order
@@ -506,12 +521,13 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
                     const float tq = tq4[e], dq = dq4[e];
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) {
-                        const float yp = fmaxf(fmaf(c, S[kb][qb][v], -tq), 0.f);
+                        // (same units as the staggered body: y / rho, rho^r, rho^(r-1))
+                        const float yp = fmaxf(S[kb][qb][v] + tq, 0.f);
                         float u;
                         if constexpr (AM == ALPHA_15) u = yp;
                         else u = (yp > 0.f) ? pow_r1<AM>(yp, r) : 0.f;
                         S[kb][qb][v] = u * yp;
-                        dP[kb][qb][v] = u * (dP[kb][qb][v] - dq);
+                        dP[kb][qb][v] = u * (dP[kb][qb][v] + dq);
                     }
                 }
             }
@@ -531,7 +547,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
                 if (!((tl[it] >> (16 + mycol)) & 1)) return;
                 ++ntile_done;
                 const float* tau_s = (const float*)(qbuf + VEC_OFF);
-                dkdv_tile_staggered<E, E2, D, AM>(qbuf, qbuf + SM::RBYTES, tau_s, tau_s + TILE, kf, vf, XV, XK, c, r, h, frag1, frag2);
+                dkdv_tile_staggered<E, E2, D, AM>(qbuf, qbuf + SM::RBYTES, tau_s, tau_s + TILE, kf, vf, XV, XK, r, h, frag1, frag2);
             });
     } else {
         stream_tiles<NBUF>(ntl, set0, NBUF == 2 ? set1 : set0, issue_qg, tile_plain_order);
@@ -541,8 +557,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) { settle_acc(XV[db][qb]); settle_acc(XK[db][qb]); }
     if (active) {
-        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax, lane);
-        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax, lane);
+        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * p.rho_p, lane);
+        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * p.rho_u, lane);
     }
     {
         const int slot[1] = {4};

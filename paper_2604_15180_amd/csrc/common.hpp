@@ -15,6 +15,7 @@ struct Params {
     const void* V2;       // forward: V in the stage-2 element type (fp16 copy for bf16 inputs)
     float* O;             // forward: output; backward: the forward's output (nullable)
     float* tau; float* delta;
+    float* ntau;          // backward scratch [BH][N]: -tau / rho, the bias the dK/dV kernel starts its scores from
     float* dQ; float* dK; float* dV;
     int32_t* mask;        // exported / final mask   [BH][T][W]
     int32_t* wmask;       // working mask (superset) [BH][T][W]
@@ -30,6 +31,9 @@ struct Params {
     int BH, N, T, W;
     int causal;
     float c;              // (alpha-1)/sqrt(d): x = c * <q,k>
+    // c = kappa * rho with kappa a power of two and 1 <= rho < 2 (dK/dV kernel: keys scaled by kappa,
+    // which is exact, scores kept in units of rho); rho_p = rho^r, rho_u = rho^(r-1)
+    float kappa, rho, rho_p, rho_u;
     float r;              // 1/(alpha-1)
     float alpha;
     float inv_sqrt_d;
