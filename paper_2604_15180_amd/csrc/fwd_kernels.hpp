@@ -403,6 +403,26 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     }
 }
 
+// A cheap lower bound of the histogram's root for general alpha, used while the sweep is under way:
+// the largest bin edge e_j with f_h(e_j) >= 0 (f_h falls with tau, so tau_h >= e_j), found by
+// bisection over j.  At a bin edge f_h needs no power function: f_h(e_j) = sum_{k>j} H_k pw[k-j] - 1
+// with the table pw[m] = (m h)^r.  Returns -h when even the window's bottom edge is too high.
+template <int SLOTS, int BITS>
+EA_DEV float histogram_edge_bound(const uint32_t* H, int rot, int shift, float h, const float* pw) {
+    auto count = [&](int k) {
+        const uint32_t w = H[(rot + k) & (SLOTS - 1)] >> shift;
+        return (float)(BITS == 32 ? w : (w & ((1u << (BITS & 31)) - 1u)));
+    };
+    int lo = -1, hi = SLOTS - 1;          // f_h(e_hi) = -1 < 0: no bin lies above the top one
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        float f = -1.f;
+        for (int k = mid + 1; k < SLOTS; ++k) f = fmaf(count(k), pw[k - mid], f);
+        if (f >= 0.f) lo = mid; else hi = mid;
+    }
+    return (float)lo * h;
+}
+
 // ---- threshold kernel with candidate lists -----------------------------------------------------
 // Phases 1-3 of Alg. 1 from ONE dense sweep.  By Eq. 5, tau* >= max - 1 (in units of (alpha-1) s),
 // and both the maximum and tau* over a prefix of the keys are at most their values over all keys,
@@ -431,6 +451,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     constexpr int GROW = 24;              // list growth (entries per lane) between two histogram solves
     __shared__ __align__(1024) char kring[NBUF * KT::BYTES];
     __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
+    __shared__ float pw[AM == ALPHA_GEN ? SLOTS : 1];             // (m h)^r, general alpha only
     // used only once the sweep is over: they live in the key-tile ring
     static_assert(MR * MAX_W * 4 + MR * 4 + 64 <= NBUF * KT::BYTES, "post-sweep arrays must fit in the ring");
     uint32_t* const wm = (uint32_t*)kring;
@@ -455,6 +476,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
     for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
+    if constexpr (AM == ALPHA_GEN) {
+        if (tid < SLOTS) pw[tid] = tid == 0 ? 0.f : pow_r<AM>((float)tid * (1.f / NB), p.r);
+    }
 
     // this lane's lists (per-lane 64-bit addresses: a scalar base would have to be fetched from
     // spilled scalar registers at every append)
@@ -474,7 +498,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     // Root of the row's histogram (Eq. 9) as it stands: lane (n, h) solves row block qb = h of row n
     // (with one row per lane, both lanes solve the same), then the two lanes of a row swap.  Returns
     // per row block tau_0 = max(tau_h, max - 1) less the fp32 slack, and the bracket's upper end.
-    auto histogram_bound = [&](float (&lo)[QB], float (&up)[QB]) {
+    // (coarse: while the sweep runs only a lower bound is wanted; for general alpha, whose exact
+    // solve costs hundreds of power functions, the best bin edge then stands in for the root)
+    auto histogram_bound = [&](float (&lo)[QB], float (&up)[QB], bool coarse) {
         lds_settle();
         const int sq = (QB == 2) ? h : 0;
         int top = a_top[0];
@@ -482,8 +508,11 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
         if constexpr (QB == 2) { if (h) { top = a_top[1]; mx = run[1]; } }
         const int a_lo = top == INT_MIN ? 0 : top - (SLOTS - 1);
         const float origin = (float)a_lo * hb;                        // left edge of the window
-        const float tau_h = solve_histogram<AM, SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1),
-                                                                  SM::CBITS * sq & 31, hb, r) + origin;
+        float tau_h;
+        if (AM == ALPHA_GEN && coarse)
+            tau_h = histogram_edge_bound<SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1), SM::CBITS * sq & 31, hb, pw) + origin;
+        else
+            tau_h = solve_histogram<AM, SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1), SM::CBITS * sq & 31, hb, r) + origin;
         const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
         const float my_lo = fmaxf(tau_h - slack, fmaf(c, mx, -1.f)), my_up = tau_h + hb + slack;
         const float o_lo = xhalf_other(my_lo, h), o_up = xhalf_other(my_up, h);
@@ -592,7 +621,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
             if (__any(grown)) {
                 // a better lower bound from the histogram so far
                 float lo[QB], up[QB];
-                histogram_bound(lo, up);
+                histogram_bound(lo, up, true);
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb) {
                     const float braw = lo[qb] * inv_c;
@@ -612,7 +641,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     int any_over = 0;
     if (active) {
         float thr[QB], blo[QB], bhi[QB];
-        histogram_bound(thr, bhi);
+        histogram_bound(thr, bhi, false);
         int iters[QB], done[QB], mycnt[QB];
         float f1_last[QB];
         int nmax = 0;
