@@ -156,6 +156,20 @@ def test_flat_attention_overflows_candidate_lists(ea, dtype, N):
     print("  flat", info, ginfo, "mean iters", iters.float().mean().item(), flush=True)
 
 
+def test_mfma_probe_runs(ea):
+    # measurement aid: every lane sums its accumulators into `sink`; with operands of +-1 the sums
+    # are integers, and the argument checks of the binding hold
+    data = torch.ones(8192, dtype=torch.float16, device="cuda")
+    sink = torch.full((256 * 4,), float("nan"), device="cuda")
+    flops = ea.entmax_attn_mfma_probe(data, sink, 4, 3)
+    torch.cuda.synchronize()
+    assert flops == 4 * 4 * 3 * 32 * 32768.0
+    # each accumulator entry: 3 rounds x 8 MFMAs x 16 products of 1 x 1; 64 entries per lane
+    assert torch.all(sink == 3 * 8 * 16 * 64).item()
+    with pytest.raises(ValueError):
+        ea.entmax_attn_mfma_probe(data[:100], sink, 4, 3)
+
+
 def test_c2_shape_two_heads(ea):
     # configs[1]: alpha=1.5 bf16 B=4 H=16 N=4096 d=64 causal sigma=1.5, on 2 of its 64 heads
     run_case(ea, 1, 2, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
