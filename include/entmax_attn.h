@@ -117,6 +117,25 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
                     int B, int H, int N, int d, ea_dtype dtype, float alpha, int causal,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * The same two operations with one alpha per head (Sec. 3.2 gives the solver for every alpha in
+ * (1, 2]; heads of one layer may use different values).  `alpha_per_head` is a HOST pointer to H
+ * floats, each in (1, 2]; it is read before the call returns.  Head h of every batch entry uses
+ * alpha_per_head[h].  When the values differ, all heads run the general-alpha code (power functions
+ * through exp2/log2) and a table of per-head constants is written into the workspace first; when
+ * they are all equal the call is the single-alpha one.  Everything else as in entmax_attn_fwd /
+ * entmax_attn_bwd; EA_ERR_ALPHA if any value is outside (1, 2].
+ */
+int entmax_attn_fwd_alpha_per_head(const void* Q, const void* K, const void* V,
+                                   float* O, float* tau, int32_t* block_mask, int32_t* iters,
+                                   int B, int H, int N, int d, ea_dtype dtype, const float* alpha_per_head, int causal,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                   const float* tau, const int32_t* block_mask,
+                                   float* dQ, float* dK, float* dV,
+                                   int B, int H, int N, int d, ea_dtype dtype, const float* alpha_per_head, int causal,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char* entmax_attn_strerror(int code);
 

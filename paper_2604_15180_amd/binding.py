@@ -54,6 +54,10 @@ def lib():
         L.entmax_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
         L.entmax_attn_bwd.restype = ci
         L.entmax_attn_bwd.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+        L.entmax_attn_fwd_alpha_per_head.restype = ci
+        L.entmax_attn_fwd_alpha_per_head.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, ctypes.POINTER(cf), ci, vp, sz, vp]
+        L.entmax_attn_bwd_alpha_per_head.restype = ci
+        L.entmax_attn_bwd_alpha_per_head.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, ctypes.POINTER(cf), ci, vp, sz, vp]
         L.entmax_attn_timer_enable.restype = ci
         L.entmax_attn_timer_enable.argtypes = [ci]
         L.entmax_attn_timer_read.restype = ci
@@ -117,9 +121,20 @@ def _prep(*tensors):
     return first.shape
 
 
+def _alpha_array(alpha, H):
+    """None for a single alpha; else a ctypes array of H floats (one alpha per head)."""
+    if isinstance(alpha, (int, float)):
+        return None
+    vals = [float(a) for a in (alpha.tolist() if hasattr(alpha, "tolist") else alpha)]
+    if len(vals) != H:
+        raise ValueError(f"entmax_attn: {len(vals)} alphas for {H} heads")
+    return (ctypes.c_float * H)(*vals)
+
+
 def entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=False, workspace=None):
-    """-> (O, tau, block_mask) or (O, tau, block_mask, iters).  The workspace used is kept in
-    `entmax_attn_fwd.last_workspace` so that read_stats() can fetch the tile counters."""
+    """-> (O, tau, block_mask) or (O, tau, block_mask, iters).  `alpha`: one float, or a sequence of
+    H floats (one per head).  The workspace used is kept in `entmax_attn_fwd.last_workspace` so
+    that read_stats() can fetch the tile counters."""
     B, H, N, d = _prep(Q, K, V)
     dev = Q.device
     T = N // 64 if N % 64 == 0 else 0
@@ -130,9 +145,15 @@ def entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=False, workspace=None):
     nbytes = entmax_attn_workspace_bytes(B, H, N, d, Q.dtype, causal, False)
     ws = workspace if workspace is not None else _workspace(nbytes, dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
-    rc = lib().entmax_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(mask), _ptr(iters),
-                               B, H, N, d, _dtype_code(Q.dtype), float(alpha), int(bool(causal)),
-                               _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    per_head = _alpha_array(alpha, H)
+    if per_head is None:
+        rc = lib().entmax_attn_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(mask), _ptr(iters),
+                                   B, H, N, d, _dtype_code(Q.dtype), float(alpha), int(bool(causal)),
+                                   _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    else:
+        rc = lib().entmax_attn_fwd_alpha_per_head(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(mask), _ptr(iters),
+                                                  B, H, N, d, _dtype_code(Q.dtype), per_head, int(bool(causal)),
+                                                  _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
     _check(rc)
     entmax_attn_fwd.last_workspace = ws
     return (O, tau, mask, iters) if want_iters else (O, tau, mask)
@@ -148,9 +169,15 @@ def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspa
     nbytes = entmax_attn_workspace_bytes(B, H, N, d, Q.dtype, causal, True)
     ws = workspace if workspace is not None else _workspace(nbytes, dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
-    rc = lib().entmax_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
-                               _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, d, _dtype_code(Q.dtype), float(alpha),
-                               int(bool(causal)), _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    per_head = _alpha_array(alpha, H)
+    if per_head is None:
+        rc = lib().entmax_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
+                                   _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, d, _dtype_code(Q.dtype), float(alpha),
+                                   int(bool(causal)), _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    else:
+        rc = lib().entmax_attn_bwd_alpha_per_head(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
+                                                  _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, d, _dtype_code(Q.dtype), per_head,
+                                                  int(bool(causal)), _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
     _check(rc)
     entmax_attn_bwd.last_workspace = ws
     return dQ, dK, dV

@@ -39,7 +39,7 @@ constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
 };
 
 // element size of the stage-2 copies
@@ -50,6 +50,7 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
     L.stats = off; off += align256(STATS_BYTES + 256);   // counters, then the scale words
+    L.hc = off; off += align256((size_t)H * sizeof(HeadConsts)); // per-head constants (alpha per head)
     L.a = off; off += align256(BH * N * d * t_elem(t));          // V in the stage-2 type
     L.wmask = off; off += align256(BH * T * W * 4);
     L.tmax = off; off += align256(BH * T * (size_t)N * 2);       // per-row key-tile maxima, fp16
@@ -67,6 +68,7 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
     L.stats = off; off += align256(STATS_BYTES + 256);   // counters, then the scale words
+    L.hc = off; off += align256((size_t)H * sizeof(HeadConsts)); // per-head constants (alpha per head)
     L.a = off; off += align256(BH * N * d * t_elem(t));          // K, Q, V, dO in the stage-2 type
     L.b = off; off += align256(BH * N * d * t_elem(t));
     L.c = off; off += align256(BH * N * d * t_elem(t));
@@ -79,11 +81,13 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     return L;
 }
 
+bool alpha_ok(float alpha) { return isfinite(alpha) && alpha > 1.f && alpha <= 2.f; }
+
 int check_common(int B, int H, int N, int d, ea_dtype t, float alpha) {
     if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
     if (B <= 0 || H <= 0 || N <= 0 || N % 64 != 0 || N > 131072 || (d != 64 && d != 128)) return EA_ERR_SHAPE;
     if ((long)B * H > 65535) return EA_ERR_SHAPE;
-    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > 2.f) return EA_ERR_ALPHA;
+    if (!alpha_ok(alpha)) return EA_ERR_ALPHA;
     return EA_OK;
 }
 
@@ -98,20 +102,38 @@ int dispatch(bool is_bwd, ea_dtype t, int d, const Params& p, bool rebuild, void
     return d == 64 ? run_f32_d64(is_bwd, p, rebuild, copies, s) : run_f32_d128(is_bwd, p, rebuild, copies, s);
 }
 
+// The alpha-dependent constants (host and device: the per-head table is filled by a kernel).
+__host__ __device__ inline HeadConsts head_consts_of(float alpha, float inv_sqrt_d) {
+    HeadConsts k;
+    k.alpha = alpha;
+    k.c = (alpha - 1.f) * inv_sqrt_d;
+    k.r = 1.f / (alpha - 1.f);
+    int ex = 0;
+    const float mant = frexpf(k.c, &ex);          // c = mant * 2^ex, 0.5 <= mant < 1
+    k.kappa = ldexpf(1.f, ex - 1);
+    k.rho = 2.f * mant;
+    k.rho_p = powf(k.rho, k.r);
+    k.rho_u = powf(k.rho, k.r - 1.f);
+    k.pad = 0.f;
+    return k;
+}
+
+// Up to 32 alphas travel as kernel arguments (the caller's array is host memory and need not
+// outlive the call); thread i writes the constants of head first + i.
+struct AlphaChunk { float a[32]; };
+__global__ void head_consts_kernel(AlphaChunk chunk, int first, int count, float inv_sqrt_d, HeadConsts* table) {
+    const int i = threadIdx.x;
+    if (i < count) table[first + i] = head_consts_of(chunk.a[i], inv_sqrt_d);
+}
+
 Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int causal) {
     Params p{};
     p.BH = B * H; p.N = N; p.T = N / 64; p.W = (p.T + 31) / 32;
     p.causal = causal ? 1 : 0;
-    p.alpha = alpha;
     p.inv_sqrt_d = 1.f / sqrtf((float)d);
-    p.c = (alpha - 1.f) * p.inv_sqrt_d;
-    p.r = 1.f / (alpha - 1.f);
-    int ex = 0;
-    const float mant = frexpf(p.c, &ex);          // c = mant * 2^ex, 0.5 <= mant < 1
-    p.kappa = ldexpf(1.f, ex - 1);
-    p.rho = 2.f * mant;
-    p.rho_p = powf(p.rho, p.r);
-    p.rho_u = powf(p.rho, p.r - 1.f);
+    p.hc = head_consts_of(alpha, p.inv_sqrt_d);
+    p.hc_table = nullptr;
+    p.H = H;
     p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
     p.max_sweeps = MAX_SWEEPS;
     return p;
@@ -163,12 +185,39 @@ size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype t, int c
     return is_bwd ? bwd_layout(B, H, N, d, t).total : fwd_layout(B, H, N, d, t).total;
 }
 
-int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
-                    int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, int causal,
-                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+// alpha_h: null (one alpha for all heads) or H alphas in host memory
+int check_alphas(int H, const float* alpha_h, float& alpha) {
+    if (!alpha_h) return EA_OK;
+    bool same = true;
+    for (int i = 0; i < H; ++i) {
+        if (!alpha_ok(alpha_h[i])) return EA_ERR_ALPHA;
+        same = same && alpha_h[i] == alpha_h[0];
+    }
+    alpha = alpha_h[0];
+    return same ? 1 : 2;      // 1: all heads alike (the single-alpha path serves), 2: a table is needed
+}
+int fill_head_table(const float* alpha_h, int H, float inv_sqrt_d, HeadConsts* table, hipStream_t s) {
+    for (int first = 0; first < H; first += 32) {
+        AlphaChunk chunk{};
+        const int count = H - first < 32 ? H - first : 32;
+        for (int i = 0; i < count; ++i) chunk.a[i] = alpha_h[first + i];
+        hipLaunchKernelGGL(head_consts_kernel, dim3(1), dim3(32), 0, s, chunk, first, count, inv_sqrt_d, table);
+        EA_HIP(hipGetLastError());
+    }
+    return EA_OK;
+}
+
+int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
+             int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, const float* alpha_h, int causal,
+             void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!Q || !K || !V || !O || !tau || !block_mask) return EA_ERR_NULL;
-    int rc = check_common(B, H, N, d, t, alpha);
+    int rc = check_common(B, H, N, d, t, alpha_h ? 1.5f : alpha);
     if (rc) return rc;
+    const int per_head = check_alphas(H, alpha_h, alpha);
+    if (per_head < 0) return per_head;
     const Layout L = fwd_layout(B, H, N, d, t);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return EA_ERR_WORKSPACE;
     char* ws = (char*)workspace;
@@ -185,16 +234,23 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
+    if (per_head == 2) {
+        p.hc_table = (const HeadConsts*)(ws + L.hc);
+        if ((rc = fill_head_table(alpha_h, H, p.inv_sqrt_d, (HeadConsts*)(ws + L.hc), s))) return rc;
+    }
     timer_begin_call();
     return dispatch(false, t, d, p, false, nullptr, s);
 }
 
-int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
-                    const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
-                    ea_dtype t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
+             const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
+             ea_dtype t, float alpha, const float* alpha_h, int causal, void* workspace, size_t workspace_bytes,
+             void* hip_stream) {
     if (!Q || !K || !V || !dO || !tau || !dQ || !dK || !dV) return EA_ERR_NULL;
-    int rc = check_common(B, H, N, d, t, alpha);
+    int rc = check_common(B, H, N, d, t, alpha_h ? 1.5f : alpha);
     if (rc) return rc;
+    const int per_head = check_alphas(H, alpha_h, alpha);
+    if (per_head < 0) return per_head;
     const Layout L = bwd_layout(B, H, N, d, t);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < L.total) return EA_ERR_WORKSPACE;
     char* ws = (char*)workspace;
@@ -214,8 +270,39 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
     p.scal = (unsigned int*)(ws + L.stats + STATS_BYTES);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
+    if (per_head == 2) {
+        p.hc_table = (const HeadConsts*)(ws + L.hc);
+        if ((rc = fill_head_table(alpha_h, H, p.inv_sqrt_d, (HeadConsts*)(ws + L.hc), s))) return rc;
+    }
     timer_begin_call();
     return dispatch(true, t, d, p, rebuild, copies, s);
+}
+}  // namespace
+
+extern "C" {
+
+int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
+                    int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, int causal,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return fwd_impl(Q, K, V, O, tau, block_mask, iters, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes, hip_stream);
+}
+int entmax_attn_fwd_alpha_per_head(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
+                                   int32_t* iters, int B, int H, int N, int d, ea_dtype t, const float* alpha_per_head,
+                                   int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!alpha_per_head) return EA_ERR_NULL;
+    return fwd_impl(Q, K, V, O, tau, block_mask, iters, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
+}
+int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
+                    const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
+                    ea_dtype t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes, hip_stream);
+}
+int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                                   const float* tau, const int32_t* block_mask, float* dQ, float* dK, float* dV, int B,
+                                   int H, int N, int d, ea_dtype t, const float* alpha_per_head, int causal,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!alpha_per_head) return EA_ERR_NULL;
+    return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
 }
 
 int entmax_attn_timer_enable(int on) {

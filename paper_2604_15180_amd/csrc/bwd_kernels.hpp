@@ -145,7 +145,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     const elem* Kh = (const elem*)p.K + hoff;
     const elem* Vh = (const elem*)p.V + hoff;
     const int myrow = (wave * 32 * QB) / 64;
-    const float c = p.c, r = p.r;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
 
     for (int i = tid; i < MR * W; i += THREADS)
         fm[i] = (I * MR + i / W < T) ? (uint32_t)p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
@@ -278,7 +279,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
         if (h == 0 && active) {
             // for the dK/dV kernel, as the biases its two stage-1 products start from
             p.delta[(long)bh * N + qw0 + 32 * qb + n] = -(drel + ctr[qb]);
-            p.ntau[(long)bh * N + qw0 + 32 * qb + n] = -thr[qb] / p.rho;
+            p.ntau[(long)bh * N + qw0 + 32 * qb + n] = -thr[qb] / hc.rho;
         }
         const float sa = p.inv_sqrt_d * amax, sb = drel * p.inv_sqrt_d * amax;
 #pragma unroll
@@ -432,7 +433,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     }
     const int mycol = (wave * 32 * QB) / 64;  // my mask column within the group
     const int jc0 = J * MC;                   // first mask column of the group
-    const float c = p.c, r = p.r;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
 
     // ---- column walk of the row-packed mask: list of query tiles with a set bit -------------
     const int i_min = p.causal ? jc0 : 0;
@@ -473,7 +475,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int s = 0; s < D / E::KSTEP; ++s) kf.f[qb][s] = kf.f[qb][s] * (elem)p.kappa;
+        for (int s = 0; s < D / E::KSTEP; ++s) kf.f[qb][s] = kf.f[qb][s] * (elem)hc.kappa;
     load_owned<E, D, QB>(vf, (const elem*)p.V + hoff, active ? kw0 : 0, lane);
 
     f32x16 XV[D / 32][QB], XK[D / 32][QB];
@@ -557,8 +559,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) { settle_acc(XV[db][qb]); settle_acc(XK[db][qb]); }
     if (active) {
-        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * p.rho_p, lane);
-        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * p.rho_u, lane);
+        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * hc.rho_p, lane);
+        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * hc.rho_u, lane);
     }
     {
         const int slot[1] = {4};

@@ -10,6 +10,18 @@ constexpr int MAX_W = 64;       // mask words per row
 constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 constexpr int LIST_CAP = 256;   // candidate entries per (row, lane half)
 
+// What depends on alpha, per head when alpha differs between heads (then a table of these, one per
+// head, sits in the workspace; otherwise the copy inside Params is used).
+struct HeadConsts {
+    float alpha;
+    float c;              // (alpha-1)/sqrt(d): x = c * <q,k>
+    float r;              // 1/(alpha-1)
+    // c = kappa * rho with kappa a power of two and 1 <= rho < 2 (dK/dV kernel: keys scaled by kappa,
+    // which is exact, scores kept in units of rho); rho_p = rho^r, rho_u = rho^(r-1)
+    float kappa, rho, rho_p, rho_u;
+    float pad;
+};
+
 struct Params {
     const void* Q; const void* K; const void* V; const void* dO;
     const void* V2;       // forward: V in the stage-2 element type (fp16 copy for bf16 inputs)
@@ -30,16 +42,15 @@ struct Params {
     unsigned int* scal;
     int BH, N, T, W;
     int causal;
-    float c;              // (alpha-1)/sqrt(d): x = c * <q,k>
-    // c = kappa * rho with kappa a power of two and 1 <= rho < 2 (dK/dV kernel: keys scaled by kappa,
-    // which is exact, scores kept in units of rho); rho_p = rho^r, rho_u = rho^(r-1)
-    float kappa, rho, rho_p, rho_u;
-    float r;              // 1/(alpha-1)
-    float alpha;
+    HeadConsts hc;        // the constants of the call's single alpha
+    const HeadConsts* hc_table;   // [H] per-head constants, or null
+    int H;
     float inv_sqrt_d;
     float tol;
     int max_sweeps;
 };
+
+EA_DEV HeadConsts head_consts(const Params& p, int bh) { return p.hc_table ? p.hc_table[bh % p.H] : p.hc; }
 
 // Consecutive block ids are dealt round-robin to the 8 XCDs (each with its own L2).  When the
 // number of heads divides by 8 every XCD gets whole heads, so the work-groups that run together

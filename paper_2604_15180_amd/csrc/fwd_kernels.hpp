@@ -192,7 +192,8 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
     const int njt = p.causal ? min((int)((q0 + BR) / 64), T) : T;          // tiles the group streams
     const int wjt = !active ? 0 : p.causal ? (int)((qw0 + 32 * QB - 1) / 64) + 1 : T;   // tiles this wave needs
     const int myrow = (wave * 32 * QB) / 64;                               // my mask row in the group
-    const float c = p.c, r = p.r;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
@@ -379,7 +380,7 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             bool done = fabsf(f) <= p.tol;
             float tau = thr[qb];
             if (!done) {
-                const float cand_tau = hybrid_step(tau, f, g, hs, r, p.alpha, blo[qb], bhi[qb]);
+                const float cand_tau = hybrid_step(tau, f, g, hs, r, hc.alpha, blo[qb], bhi[qb]);
                 done = fabsf(cand_tau - tau) < p.tol;
                 tau = cand_tau;
             }
@@ -470,14 +471,15 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     const int njt = p.causal ? min((int)((q0 + BR) / 64), T) : T;
     const int wjt = !active ? 0 : p.causal ? (int)((qw0 + 32 * QB - 1) / 64) + 1 : T;
     const int myrow = (wave * 32 * QB) / 64;
-    const float c = p.c, r = p.r;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
     constexpr float hb = 1.f / NB;
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
     for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
     if constexpr (AM == ALPHA_GEN) {
-        if (tid < SLOTS) pw[tid] = tid == 0 ? 0.f : pow_r<AM>((float)tid * (1.f / NB), p.r);
+        if (tid < SLOTS) pw[tid] = tid == 0 ? 0.f : pow_r<AM>((float)tid * (1.f / NB), r);
     }
 
     // this lane's lists (per-lane 64-bit addresses: a scalar base would have to be fetched from
@@ -698,7 +700,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                     f1_last[qb] = -r * g;
                     if (fabsf(f) <= p.tol) done[qb] = 1;
                     else {
-                        const float cand_tau = hybrid_step(thr[qb], f, g, hs, r, p.alpha, blo[qb], bhi[qb]);
+                        const float cand_tau = hybrid_step(thr[qb], f, g, hs, r, hc.alpha, blo[qb], bhi[qb]);
                         if (fabsf(cand_tau - thr[qb]) < p.tol) done[qb] = 1;
                         thr[qb] = cand_tau;
                     }
@@ -772,7 +774,8 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     // V in the stage-2 element type (for bf16 inputs: the fp16 copy made by convert_kernel)
     const typename E2::elem* Vh = MASK_ONLY ? nullptr : (const typename E2::elem*)p.V2 + (long)bh * N * D;
     const int myrow = (wave * 32 * QB) / 64;
-    const float c = p.c, r = p.r;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
 
     for (int i = tid; i < MR * W; i += THREADS) {
         wm[i] = (I * MR + i / W < T) ? (uint32_t)p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
@@ -895,7 +898,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                         if (!have_f) iters[qb] += 1;
                         if (!have_f && fabsf(f) <= p.tol) done[qb] = 1;
                         else {
-                            const float cand = hybrid_step(thr[qb], f, g, hs, r, p.alpha, lo[qb], hi[qb]);
+                            const float cand = hybrid_step(thr[qb], f, g, hs, r, hc.alpha, lo[qb], hi[qb]);
                             if (fabsf(cand - thr[qb]) < p.tol) done[qb] = 1;
                             thr[qb] = cand;
                         }

@@ -122,7 +122,8 @@ struct Ops {
 
 template <class E, class E2, int D>
 int dispatch_alpha(bool is_bwd, Params p, bool rebuild, void* const copies[4], hipStream_t s) {
-    switch (alpha_mode(p.alpha)) {
+    // heads with different alphas all take the general-alpha code
+    switch (p.hc_table ? ALPHA_GEN : alpha_mode(p.hc.alpha)) {
         case ALPHA_15: return is_bwd ? Ops<E, E2, D, ALPHA_15>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_15>::fwd(p, s);
         case ALPHA_20: return is_bwd ? Ops<E, E2, D, ALPHA_20>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_20>::fwd(p, s);
         default: return is_bwd ? Ops<E, E2, D, ALPHA_GEN>::bwd(p, rebuild, copies, s) : Ops<E, E2, D, ALPHA_GEN>::fwd(p, s);

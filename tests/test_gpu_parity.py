@@ -156,6 +156,35 @@ def test_flat_attention_overflows_candidate_lists(ea, dtype, N):
     print("  flat", info, ginfo, "mean iters", iters.float().mean().item(), flush=True)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_alpha_per_head(ea, dtype):
+    # one alpha per head (general-alpha code for all heads, constants from the per-head table),
+    # each head against the oracle run with that head's alpha
+    B, H, N, d, causal = 2, 3, 320, 64, True
+    alphas = [1.25, 1.5, 2.0]
+    sigma = 1.0 if dtype == "f32" else 2.0
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, dtype, sigma, seed=71)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alphas, causal, want_iters=True)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alphas, causal, block_mask=mask)
+    torch.cuda.synchronize()
+    for hh, a in enumerate(alphas):
+        sl = slice(hh, hh + 1)
+        ref, info = parity.check_forward(q[:, sl], k[:, sl], v[:, sl], a, causal, O[:, sl], tau[:, sl], mask[:, sl],
+                                         label=f"head {hh} alpha {a}")
+        excl = parity.near_threshold_rows(q[:, sl], k[:, sl], a, causal, ref["tau"]) if a == 2.0 else None
+        _, ginfo = parity.check_backward(q[:, sl], k[:, sl], v[:, sl], do[:, sl], a, causal, dQ[:, sl], dK[:, sl],
+                                         dV[:, sl], label=f"head {hh} alpha {a}", exclude_rows=excl)
+        print(f"  head {hh} alpha {a}:", info, ginfo, flush=True)
+    # equal values take the single-alpha path and must give its result bit for bit
+    O1, tau1, mask1 = ea.entmax_attn_fwd(Q, K, V, [1.5] * H, causal)
+    O2, tau2, mask2 = ea.entmax_attn_fwd(Q, K, V, 1.5, causal)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2) and torch.equal(tau1, tau2) and torch.equal(mask1, mask2)
+    with pytest.raises(ea.EntmaxAttnError):
+        ea.entmax_attn_fwd(Q, K, V, [1.5, 2.5, 1.5], causal)
+
+
 def test_mfma_probe_runs(ea):
     # measurement aid: every lane sums its accumulators into `sink`; with operands of +-1 the sums
     # are integers, and the argument checks of the binding hold
