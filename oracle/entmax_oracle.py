@@ -125,6 +125,25 @@ def attn_bwd(Q, K, V, dO, alpha, causal):
     return {"dQ": dQ, "dK": dK, "dV": dV, "delta": delta}
 
 
+def attn_decode(q, K, V, alpha):
+    """Inference variant on materialised logits (appendix on language modelling: "a simplified
+    variant that operates on fully materialized logits z in R^n"): one query row per head against
+    all N cached keys.  z = K q / sqrt(d), p = alpha-entmax(z) (Eq. 3), o = p V.
+
+    q: [B,H,d], K, V: [B,H,N,d].  Returns dict(O [B,H,d], tau [B,H] (raw convention:
+    p = [(alpha-1) z - tau]_+^(1/(alpha-1))), P [B,H,N], z [B,H,N])."""
+    q, K, V = _c(q), _c(K), _c(V)
+    B, H, N, d = K.shape
+    O = np.empty((B, H, d)); tau = np.empty((B, H)); P = np.empty((B, H, N)); Z = np.empty((B, H, N))
+    for b in range(B):
+        for h in range(H):
+            z = K[b, h] @ q[b, h] / np.sqrt(d)
+            pr, t = entmax(z, alpha)
+            Z[b, h] = z; P[b, h] = pr; tau[b, h] = t
+            O[b, h] = pr @ V[b, h]
+    return {"O": O, "tau": tau, "P": P, "z": Z}
+
+
 def block_mask_words(margin):
     """Pack margin > 0 into int32 words, bit k of word m <-> key tile 32m+k (App. C.4)."""
     bits = (margin > 0)

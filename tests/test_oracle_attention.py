@@ -149,3 +149,36 @@ def test_gradient_invariants(alpha):
     unused = P[0, 0].max(0) == 0
     assert unused.any()
     assert np.all(g["dK"][0, 0, unused] == 0) and np.all(g["dV"][0, 0, unused] == 0)
+
+
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+def test_decode_is_the_last_causal_row(alpha):
+    # the inference variant (one query against all cached keys) must equal what the attention
+    # oracle, a separate C routine, gives for the last row of a causal problem, whose query sees
+    # every key; and its probabilities must solve Eq. 3-4
+    rng = np.random.default_rng(5)
+    B, H, N, d = 1, 2, 96, 16
+    Q, K, V = (1.5 * rng.standard_normal((B, H, N, d)) for _ in range(3))
+    full = eo.attn_fwd(Q, K, V, alpha, True, tile=32, want_margin=False)
+    dec = eo.attn_decode(Q[:, :, -1], K, V, alpha)
+    assert np.abs(dec["O"] - full["O"][:, :, -1]).max() < 1e-12
+    assert np.abs(dec["tau"] - full["tau"][:, :, -1]).max() < 1e-12
+    assert np.abs(dec["P"].sum(-1) - 1).max() < 1e-10 and dec["P"].min() >= 0   # (bisection stops at a 1e-12 bracket in tau)
+    x = (alpha - 1) * dec["z"] - dec["tau"][..., None]
+    assert np.abs(dec["P"] - np.maximum(x, 0) ** (1 / (alpha - 1))).max() < 1e-12
+
+
+def test_decode_one_dominant_key_and_equal_keys():
+    # a key far ahead of the rest: one-hot, o = its value row, tau = (alpha-1) z_max - 1 (lower
+    # end of Eq. 5); all keys equal: uniform, o = mean of V, tau = (alpha-1) z - n^(1-alpha)
+    rng = np.random.default_rng(6)
+    N, d, alpha = 40, 8, 1.5
+    q = np.ones((1, 1, d)); K = np.zeros((1, 1, N, d)); K[0, 0, 7] = 10.0
+    V = rng.standard_normal((1, 1, N, d))
+    dec = eo.attn_decode(q, K, V, alpha)
+    assert np.abs(dec["O"][0, 0] - V[0, 0, 7]).max() < 1e-12
+    assert abs(dec["tau"][0, 0] - ((alpha - 1) * 10.0 * d / np.sqrt(d) - 1)) < 1e-12
+    K[:] = 0.3
+    dec = eo.attn_decode(q, K, V, alpha)
+    assert np.abs(dec["O"][0, 0] - V[0, 0].mean(0)).max() < 1e-12
+    assert abs(dec["tau"][0, 0] - ((alpha - 1) * 0.3 * d / np.sqrt(d) - N ** (1 - alpha))) < 1e-12
