@@ -136,6 +136,28 @@ int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, 
                                    int B, int H, int N, int d, ea_dtype dtype, const float* alpha_per_head, int causal,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Inference variant on materialised logits (the paper's appendix on language modelling; Sec. 5
+ * names an optimised inference kernel as future work): one query row per head against all N
+ * cached keys, no causal mask.
+ *     z = K q / sqrt(d),  p = [(alpha-1) z - tau]_+^{1/(alpha-1)} with sum p = 1,  o = p V
+ *   q           in   [B,H,d] of `dtype`
+ *   K, V        in   [B,H,N,d] of `dtype`; any N in 1 .. 4194304, d 64 or 128
+ *   O           out  [B,H,d] float32
+ *   tau         out  [B,H]   float32, raw convention as in entmax_attn_fwd
+ *   support     out  [B,H]   int32, may be NULL: number of keys with p > 0
+ *   iters       out  [B,H]   int32, may be NULL: evaluations of f the refinement took
+ * The logits are written to the workspace (N floats per head) by a kernel that reads K once; a second
+ * kernel solves tau per head (histogram of the scores within one unit of the maximum, Eq. 5-9, then
+ * the hybrid refinement of Sec. 3.2) and gathers the rows of V in the support.  Conventions, error
+ * codes and workspace rules as above; entmax_attn_decode_workspace_bytes returns 0 for a bad shape.
+ */
+size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype);
+int entmax_attn_decode(const void* q, const void* K, const void* V,
+                       float* O, float* tau, int32_t* support, int32_t* iters,
+                       int B, int H, int N, int d, ea_dtype dtype, float alpha,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable text for a return code. */
 const char* entmax_attn_strerror(int code);
 

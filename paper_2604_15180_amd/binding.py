@@ -62,6 +62,10 @@ def lib():
         L.entmax_attn_timer_enable.argtypes = [ci]
         L.entmax_attn_timer_read.restype = ci
         L.entmax_attn_timer_read.argtypes = [ctypes.POINTER(cf), ctypes.POINTER(ci), ci]
+        L.entmax_attn_decode_workspace_bytes.restype = sz
+        L.entmax_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+        L.entmax_attn_decode.restype = ci
+        L.entmax_attn_decode.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, vp, sz, vp]
         L.entmax_attn_mfma_probe.restype = ci
         L.entmax_attn_mfma_probe.argtypes = [vp, vp, ci, ci, vp]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
@@ -181,6 +185,32 @@ def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspa
     _check(rc)
     entmax_attn_bwd.last_workspace = ws
     return dQ, dK, dV
+
+
+def entmax_attn_decode_workspace_bytes(B, H, N, d, dtype):
+    return int(lib().entmax_attn_decode_workspace_bytes(B, H, N, d, _dtype_code(dtype)))
+
+
+def entmax_attn_decode(q, K, V, alpha, workspace=None):
+    """One query per head against all cached keys: q [B,H,d], K, V [B,H,N,d] -> (O [B,H,d], tau [B,H],
+    support [B,H], iters [B,H])."""
+    for t in (q, K, V):
+        if not t.is_cuda:
+            raise ValueError("entmax_attn_decode: tensors must live on the GPU (there is no CPU path)")
+    if K.dim() != 4 or K.shape != V.shape or q.shape != K.shape[:2] + K.shape[3:] or not (
+            q.is_contiguous() and K.is_contiguous() and V.is_contiguous()) or not (q.dtype == K.dtype == V.dtype):
+        raise ValueError("entmax_attn_decode: q [B,H,d], K, V [B,H,N,d], contiguous, of one dtype")
+    B, H, N, d = K.shape
+    dev = K.device
+    O = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+    tau = torch.empty((B, H), dtype=torch.float32, device=dev)
+    support = torch.empty((B, H), dtype=torch.int32, device=dev)
+    iters = torch.empty((B, H), dtype=torch.int32, device=dev)
+    ws = workspace if workspace is not None else _workspace(entmax_attn_decode_workspace_bytes(B, H, N, d, K.dtype), dev)
+    _check(lib().entmax_attn_decode(_ptr(q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(support), _ptr(iters),
+                                    B, H, N, d, _dtype_code(K.dtype), float(alpha), _ptr(ws), ws.numel(),
+                                    ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)))
+    return O, tau, support, iters
 
 
 def entmax_attn_mfma_probe(data, sink, groups, iters):

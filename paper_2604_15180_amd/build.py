@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libentmax_attn.so")
-UNITS = ["api", "inst_bf16_d64", "inst_bf16_d128", "inst_f32_d64", "inst_f32_d128"]
+UNITS = ["api", "decode", "inst_bf16_d64", "inst_bf16_d128", "inst_f32_d64", "inst_f32_d128"]
 HEADERS = [os.path.join(CSRC, f) for f in
            ("tiles.hpp", "common.hpp", "fwd_kernels.hpp", "bwd_kernels.hpp", "launch.hpp", "ops.hpp")] + [
     os.path.join(os.path.dirname(HERE), "include", "entmax_attn.h")]
