@@ -115,6 +115,63 @@ def context_scaling(ea, workloads, dev, args):
                           lengths=rows)), flush=True)
 
 
+def decode_workload(ea, workloads, dev, args):
+    """Third workload: the inference variant on materialised logits (one query per head against a
+    long key/value cache; the paper's appendix on language modelling).  Bandwidth-bound: the score
+    kernel reads K once.  bf16, d = 128, alpha = 1.5, 32 heads, Q, K ~ N(0, 9): a handful of keys
+    in the support, as in the long-context regime."""
+    from oracle import entmax_oracle as eo
+    B, H, d, alpha, sigma = 4, 8, 128, 1.5, 3.0
+    rows, roofline, cpu_baseline = [], None, None
+    for N in (8192, 32768, 131072):
+        q4, k, v, _ = workloads.gaussian_qkv(B, H, N, d, "bf16", sigma, seed=9000 + N // 8192)
+        q = q4[:, :, -1].contiguous()
+        Q, K, V = q.to(dev), k.to(dev), v.to(dev)
+        ws = torch.empty(ea.entmax_attn_decode_workspace_bytes(B, H, N, d, "bf16"), dtype=torch.uint8, device=dev)
+        for _ in range(args.warmup):
+            ea.entmax_attn_decode(Q, K, V, alpha, workspace=ws)
+        torch.cuda.synchronize()
+        ea.entmax_attn_timer_enable(True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            O, tau, support, iters = ea.entmax_attn_decode(Q, K, V, alpha, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        kt = ea.entmax_attn_timer_read()
+        ea.entmax_attn_timer_enable(False)
+        call_us = e0.elapsed_time(e1) * 1e3 / args.steps
+        score_us = kt["decode_scores"][0] * 1e3 / kt["decode_scores"][1]
+        # algorithmic bytes of the score kernel: K once (bf16) + the logits written (fp32) + q
+        score_bytes = B * H * (N * d * 2 + N * 4 + d * 2)
+        rows.append(dict(N=N, heads=B * H, call_us=round(call_us, 1), score_kernel_us=round(score_us, 1),
+                         score_kernel_GBps=round(score_bytes / (score_us * 1e-6) / 1e9, 1),
+                         tokens_per_s=round(B * H / (call_us * 1e-6), 1),
+                         mean_support=round(float(support.float().mean().item()), 2),
+                         mean_tau_iters=round(float(iters.float().mean().item()), 2)))
+        log(rows[-1])
+        if N == 131072:
+            roofline = dict(bound="hbm", kernel="decode_scores_kernel", achieved=rows[-1]["score_kernel_GBps"], peak=8000.0,
+                            unit="GB/s", frac=round(rows[-1]["score_kernel_GBps"] / 8000.0, 4), traffic=None,
+                            avg_launch_ms=round(score_us * 1e-3, 4))
+            if not args.no_cpu_baseline:
+                c0 = time.perf_counter()
+                eo.attn_decode(q.double().numpy(), k.double().numpy(), v.double().numpy(), alpha)
+                c1 = time.perf_counter()
+                cpu_baseline = dict(value=round(B * H / (c1 - c0), 2), unit="head-queries/s", cores=eo.num_threads(), kind="oracle",
+                                    seconds=round(c1 - c0, 2), sample=f"float64 oracle, all {B * H} heads at N={N}")
+        del Q, K, V, ws
+        torch.cuda.empty_cache()
+    last = rows[-1]
+    print(json.dumps(dict(metric="decode: head-queries/s of one-query alpha-entmax attention against a 128k-token cache",
+                          value=last["tokens_per_s"], unit="head-queries/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+                          ms_per_step=round(last["call_us"] * 1e-3, 4), higher_is_better=True, scaling="weak", vs_baseline=None,
+                          dtype="bf16", data="synthetic",
+                          config=dict(workload=f"inference variant: alpha={alpha} bf16 B={B} H={H} d={d}, one query per head, "
+                                               f"cache lengths 8k/32k/128k, Q,K ~ N(0,{sigma * sigma:g})"),
+                          lengths=rows, roofline=roofline, cpu_baseline=cpu_baseline)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -125,9 +182,10 @@ def main():
                     help="block-correlated query variant of the generator (0 = i.i.d. rows as in the config)")
     ap.add_argument("--small", action="store_true", help="N=2048 instead of 16384 (plumbing check only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["sparsity", "context"], default="sparsity",
+    ap.add_argument("--workload", choices=["sparsity", "context", "decode"], default="sparsity",
                     help="sparsity: the sigma sweep at N=16k the metric is quoted on (default); "
-                         "context: forward+backward time against context length 4K..128K at a fixed token budget")
+                         "context: forward+backward time against context length 4K..128K at a fixed token budget; "
+                         "decode: one query per head against an 8k..128k-token cache (inference variant)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; heads would shard over GPUs with no communication, "
@@ -144,6 +202,9 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "context":
         context_scaling(ea, workloads, dev, args)
+        return
+    if args.workload == "decode":
+        decode_workload(ea, workloads, dev, args)
         return
     cfg = dict(workloads.CONFIGS["c3_bf16_n16k"])
     if args.small:

@@ -181,7 +181,8 @@ enum {
     EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
     EA_TIMER_BWD_PREP = 4,  /* max |dO| and the fp16 copies of K, Q, V, dO (bf16 inputs) */
     EA_TIMER_DQ = 5,        /* delta and dQ, one sweep */
-    EA_TIMER_DKDV = 6       /* dK, dV */
+    EA_TIMER_DKDV = 6,      /* dK, dV */
+    EA_TIMER_DECODE_SCORES = 7 /* entmax_attn_decode: the kernel that reads K and writes the logits */
 };
 int entmax_attn_timer_enable(int on);
 int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);

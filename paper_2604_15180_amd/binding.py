@@ -18,7 +18,7 @@ EA_STATS_COPIES = 64
 STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
               "sweeps", "mask_subtiles", "out_pv_subtiles", "list_overflow_blocks")
 EA_TIMER_SLOTS = 8
-TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "unused")
+TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "decode_scores")
 
 
 class EntmaxAttnError(RuntimeError):

@@ -166,6 +166,7 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const f16x8* data, floa
 
 namespace ea {
 void set_last_hip_error(int e) { g_last_hip_error = e; }
+void timer_begin() { timer_begin_call(); }
 void timer_mark(int slot, int which, hipStream_t s) {
     if (g_timer_call < 0) return;
     (void)hipEventRecord(g_timer.ev[g_timer_call][slot][which], s);

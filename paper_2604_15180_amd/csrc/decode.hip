@@ -214,8 +214,12 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
 
 template <class E, int D>
 int decode_run(const DecodeParams& p, hipStream_t s) {
+    timer_begin();
     hipLaunchKernelGGL(decode_reset_kernel, dim3(1), dim3(256), 0, s, p.hmax, p.BH);
-    hipLaunchKernelGGL((decode_scores_kernel<E, D>), dim3((p.N + p.chunk - 1) / p.chunk, p.BH), dim3(256), 0, s, p);
+    {
+        ScopedKernelTime t(EA_TIMER_DECODE_SCORES, s);
+        hipLaunchKernelGGL((decode_scores_kernel<E, D>), dim3((p.N + p.chunk - 1) / p.chunk, p.BH), dim3(256), 0, s, p);
+    }
     switch (p.alpha == 1.5f ? ALPHA_15 : p.alpha == 2.0f ? ALPHA_20 : ALPHA_GEN) {
         case ALPHA_15: hipLaunchKernelGGL((decode_entmax_kernel<E, D, ALPHA_15>), dim3(p.BH), dim3(1024), 0, s, p); break;
         case ALPHA_20: hipLaunchKernelGGL((decode_entmax_kernel<E, D, ALPHA_20>), dim3(p.BH), dim3(1024), 0, s, p); break;

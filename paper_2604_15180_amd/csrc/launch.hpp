@@ -16,6 +16,8 @@ void set_last_hip_error(int e);
 // Records a HIP event on `s` before (which = 0) or after (which = 1) the kernels of timer slot
 // `slot`; does nothing unless timing was switched on for the call in flight.
 void timer_mark(int slot, int which, hipStream_t s);
+// Opens the timer row of a new library call (no-op unless timing is switched on).
+void timer_begin();
 
 struct ScopedKernelTime {
     int slot; hipStream_t s;
