@@ -11,6 +11,8 @@
 //                          and o = sum_j p_j v_j over the support only (a gather of a few rows of V).
 #include <math.h>
 
+#include <type_traits>
+
 #include "fwd_kernels.hpp"
 #include "launch.hpp"
 
@@ -19,30 +21,39 @@ namespace ea {
 struct DecodeParams {
     const void* q; const void* K; const void* V;
     float* O; float* tau; int32_t* support; int32_t* iters;
-    float* logits;            // [BH][N]
-    unsigned int* hmax;       // [BH] maximum logit, as unsigned ints that order like the floats
-    int BH, N, chunk;         // chunk: keys per work-group of the score kernel
+    float* logits;            // [BH][Npad], Npad = N rounded up to 4: every head's logits start 16-byte aligned
+    float* gmax;              // [BH][ngrp] maximum logit of each work-group of the score kernel
+    int BH, N, Npad, chunk, ngrp;   // chunk: keys per work-group of the score kernel; ngrp of them per head
     float inv_sqrt_d, alpha, r, tol;
     int max_iters;
 };
 
-EA_DEV unsigned int ordered_bits(float f) {
-    const unsigned int u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u ^ 0x80000000u);
+// Sum of v over each aligned group of G lanes (G = 8, 16 or 32), left in all of the group's lanes.
+// Within a row of 16 lanes the exchanges are data-parallel-primitive modifiers of the add itself
+// (quad permutes, then mirrors: once every lane of a half holds its half's sum, the mirrored lane
+// holds the other half's), so a key row's dot product costs four ALU operations and no LDS traffic.
+template <int CTRL> EA_DEV float dpp_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
-EA_DEV float from_ordered_bits(unsigned int u) { return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u); }
-
-static __global__ void decode_reset_kernel(unsigned int* hmax, int n) {
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) hmax[i] = 0u;   // below every float
+template <int G> EA_DEV float group_sum(float v) {
+    v = dpp_add<0xB1>(v);                       // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);                       // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);                      // row_half_mirror
+    if constexpr (G >= 16) v = dpp_add<0x140>(v);   // row_mirror
+    if constexpr (G >= 32) v += __shfl_xor(v, 16);
+    return v;
 }
 
-// A key row is D elements = LPR lanes x 16 bytes; a wave reads 64 / LPR rows per load, four loads in
-// flight; the row's dot product with q is reduced over its LPR lanes.
+// A key row is D elements = LPR lanes x 16 bytes; a wave reads RPW = 64 / LPR rows per load and a
+// work-group 4 RPW.  U loads per lane form a batch; the next batch is requested before the current
+// one is reduced, so a wave always has loads in flight.  K is read once and never again: the loads
+// are non-temporal, which keeps the stream out of the way of the cached lines.
 template <class E, int D>
 __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
     using elem = typename E::elem;
-    constexpr int EPV = 16 / (int)sizeof(elem), LPR = D / EPV, RPW = 64 / LPR, U = 4;
+    constexpr int EPV = 16 / (int)sizeof(elem), LPR = D / EPV, RPW = 64 / LPR, U = 4, RPB = 4 * RPW * U;
     typedef elem vec __attribute__((ext_vector_type(EPV)));
+    static_assert(LPR == 8 || LPR == 16 || LPR == 32, "a key row spans 8, 16 or 32 lanes");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane % LPR, rsel = lane / LPR;
     const int bh = blockIdx.y;
@@ -52,34 +63,59 @@ __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
 #pragma unroll
     for (int e = 0; e < EPV; ++e) qf[e] = (float)qv[e];
     const elem* Kh = (const elem*)p.K + (long)bh * p.N * D;
-    float* zh = p.logits + (long)bh * p.N;
+    float* zh = p.logits + (long)bh * p.Npad;
+    __shared__ float wmax[4];
     float lmax = -INFINITY;
-    for (long base = k0 + wave * RPW; base < k1; base += 4 * RPW * U) {
-        vec kv[U];
+    const long nfull = (k1 - k0) / RPB;                     // batches with every row inside the chunk
+    const long row_w = k0 + wave * RPW + rsel;              // this lane's row in batch 0, load 0
+    auto load = [&](vec (&kv)[U], long it) {
+        const elem* src = Kh + (row_w + it * RPB) * D + sub * EPV;
+#pragma unroll
+        for (int u = 0; u < U; ++u) kv[u] = __builtin_nontemporal_load((const vec*)(src + (long)u * 4 * RPW * D));
+    };
+    auto reduce = [&](auto guarded, const vec (&kv)[U], long it) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const long row = base + (long)u * 4 * RPW + rsel;
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) kv[u][e] = (elem)0.f;
-            if (row < k1) kv[u] = *(const vec*)(Kh + row * D + sub * EPV);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const long row = base + (long)u * 4 * RPW + rsel;
+            const long row = row_w + it * RPB + (long)u * 4 * RPW;
             float dot = 0.f;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) dot = fmaf(qf[e], (float)kv[u][e], dot);
-#pragma unroll
-            for (int off = LPR / 2; off >= 1; off >>= 1) dot += __shfl_xor(dot, off);
-            const float zval = dot * p.inv_sqrt_d;
-            if (row < k1) {
+            const float zval = group_sum<LPR>(dot) * p.inv_sqrt_d;
+            if (!decltype(guarded)::value || row < k1) {
                 if (sub == 0) zh[row] = zval;
                 lmax = fmaxf(lmax, zval);
             }
         }
+    };
+    if (nfull > 0) {
+        vec ka[U], kb[U];
+        load(ka, 0);
+        for (long it = 0; it < nfull; it += 2) {
+            if (it + 1 < nfull) load(kb, it + 1);
+            reduce(std::false_type{}, ka, it);
+            if (it + 1 < nfull) {
+                if (it + 2 < nfull) load(ka, it + 2);
+                reduce(std::false_type{}, kb, it + 1);
+            }
+        }
     }
+    if (k0 + nfull * RPB < k1) {                            // ragged tail: one guarded batch
+        vec kt[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long row = row_w + nfull * RPB + (long)u * 4 * RPW;
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) kt[u][e] = (elem)0.f;
+            if (row < k1) kt[u] = *(const vec*)(Kh + row * D + sub * EPV);
+        }
+        reduce(std::true_type{}, kt, nfull);
+    }
+    // one maximum per work-group, each in a slot of its own: thousands of atomic maxima on one
+    // cache line would queue up behind each other for longer than a short cache takes to read
     lmax = wave_max(lmax);
-    if (lane == 0 && lmax > -INFINITY) atomicMax(&p.hmax[bh], ordered_bits(lmax));
+    if (lane == 0) wmax[wave] = lmax;
+    __syncthreads();
+    if (tid == 0) p.gmax[(long)bh * p.ngrp + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
 }
 
 template <class E, int D, int AM>
@@ -95,26 +131,41 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
     __shared__ float osum[NWV][D];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int bh = blockIdx.x, N = p.N;
-    const float* z = p.logits + (long)bh * N;
+    const float* z = p.logits + (long)bh * p.Npad;
     const float c = p.alpha - 1.f, r = p.r;
     constexpr float hb = 1.f / NB;
-    const float mx = c * from_ordered_bits(p.hmax[bh]), lower = mx - 1.f;
 
     if (tid < SLOTS) hist[tid] = 0u;
     if (tid == 0) cnt_s = 0;
+    float gm = -INFINITY;
+    for (int i = tid; i < p.ngrp; i += T) gm = fmaxf(gm, p.gmax[(long)bh * p.ngrp + i]);
+    gm = wave_max(gm);
+    if (lane == 0) red[wave][0] = gm;
     __syncthreads();
-    // candidates: scores within one unit of the maximum (Eq. 5), compacted and binned (Eq. 6-8)
-    for (int j0 = tid; j0 < N; j0 += 4 * T) {
-        float zv[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) zv[u] = (j0 + u * T < N) ? z[j0 + u * T] : -INFINITY;
+    for (int w = 0; w < NWV; ++w) gm = fmaxf(gm, red[w][0]);
+    const float mx = c * gm, lower = mx - 1.f;
+    // candidates: scores within one unit of the maximum (Eq. 5), compacted and binned (Eq. 6-8);
+    // four 16-byte loads per thread in flight (the padding of the last four reads as is: tested below)
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    for (int j0 = 4 * tid; j0 < N; j0 += 16 * T) {
+        f32x4 zv[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const float x = c * zv[u];
-            if (x >= lower) {
-                const int slot = atomicAdd(&cnt_s, 1);
-                if (slot < CAP) { lx[slot] = x; lj[slot] = j0 + u * T; }
-                atomicAdd(&hist[min((int)((x - lower) * (float)NB), SLOTS - 1)], 1u);
+            zv[u] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (j0 + u * 4 * T < N) zv[u] = *(const f32x4*)(z + j0 + u * 4 * T);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int j = j0 + u * 4 * T + e;
+                const float x = c * zv[u][e];
+                if (j < N && x >= lower) {
+                    const int slot = atomicAdd(&cnt_s, 1);
+                    if (slot < CAP) { lx[slot] = x; lj[slot] = j; }
+                    atomicAdd(&hist[min((int)((x - lower) * (float)NB), SLOTS - 1)], 1u);
+                }
             }
         }
     }
@@ -215,10 +266,9 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
 template <class E, int D>
 int decode_run(const DecodeParams& p, hipStream_t s) {
     timer_begin();
-    hipLaunchKernelGGL(decode_reset_kernel, dim3(1), dim3(256), 0, s, p.hmax, p.BH);
     {
         ScopedKernelTime t(EA_TIMER_DECODE_SCORES, s);
-        hipLaunchKernelGGL((decode_scores_kernel<E, D>), dim3((p.N + p.chunk - 1) / p.chunk, p.BH), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((decode_scores_kernel<E, D>), dim3(p.ngrp, p.BH), dim3(256), 0, s, p);
     }
     switch (p.alpha == 1.5f ? ALPHA_15 : p.alpha == 2.0f ? ALPHA_20 : ALPHA_GEN) {
         case ALPHA_15: hipLaunchKernelGGL((decode_entmax_kernel<E, D, ALPHA_15>), dim3(p.BH), dim3(1024), 0, s, p); break;
@@ -234,6 +284,16 @@ int decode_run(const DecodeParams& p, hipStream_t s) {
 
 namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+// Keys per work-group of the score kernel: about four work-groups per CU over all heads, each a
+// multiple of 256 keys.
+int decode_chunk(int BH, int N) {
+    const int want = (1024 + BH - 1) / BH;
+    int chunk = (N + want - 1) / want;
+    chunk = ((chunk + 255) / 256) * 256;
+    return chunk < 256 ? 256 : chunk;
+}
+int decode_groups(int BH, int N) { const int ch = decode_chunk(BH, N); return (N + ch - 1) / ch; }
+size_t decode_npad(int N) { return ((size_t)N + 3) & ~(size_t)3; }
 bool decode_shape_ok(int B, int H, int N, int d, ea_dtype t) {
     return (t == EA_F32 || t == EA_BF16) && B > 0 && H > 0 && (long)B * H <= 65535 && N > 0 && N <= (1 << 22) && (d == 64 || d == 128);
 }
@@ -243,7 +303,7 @@ extern "C" {
 
 size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype t) {
     if (!decode_shape_ok(B, H, N, d, t)) return 0;
-    return align256((size_t)B * H * 4) + align256((size_t)B * H * N * 4);
+    return align256((size_t)B * H * decode_groups(B * H, N) * 4) + align256((size_t)B * H * decode_npad(N) * 4);
 }
 
 int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
@@ -258,14 +318,11 @@ int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, fl
         return EA_ERR_WORKSPACE;
     DecodeParams p{};
     p.q = q; p.K = K; p.V = V; p.O = O; p.tau = tau; p.support = support; p.iters = iters;
-    p.hmax = (unsigned int*)workspace;
-    p.logits = (float*)((char*)workspace + align256((size_t)B * H * 4));
-    p.BH = B * H; p.N = N;
-    // about four work-groups of the score kernel per CU, each a multiple of 256 keys
-    const int want = (1024 + p.BH - 1) / p.BH;
-    int chunk = (N + want - 1) / want;
-    chunk = ((chunk + 255) / 256) * 256;
-    p.chunk = chunk < 256 ? 256 : chunk;
+    p.BH = B * H; p.N = N; p.Npad = (int)decode_npad(N);
+    p.chunk = decode_chunk(p.BH, N);
+    p.ngrp = decode_groups(p.BH, N);
+    p.gmax = (float*)workspace;
+    p.logits = (float*)((char*)workspace + align256((size_t)p.BH * p.ngrp * 4));
     p.inv_sqrt_d = 1.f / sqrtf((float)d);
     p.alpha = alpha; p.r = 1.f / (alpha - 1.f);
     p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
