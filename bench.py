@@ -142,8 +142,9 @@ def decode_workload(ea, workloads, dev, args):
         ea.entmax_attn_timer_enable(False)
         call_us = e0.elapsed_time(e1) * 1e3 / args.steps
         score_us = kt["decode_scores"][0] * 1e3 / kt["decode_scores"][1]
-        # algorithmic bytes of the score kernel: K once (bf16) + the logits written (fp32) + q
-        score_bytes = B * H * (N * d * 2 + N * 4 + d * 2)
+        # algorithmic bytes of the score kernel: K once (bf16) + q (the few logits it keeps, those
+        # within the window of Eq. 5 below the running maximum, are not counted)
+        score_bytes = B * H * (N * d * 2 + d * 2)
         rows.append(dict(N=N, heads=B * H, call_us=round(call_us, 1), score_kernel_us=round(score_us, 1),
                          score_kernel_GBps=round(score_bytes / (score_us * 1e-6) / 1e9, 1),
                          tokens_per_s=round(B * H / (call_us * 1e-6), 1),

@@ -2,11 +2,15 @@
 // inference a simplified variant runs on the fully materialised logits z of one query; Sec. 5
 // leaves an optimised inference kernel to future work): one query row per head against all N
 // cached keys.
-//   decode_scores_kernel : z_j = <q, k_j> / sqrt(d) for all keys, written to the workspace, and the
-//                          head's maximum logit.  Reads K once: this is the kernel the HBM roofline
-//                          prices (N d element bytes per head against 2 N d flops).
-//   decode_entmax_kernel : per head, tau from the logits - scores within one unit of the maximum
-//                          (Eq. 5) compacted into LDS, histogram (Eq. 6-8) and its root (Eq. 9), then
+//   decode_scores_kernel : z_j = <q, k_j> / sqrt(d) for all keys.  Reads K once: this is the kernel
+//                          the HBM roofline prices (N d element bytes per head against 2 N d flops).
+//                          By Eq. 5 only logits within 1 / (alpha - 1) of the head's maximum can be
+//                          in the support, and a running maximum is a lower bound of the final one,
+//                          so a work-group keeps just the logits within that window of the largest
+//                          it has met so far (a few per cent of them) and its own maximum: the other
+//                          logits are never written.
+//   decode_entmax_kernel : per head, tau from the kept logits - those within one unit of the true
+//                          maximum compacted into LDS, histogram (Eq. 6-8) and its root (Eq. 9), then
 //                          the safeguarded hybrid refinement (Sec. 3.2) over the compacted scores -
 //                          and o = sum_j p_j v_j over the support only (a gather of a few rows of V).
 #include <math.h>
@@ -21,12 +25,21 @@ namespace ea {
 struct DecodeParams {
     const void* q; const void* K; const void* V;
     float* O; float* tau; int32_t* support; int32_t* iters;
-    float* logits;            // [BH][Npad], Npad = N rounded up to 4: every head's logits start 16-byte aligned
-    float* gmax;              // [BH][ngrp] maximum logit of each work-group of the score kernel
-    int BH, N, Npad, chunk, ngrp;   // chunk: keys per work-group of the score kernel; ngrp of them per head
+    uint2* cand;              // [BH][ngrp][chunk] kept logits: (bits of z_j, j)
+    int* ccnt;                // [BH][ngrp] how many each work-group of the score kernel kept
+    float* gmax;              // [BH][ngrp] maximum logit of each work-group
+    int BH, N, chunk, ngrp;   // chunk: keys per work-group of the score kernel; ngrp of them per head
     float inv_sqrt_d, alpha, r, tol;
+    float zwin;               // 1 / (alpha - 1), slightly widened: the window of Eq. 5 in units of z
     int max_iters;
 };
+
+// unsigned integers that order like the floats they come from (for an integer atomic maximum)
+EA_DEV unsigned int ordered_bits(float f) {
+    const unsigned int u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u ^ 0x80000000u);
+}
+EA_DEV float from_ordered_bits(unsigned int u) { return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u); }
 
 // Sum of v over each aligned group of G lanes (G = 8, 16 or 32), left in all of the group's lanes.
 // Within a row of 16 lanes the exchanges are data-parallel-primitive modifiers of the add itself
@@ -48,12 +61,17 @@ template <int G> EA_DEV float group_sum(float v) {
 // work-group 4 RPW.  U loads per lane form a batch; the next batch is requested before the current
 // one is reduced, so a wave always has loads in flight.  K is read once and never again: the loads
 // are non-temporal, which keeps the stream out of the way of the cached lines.
+// A logit is kept when it is within the window of the largest logit known so far: the largest this
+// lane has computed, or the one the work-group's waves share through an LDS word.
 template <class E, int D>
 __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
     using elem = typename E::elem;
     constexpr int EPV = 16 / (int)sizeof(elem), LPR = D / EPV, RPW = 64 / LPR, U = 4, RPB = 4 * RPW * U;
     typedef elem vec __attribute__((ext_vector_type(EPV)));
     static_assert(LPR == 8 || LPR == 16 || LPR == 32, "a key row spans 8, 16 or 32 lanes");
+    __shared__ float wmax[4];
+    __shared__ unsigned int smax;                           // ordered bits of the shared running maximum
+    __shared__ int lcnt;                                    // logits kept so far
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int sub = lane % LPR, rsel = lane / LPR;
     const int bh = blockIdx.y;
@@ -63,8 +81,9 @@ __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
 #pragma unroll
     for (int e = 0; e < EPV; ++e) qf[e] = (float)qv[e];
     const elem* Kh = (const elem*)p.K + (long)bh * p.N * D;
-    float* zh = p.logits + (long)bh * p.Npad;
-    __shared__ float wmax[4];
+    uint2* const kept = p.cand + ((size_t)bh * p.ngrp + blockIdx.x) * (size_t)p.chunk;
+    if (tid == 0) { smax = ordered_bits(-INFINITY); lcnt = 0; }
+    __syncthreads();
     float lmax = -INFINITY;
     const long nfull = (k1 - k0) / RPB;                     // batches with every row inside the chunk
     const long row_w = k0 + wave * RPW + rsel;              // this lane's row in batch 0, load 0
@@ -74,29 +93,51 @@ __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
         for (int u = 0; u < U; ++u) kv[u] = __builtin_nontemporal_load((const vec*)(src + (long)u * 4 * RPW * D));
     };
     auto reduce = [&](auto guarded, const vec (&kv)[U], long it) {
+        float zval[U];
+        float bmax = -INFINITY;
+        const long row0 = row_w + it * RPB;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const long row = row_w + it * RPB + (long)u * 4 * RPW;
             float dot = 0.f;
 #pragma unroll
             for (int e = 0; e < EPV; ++e) dot = fmaf(qf[e], (float)kv[u][e], dot);
-            const float zval = group_sum<LPR>(dot) * p.inv_sqrt_d;
-            if (!decltype(guarded)::value || row < k1) {
-                if (sub == 0) zh[row] = zval;
-                lmax = fmaxf(lmax, zval);
+            zval[u] = group_sum<LPR>(dot) * p.inv_sqrt_d;
+            if (decltype(guarded)::value && row0 + (long)u * 4 * RPW >= k1) zval[u] = -INFINITY;
+            bmax = fmaxf(bmax, zval[u]);
+        }
+        lmax = fmaxf(lmax, bmax);
+        const float shared_max = from_ordered_bits(*(volatile unsigned int*)&smax);
+        const float m = fmaxf(lmax, shared_max);
+        // rounding in the comparison made later, (alpha - 1) z >= (alpha - 1) max - 1, is far
+        // inside the extra width
+        const float keep = m - p.zwin - 1e-6f * fabsf(m);
+        if (sub == 0 && bmax >= keep) {                     // -inf (a row past the end) never is
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (zval[u] >= keep) {
+                    const int slot = atomicAdd(&lcnt, 1);
+                    kept[slot] = make_uint2(__float_as_uint(zval[u]), (unsigned int)(row0 + (long)u * 4 * RPW));
+                }
             }
+            if (bmax > shared_max) atomicMax(&smax, ordered_bits(bmax));
         }
     };
     if (nfull > 0) {
         vec ka[U], kb[U];
         load(ka, 0);
-        for (long it = 0; it < nfull; it += 2) {
-            if (it + 1 < nfull) load(kb, it + 1);
+        long it = 0;
+        for (; it + 2 < nfull; it += 2) {
+            load(kb, it + 1);
             reduce(std::false_type{}, ka, it);
-            if (it + 1 < nfull) {
-                if (it + 2 < nfull) load(ka, it + 2);
-                reduce(std::false_type{}, kb, it + 1);
-            }
+            load(ka, it + 2);
+            reduce(std::false_type{}, kb, it + 1);
+        }
+        if (it + 1 < nfull) {                               // two batches left, the first one loaded
+            load(kb, it + 1);
+            reduce(std::false_type{}, ka, it);
+            reduce(std::false_type{}, kb, it + 1);
+        } else {
+            reduce(std::false_type{}, ka, it);
         }
     }
     if (k0 + nfull * RPB < k1) {                            // ragged tail: one guarded batch
@@ -115,7 +156,10 @@ __global__ __launch_bounds__(256) void decode_scores_kernel(DecodeParams p) {
     lmax = wave_max(lmax);
     if (lane == 0) wmax[wave] = lmax;
     __syncthreads();
-    if (tid == 0) p.gmax[(long)bh * p.ngrp + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+    if (tid == 0) {
+        p.gmax[(long)bh * p.ngrp + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+        p.ccnt[(long)bh * p.ngrp + blockIdx.x] = lcnt;
+    }
 }
 
 template <class E, int D, int AM>
@@ -129,49 +173,70 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
     __shared__ float red[NWV][4];
     __shared__ float bc[2];
     __shared__ float osum[NWV][D];
+    __shared__ int pref[T + 1];             // kept logits of the score kernel's work-groups before group g
+    __shared__ int wsum[NWV];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int bh = blockIdx.x, N = p.N;
-    const float* z = p.logits + (long)bh * p.Npad;
+    const int bh = blockIdx.x, N = p.N, ngrp = p.ngrp;
+    const uint2* kept = p.cand + (size_t)bh * ngrp * (size_t)p.chunk;
     const float c = p.alpha - 1.f, r = p.r;
     constexpr float hb = 1.f / NB;
 
     if (tid < SLOTS) hist[tid] = 0u;
     if (tid == 0) cnt_s = 0;
-    float gm = -INFINITY;
-    for (int i = tid; i < p.ngrp; i += T) gm = fmaxf(gm, p.gmax[(long)bh * p.ngrp + i]);
+    // the head's maximum, and the running count of kept logits over the score kernel's work-groups
+    // (at most T of them): entry i of the head's kept logits is entry i - pref[g] of group g
+    float gm = tid < ngrp ? p.gmax[(long)bh * ngrp + tid] : -INFINITY;
+    int incl = tid < ngrp ? p.ccnt[(long)bh * ngrp + tid] : 0;
     gm = wave_max(gm);
-    if (lane == 0) red[wave][0] = gm;
-    __syncthreads();
 #pragma unroll
-    for (int w = 0; w < NWV; ++w) gm = fmaxf(gm, red[w][0]);
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+    }
+    if (lane == 0) red[wave][0] = gm;
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int before = 0;
+#pragma unroll
+    for (int w = 0; w < NWV; ++w) {
+        gm = fmaxf(gm, red[w][0]);
+        before += w < wave ? wsum[w] : 0;
+    }
+    pref[tid + 1] = before + incl;
+    if (tid == 0) pref[0] = 0;
+    __syncthreads();
+    const int M = pref[ngrp];
     const float mx = c * gm, lower = mx - 1.f;
+    auto kept_at = [&](int i) {             // i < M
+        int lo = 0, hi = ngrp;              // pref[lo] <= i < pref[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (pref[mid] <= i) lo = mid; else hi = mid;
+        }
+        return kept[(size_t)lo * p.chunk + (i - pref[lo])];
+    };
     // candidates: scores within one unit of the maximum (Eq. 5), compacted and binned (Eq. 6-8);
-    // four 16-byte loads per thread in flight (the padding of the last four reads as is: tested below)
-    typedef float f32x4 __attribute__((ext_vector_type(4)));
-    for (int j0 = 4 * tid; j0 < N; j0 += 16 * T) {
-        f32x4 zv[4];
+    // four loads per thread in flight
+    for (int i0 = tid; i0 < M; i0 += 4 * T) {
+        uint2 e[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            zv[u] = f32x4{-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            if (j0 + u * 4 * T < N) zv[u] = *(const f32x4*)(z + j0 + u * 4 * T);
+            e[u] = make_uint2(__float_as_uint(-INFINITY), 0u);
+            if (i0 + u * T < M) e[u] = kept_at(i0 + u * T);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int j = j0 + u * 4 * T + e;
-                const float x = c * zv[u][e];
-                if (j < N && x >= lower) {
-                    const int slot = atomicAdd(&cnt_s, 1);
-                    if (slot < CAP) { lx[slot] = x; lj[slot] = j; }
-                    atomicAdd(&hist[min((int)((x - lower) * (float)NB), SLOTS - 1)], 1u);
-                }
+            const float x = c * __uint_as_float(e[u].x);
+            if (x >= lower) {
+                const int slot = atomicAdd(&cnt_s, 1);
+                if (slot < CAP) { lx[slot] = x; lj[slot] = (int)e[u].y; }
+                atomicAdd(&hist[min((int)((x - lower) * (float)NB), SLOTS - 1)], 1u);
             }
         }
     }
     __syncthreads();
     const int total = cnt_s;
-    const bool over = total > CAP;          // then every evaluation streams the logits instead
+    const bool over = total > CAP;          // then every evaluation streams the kept logits instead
     const int nc = min(total, CAP);
     if (tid == 0) {
         const float tau_h = solve_histogram<AM, SLOTS, 32>(hist, 0, 0, hb, r) + lower;
@@ -209,7 +274,7 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
             }
         };
         if (!over) for (int i = tid; i < nc; i += T) term(lx[i]);
-        else for (int j = tid; j < N; j += T) term(c * z[j]);
+        else for (int i = tid; i < M; i += T) term(c * __uint_as_float(kept_at(i).x));
         block_sum3(F, G, Hs);
         ++iters;
         const float f = F - 1.f;
@@ -227,12 +292,15 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
     for (int k = 0; k < CPL; ++k) acc[k] = 0.f;
     float nsup = 0.f, unused1 = 0.f, unused2 = 0.f;
     const elem* Vh = (const elem*)p.V + (long)bh * N * D;
-    const int nsrc = over ? N : nc;
+    const int nsrc = over ? M : nc;
     for (int base = wave * 64; base < nsrc; base += NWV * 64) {
         const int i = base + lane;
         float x = -INFINITY;
         int j = 0;
-        if (i < nsrc) { x = over ? c * z[i] : lx[i]; j = over ? i : lj[i]; }
+        if (i < nsrc) {
+            if (over) { const uint2 e = kept_at(i); x = c * __uint_as_float(e.x); j = (int)e.y; }
+            else { x = lx[i]; j = lj[i]; }
+        }
         const float y = x - thr;
         const float pj = y > 0.f ? pow_r<AM>(y, r) : 0.f;
         unsigned long long todo = __ballot(pj > 0.f);
@@ -293,7 +361,7 @@ int decode_chunk(int BH, int N) {
     return chunk < 256 ? 256 : chunk;
 }
 int decode_groups(int BH, int N) { const int ch = decode_chunk(BH, N); return (N + ch - 1) / ch; }
-size_t decode_npad(int N) { return ((size_t)N + 3) & ~(size_t)3; }
+size_t decode_groups_bytes(int BH, int N) { return align256((size_t)BH * decode_groups(BH, N) * 4); }
 bool decode_shape_ok(int B, int H, int N, int d, ea_dtype t) {
     return (t == EA_F32 || t == EA_BF16) && B > 0 && H > 0 && (long)B * H <= 65535 && N > 0 && N <= (1 << 22) && (d == 64 || d == 128);
 }
@@ -303,7 +371,8 @@ extern "C" {
 
 size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype t) {
     if (!decode_shape_ok(B, H, N, d, t)) return 0;
-    return align256((size_t)B * H * decode_groups(B * H, N) * 4) + align256((size_t)B * H * decode_npad(N) * 4);
+    const int BH = B * H;
+    return 2 * decode_groups_bytes(BH, N) + align256((size_t)BH * decode_groups(BH, N) * (size_t)decode_chunk(BH, N) * 8);
 }
 
 int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
@@ -318,14 +387,17 @@ int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, fl
         return EA_ERR_WORKSPACE;
     DecodeParams p{};
     p.q = q; p.K = K; p.V = V; p.O = O; p.tau = tau; p.support = support; p.iters = iters;
-    p.BH = B * H; p.N = N; p.Npad = (int)decode_npad(N);
+    p.BH = B * H; p.N = N;
     p.chunk = decode_chunk(p.BH, N);
     p.ngrp = decode_groups(p.BH, N);
+    if (p.ngrp > 1024) return EA_ERR_SHAPE;               // decode_entmax_kernel indexes the groups by thread
     p.gmax = (float*)workspace;
-    p.logits = (float*)((char*)workspace + align256((size_t)p.BH * p.ngrp * 4));
+    p.ccnt = (int*)((char*)workspace + decode_groups_bytes(p.BH, N));
+    p.cand = (uint2*)((char*)workspace + 2 * decode_groups_bytes(p.BH, N));
     p.inv_sqrt_d = 1.f / sqrtf((float)d);
     p.alpha = alpha; p.r = 1.f / (alpha - 1.f);
     p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
+    p.zwin = p.r * (1.f + 1e-5f);
     p.max_iters = 16;
     hipStream_t s = (hipStream_t)hip_stream;
     if (t == EA_BF16) return d == 64 ? decode_run<Bf16, 64>(p, s) : decode_run<Bf16, 128>(p, s);
