@@ -115,6 +115,12 @@ def context_scaling(ea, workloads, dev, args):
                           lengths=rows)), flush=True)
 
 
+# HBM bytes of one launch of the decode score kernel at 32 heads x 131072 keys x 128 (bf16), from
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (FETCH_SIZE scaled by 2.0 as for the copy kernel):
+# 524389 KiB x 2 fetched + 328 KiB written - K once, as the algorithmic count has it.
+DECODE_SCORE_TRAFFIC_BYTES = 1.0743e9
+
+
 def decode_workload(ea, workloads, dev, args):
     """Third workload: the inference variant on materialised logits (one query per head against a
     long key/value cache; the paper's appendix on language modelling).  Bandwidth-bound: the score
@@ -153,7 +159,7 @@ def decode_workload(ea, workloads, dev, args):
         log(rows[-1])
         if N == 131072:
             roofline = dict(bound="hbm", kernel="decode_scores_kernel", achieved=rows[-1]["score_kernel_GBps"], peak=8000.0,
-                            unit="GB/s", frac=round(rows[-1]["score_kernel_GBps"] / 8000.0, 4), traffic=None,
+                            unit="GB/s", frac=round(rows[-1]["score_kernel_GBps"] / 8000.0, 4), traffic=DECODE_SCORE_TRAFFIC_BYTES,
                             avg_launch_ms=round(score_us * 1e-3, 4))
             if not args.no_cpu_baseline:
                 c0 = time.perf_counter()
