@@ -66,7 +66,8 @@ enum {
     EA_STAT_SWEEPS = 5,      /* work-groups that ran the sweep-based threshold kernel (each runs one refinement sweep) */
     EA_STAT_MASK_TILES = 6,  /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
     EA_STAT_OUT_PV_TILES = 7, /* sub-tiles of the output phase whose P V product was issued */
-    EA_STAT_LIST_OVERFLOW = 8 /* 64-row blocks whose candidate lists overflowed (redone by the sweep-based kernel) */
+    EA_STAT_LIST_OVERFLOW = 8, /* 64-row blocks whose candidate lists overflowed (redone by the sweep-based kernel) */
+    EA_STAT_GATHER_ROWS = 9   /* rows whose output was gathered from their listed support (no output-phase matmuls) */
 };
 
 /* Edge of the square score tiles that one bit of the block mask stands for (64). */

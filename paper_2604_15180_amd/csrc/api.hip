@@ -39,7 +39,7 @@ constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Layout {
-    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, total;
 };
 
 // element size of the stage-2 copies
@@ -59,6 +59,8 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.rs_f1 = off; off += align256(BH * N * 4);
     L.rs_state = off; off += align256(BH * N * 4);
     L.oflag = off; off += align256(BH * T * 4);                  // 64-row blocks whose candidate lists overflowed
+    L.scnt = off; off += align256(BH * N * 2 * 4);               // support entries at the front of each list
+    L.gflag = off; off += align256(BH * ((size_t)N / 128 + 1) * 4);   // row groups that take the gather kernel
     L.lists = off; off += align256(BH * N * (size_t)(2 * LIST_CAP * 8));   // candidate lists, two per row
     L.total = off;
     return L;
@@ -232,6 +234,8 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
     p.tmax = (_Float16*)(ws + L.tmax);
     p.lists = ws + L.lists;
     p.oflag = (int32_t*)(ws + L.oflag);
+    p.scnt = (int32_t*)(ws + L.scnt);
+    p.gflag = (int32_t*)(ws + L.gflag);
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());

@@ -7,6 +7,9 @@ namespace ea {
 
 constexpr int MAX_T = 2048;     // N <= 131072
 constexpr int MAX_W = 64;       // mask words per row
+// A row group's output comes from the gather kernel when its candidate lists average at most
+// GATHER_LIST_MAX entries per row and its supports at most GATHER_SUP_MAX keys per row.
+constexpr int GATHER_LIST_MAX = 96, GATHER_SUP_MAX = 32;
 constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 constexpr int LIST_CAP = 256;   // candidate entries per (row, lane half)
 
@@ -34,7 +37,10 @@ struct Params {
     int32_t* iters;       // nullable
     float* rs_lo; float* rs_hi; float* rs_f1; int* rs_state;   // [BH][N] solver state handed from tau_kernel to out_kernel
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
-    void* lists;          // [BH][N][2][LIST_CAP] candidate scores (raw score, key tile), 8 bytes each
+    void* lists;          // [BH][N][2][LIST_CAP] candidate scores (raw score, key index), 8 bytes each
+    int32_t* scnt;        // [BH][N][2] entries at the front of each list that are in the support at the final tau
+    int32_t* gflag;       // [BH][ceil(N / grows)] 1 = the rows of this row group get their output by the gather kernel
+    int grows;            // rows per row group of the candidate-list kernel
     int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):

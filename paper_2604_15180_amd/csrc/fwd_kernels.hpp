@@ -454,10 +454,12 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
     __shared__ float pw[AM == ALPHA_GEN ? SLOTS : 1];             // (m h)^r, general alpha only
     // used only once the sweep is over: they live in the key-tile ring
-    static_assert(MR * MAX_W * 4 + MR * 4 + 64 <= NBUF * KT::BYTES, "post-sweep arrays must fit in the ring");
-    uint32_t* const wm = (uint32_t*)kring;
-    int* const over_s = (int*)(kring + MR * MAX_W * 4);
-    unsigned long long* const blk_stats = (unsigned long long*)(kring + MR * MAX_W * 4 + ((MR * 4 + 7) & ~7));
+    static_assert(2 * MR * MAX_W * 4 + MR * 4 + 96 <= NBUF * KT::BYTES, "post-sweep arrays must fit in the ring");
+    uint32_t* const wm = (uint32_t*)kring;                        // working mask (tiles above tau_0)
+    uint32_t* const fmk = (uint32_t*)(kring + MR * MAX_W * 4);    // final mask (tiles of the support)
+    int* const over_s = (int*)(kring + 2 * MR * MAX_W * 4);
+    int* const gsum = (int*)(kring + 2 * MR * MAX_W * 4 + ((MR * 4 + 7) & ~7));   // list entries, support size, obstacles
+    unsigned long long* const blk_stats = (unsigned long long*)(kring + 2 * MR * MAX_W * 4 + ((MR * 4 + 7) & ~7) + 16);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int n = lane & 31, h = lane >> 5;
@@ -595,6 +597,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
             }
             if (!__any(maybe)) return;
             bool grown = false;
+            const int key0 = j * 64 + 8 * h;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
                 const float low = lowv[qb];
@@ -611,8 +614,8 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                             const int rel = max((int)fmaf(c4, sc, k4[qb]), bottom4[qb]);
                             lds_add_u32(hrow + (rel & (4 * SLOTS - 4)), 1u << (SM::CBITS * qb & 31));
                             // a full list keeps overwriting its last entry (its block is redone anyway)
-                            uint2 ent;
-                            ent.x = __float_as_uint(sc); ent.y = (uint32_t)j;
+                            uint2 ent;          // tile row of register v of group g: see causal_hide
+                            ent.x = __float_as_uint(sc); ent.y = (uint32_t)(key0 + 32 * (g >> 1) + 16 * (g & 1) + v);
                             *(uint2*)(lptr[qb] + 8u * (uint32_t)min(cnt[qb], LIST_CAP - 1)) = ent;
                             ++cnt[qb];
                         }
@@ -634,17 +637,21 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     };
     stream_tiles_ring<NBUF, KT::NINST / NW>(njt, kring, KT::BYTES,
         [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); }, sweep_tile);
-    for (int i = tid; i < MR * W; i += THREADS) wm[i] = 0u;      // (the walk ended with a barrier: the ring is free)
+    for (int i = tid; i < MR * W; i += THREADS) { wm[i] = 0u; fmk[i] = 0u; }   // (the walk ended with a barrier: the ring is free)
     if (tid < MR) over_s[tid] = 0;
+    if (tid < 4) gsum[tid] = 0;
     __syncthreads();
     __threadfence();      // the lists are read back below (same lanes, through L2)
 
     // ---- solve and refinement on the lists -----------------------------------------------------
     int any_over = 0;
+    float thr[QB];
+    int iters[QB], done[QB], mycnt[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) { thr[qb] = 0.f; iters[qb] = 0; done[qb] = 1; mycnt[qb] = 0; }
     if (active) {
-        float thr[QB], blo[QB], bhi[QB];
+        float blo[QB], bhi[QB];
         histogram_bound(thr, bhi, false);
-        int iters[QB], done[QB], mycnt[QB];
         float f1_last[QB];
         int nmax = 0;
 #pragma unroll
@@ -677,7 +684,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
 #pragma unroll
                     for (int u = 0; u < 16; ++u) {
                         const uint32_t bits = (u & 1) ? e[qb][u >> 1].z : e[qb][u >> 1].x;
-                        const uint32_t j = (u & 1) ? e[qb][u >> 1].w : e[qb][u >> 1].y;
+                        const uint32_t j = ((u & 1) ? e[qb][u >> 1].w : e[qb][u >> 1].y) >> 6;      // key tile
                         const float y = fmaf(c, __uint_as_float(bits), -thr[qb]);
                         if (i0 + u < mycnt[qb] && y > 0.f) {
                             if constexpr (AM == ALPHA_15) { F[qb] = fmaf(y, y, F[qb]); G[qb] += y; Hs[qb] += 1.f; }
@@ -722,7 +729,70 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
         }
     }
     if (__any(any_over) && lane == 0) atomicOr(&over_s[myrow], 1);
+
+    // ---- sparse row groups: the support itself, for the gather kernel ---------------------------
+    // Where the lists are short, the entries above the final tau - the row's support, a handful of
+    // keys - are moved to the front of their list, with their key indices; gather_out_kernel then
+    // forms O from those rows of V alone, and the block-sparse output kernel skips the row group.
+    {
+        int len = 0, obstacle = any_over;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) { len += mycnt[qb]; obstacle |= !done[qb]; }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) len += __shfl_xor(len, off);
+        if (lane == 0) atomicAdd(&gsum[0], len);
+        if (__any(obstacle) && lane == 0) atomicOr(&gsum[2], 1);
+    }
     __syncthreads();
+    const int nrows = min(BR, N - (int)q0);
+    const bool sparse = p.gflag && gsum[2] == 0 && gsum[0] <= GATHER_LIST_MAX * nrows;
+    if (sparse) {
+        int nsup = 0;
+        if (active) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                int w = 0;
+                uint32_t lastj = 0xffffffffu;
+                for (int i0 = 0; i0 < mycnt[qb]; i0 += 16) {
+                    uint4 e[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        e[u] = make_uint4(0u, 0u, 0u, 0u);
+                        if (i0 + 2 * u < mycnt[qb]) e[u] = *(const uint4*)(lptr[qb] + (i0 + 2 * u) * 8);
+                    }
+                    // (all sixteen are in registers before the first is overwritten; w <= i0 + u)
+#pragma unroll
+                    for (int u = 0; u < 16; ++u) {
+                        uint2 ent;
+                        ent.x = (u & 1) ? e[u >> 1].z : e[u >> 1].x;
+                        ent.y = (u & 1) ? e[u >> 1].w : e[u >> 1].y;
+                        if (i0 + u < mycnt[qb] && fmaf(c, __uint_as_float(ent.x), -thr[qb]) > 0.f) {
+                            *(uint2*)(lptr[qb] + 8 * w) = ent;
+                            ++w;
+                            const uint32_t j = ent.y >> 6;
+                            if (j != lastj) { atomicOr(&fmk[myrow * W + (j >> 5)], 1u << (j & 31)); lastj = j; }
+                        }
+                    }
+                }
+                p.scnt[((long)bh * N + qw0 + 32 * qb + n) * 2 + h] = w;
+                nsup += w;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) nsup += __shfl_xor(nsup, off);
+        if (lane == 0) atomicAdd(&gsum[1], nsup);
+    }
+    __syncthreads();
+    const bool gather = sparse && gsum[1] <= GATHER_SUP_MAX * nrows;
+    if (p.gflag && tid == 0) p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = gather;
+    if (gather) {
+        if (active && h == 0 && p.iters) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) p.iters[(long)bh * N + qw0 + 32 * qb + n] = iters[qb];
+        }
+        for (int i = tid; i < MR * W; i += THREADS)
+            if (I * MR + i / W < T) p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)fmk[i];
+    }
     for (int i = tid; i < MR * W; i += THREADS)
         if (I * MR + i / W < T) p.wmask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] = (int32_t)wm[i];
     if (tid < MR && I * MR + tid < T) p.oflag[(long)bh * T + (long)I * MR + tid] = over_s[tid];
@@ -730,9 +800,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
         int nover = 0;
         if (tid == 0)
             for (int i = 0; i < MR; ++i) nover += over_s[i];
-        const int slot[2] = {0, 8};
-        const unsigned long long val[2] = {ntile_done * QB, (unsigned long long)nover};
-        flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
+        const int slot[3] = {0, 8, 9};
+        const unsigned long long val[3] = {ntile_done * QB, (unsigned long long)nover, (tid == 0 && gather) ? (unsigned long long)nrows : 0ull};
+        flush_counters<3>(blk_stats, p.stats, slot, val, tid, lane);
     }
 }
 
@@ -769,6 +839,10 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
     const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
     const bool active = qw0 < N;
+    if constexpr (!MASK_ONLY) {
+        // row groups whose supports were listed get their output from gather_out_kernel
+        if (p.gflag && p.gflag[(long)bh * ((N + p.grows - 1) / p.grows) + q0 / p.grows]) return;
+    }
     const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + (long)bh * N * D;
     // V in the stage-2 element type (for bf16 inputs: the fp16 copy made by convert_kernel)
@@ -934,6 +1008,64 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
         const int slot[3] = {MASK_ONLY ? 6 : 1, 7, 0};
         const unsigned long long val[3] = {ntile_done * QB, npv_done * QB, nstat_done * QB};
         flush_counters<3>(blk_stats, p.stats, slot, val, tid, lane);
+    }
+}
+
+// Phase 4 for sparse row groups: O_r = sum over the row's support of p_j V_j, from the support
+// entries (raw score, key index) that tau_list_kernel left at the front of the row's two lists.
+// With a handful of non-zeros per row this is a gather of a few rows of V, not a matrix product:
+// sixteen lanes per row, each with D / 16 elements of the row of O; four entries, then their rows
+// of V, are requested together.  V is read in the caller's element type.
+template <class E, int D, int AM>
+__global__ __launch_bounds__(256) void gather_out_kernel(Params p) {
+    using elem = typename E::elem;
+    constexpr int EPT = D / 16;
+    typedef elem vvec __attribute__((ext_vector_type(EPT)));
+    typedef float ovec __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
+    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, G, bh, I);
+    if (!p.gflag[(long)bh * G + I]) return;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
+    const elem* Vh = (const elem*)p.V + (long)bh * N * D + sub * EPT;
+    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * LIST_CAP * 8);
+    const int row_end = min(N, (I + 1) * p.grows);
+    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+        const long gi = (long)bh * N + row;
+        const float tau = p.tau[gi];
+        const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
+        const char* l0 = lists_h + (size_t)row * (2 * LIST_CAP * 8);      // the second list follows the first
+        float acc[EPT];
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) acc[k] = 0.f;
+        for (int i0 = 0; i0 < tot; i0 += 4) {
+            uint2 e[4];
+            vvec v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u;
+                e[u] = make_uint2(0u, 0u);
+                if (i < tot) e[u] = *(const uint2*)(l0 + (i < s0 ? i * 8 : LIST_CAP * 8 + (i - s0) * 8));
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) v[u][k] = (elem)0.f;
+                if (i0 + u < tot) v[u] = *(const vvec*)(Vh + (long)e[u].y * D);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float y = fmaf(c, __uint_as_float(e[u].x), -tau);
+                const float pr = (i0 + u < tot && y > 0.f) ? pow_r<AM>(y, r) : 0.f;
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) acc[k] = fmaf(pr, (float)v[u][k], acc[k]);
+            }
+        }
+        float* out = p.O + gi * D + sub * EPT;
+#pragma unroll
+        for (int k = 0; k < EPT; k += 4) *(ovec*)(out + k) = ovec{acc[k], acc[k + 1], acc[k + 2], acc[k + 3]};
     }
 }
 

@@ -66,6 +66,8 @@ struct Ops {
             // refinement on the lists
             constexpr int QBL = (E::EPL == 8) ? QB_TAU : 1;
             constexpr int NBL = (E::EPL == 8) ? NBUF_TAUL : 2;       // fp32 tiles are twice as large
+            static_assert((32 * QBL * NW_TAUL) % (32 * QB * NW_OUT) == 0, "an output group lies inside one row group of the list kernel");
+            p.grows = 32 * QBL * NW_TAUL;
             rc = launch(tau_list_kernel<E, D, QBL, AM, NBINS, NW_TAUL, NBL>, groups(p, NW_TAUL, QBL), NW_TAUL * 64, s, p);
             if (rc) return rc;
             // sweep-based fallback for row blocks whose lists overflowed (exits at once elsewhere);
@@ -77,6 +79,9 @@ struct Ops {
             if (rc) return rc;
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
+        // sparse row groups: a gather over each row's support; all others: block-sparse matrix products
+        rc = launch(gather_out_kernel<E, D, AM>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, p);
+        if (rc) return rc;
         return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
     }
     static dim3 groups(const Params& p, int nw, int qb = QB) {

@@ -156,6 +156,30 @@ def test_flat_attention_overflows_candidate_lists(ea, dtype, N):
     print("  flat", info, ginfo, "mean iters", iters.float().mean().item(), flush=True)
 
 
+@pytest.mark.parametrize("dtype,d,alpha,sigma,want", [("bf16", 128, 1.5, 3.0, "all"), ("bf16", 64, 2.0, 3.0, "all"),
+                                                        ("f32", 64, 1.5, 2.0, "any"), ("bf16", 64, 1.25, 2.5, "any"), ("bf16", 128, 1.5, 0.3, "none"),
+                                                        ("bf16", 64, 1.5, 1.6, "any")])
+def test_sparse_row_groups_gather_their_output(ea, dtype, d, alpha, sigma, want):
+    # peaked attention: a handful of keys per row, whose rows of V the gather kernel sums instead
+    # of the block-sparse matrix products; flat attention (tiny scores: every key in the support): no row group qualifies;
+    # in between both output paths may serve parts of one head.  Checked against the oracle alike.
+    B, H, N, causal = 1, 2, 1280, True
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, dtype, sigma, seed=83)
+    Q, K, V = (t.cuda() for t in (q, k, v))
+    ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, dtype, causal, False), dtype=torch.uint8, device="cuda")
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=ws)
+    torch.cuda.synchronize()
+    st = ea.read_stats(ws)
+    print("  gather rows", st["gather_rows"], "of", B * H * N, "out sub-tiles", st["out_subtiles"], flush=True)
+    if want == "all":
+        assert st["gather_rows"] == B * H * N and st["out_subtiles"] == 0
+    elif want == "none":
+        assert st["gather_rows"] == 0
+    _, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label=f"gather {dtype} {alpha} {sigma}")
+    assert int(iters.min()) >= 1
+    print("  ", info, "mean iters", iters.float().mean().item(), flush=True)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_alpha_per_head(ea, dtype):
     # one alpha per head (general-alpha code for all heads, constants from the per-head table),
