@@ -42,6 +42,7 @@ def executed_flops(stats, d):
         "out": unit * (stats.get("out_subtiles", 0) + stats.get("out_pv_subtiles", 0)),
         "dq": unit * 4 * stats.get("dq_subtiles", 0),
         "dkdv": unit * 4 * stats.get("dkdv_subtiles", 0),
+        "bwd_list": unit * stats.get("bwd_list_subtiles", 0),
     }
     return parts
 
@@ -275,7 +276,7 @@ def main():
     dense_flops_point = 14.0 * B * H * N * N * d * (0.5 if causal else 1.0)
     value = dense_flops_point * len(points) / (ms_per_step * 1e-3) / 1e12
 
-    sweep, exec_total = [], {"tau": 0.0, "out": 0.0, "dq": 0.0, "dkdv": 0.0}
+    sweep, exec_total = [], {"tau": 0.0, "out": 0.0, "dq": 0.0, "dkdv": 0.0, "bwd_list": 0.0}
     for pt, pp in zip(points, per_point):
         parts = executed_flops(pp["stats"], d)
         for kname in exec_total:

@@ -67,7 +67,9 @@ enum {
     EA_STAT_MASK_TILES = 6,  /* sub-tiles scored when the backward rebuilds the mask (1 matmul each) */
     EA_STAT_OUT_PV_TILES = 7, /* sub-tiles of the output phase whose P V product was issued */
     EA_STAT_LIST_OVERFLOW = 8, /* 64-row blocks whose candidate lists overflowed (redone by the sweep-based kernel) */
-    EA_STAT_GATHER_ROWS = 9   /* rows whose output was gathered from their listed support (no output-phase matmuls) */
+    EA_STAT_GATHER_ROWS = 9,  /* rows whose output was gathered from their listed support (no output-phase matmuls) */
+    EA_STAT_BWD_LIST_TILES = 10, /* sub-tiles scored when the backward lists the supports of sparse row groups (1 matmul each) */
+    EA_STAT_BWD_GATHER_ROWS = 11 /* rows whose gradients were formed entry by entry from their listed support */
 };
 
 /* Edge of the square score tiles that one bit of the block mask stands for (64). */
@@ -174,7 +176,7 @@ int entmax_attn_last_hip_error(void);
  * kernel time in ms and the number of launches (arrays of at least EA_TIMER_SLOTS entries), and
  * starts a new recording window.  Enabling creates the events once; not thread-safe.
  */
-#define EA_TIMER_SLOTS 8
+#define EA_TIMER_SLOTS 10
 enum {
     EA_TIMER_FWD_PREP = 0,  /* fp16 copy of V (bf16 inputs) */
     EA_TIMER_TAU = 1,       /* dense sweep (maximum, histogram, candidate lists), solve, refinement; fallback kernel */
@@ -183,10 +185,23 @@ enum {
     EA_TIMER_BWD_PREP = 4,  /* max |dO| and the fp16 copies of K, Q, V, dO (bf16 inputs) */
     EA_TIMER_DQ = 5,        /* delta and dQ, one sweep */
     EA_TIMER_DKDV = 6,      /* dK, dV */
-    EA_TIMER_DECODE_SCORES = 7 /* entmax_attn_decode: the kernel that reads K and writes the logits */
+    EA_TIMER_DECODE_SCORES = 7, /* entmax_attn_decode: the kernel that reads K and keeps the logits near the maximum */
+    EA_TIMER_BWD_LIST = 8,  /* backward: supports of the sparse row groups listed (one matrix product per marked tile) */
+    EA_TIMER_BWD_GATHER = 9 /* backward of the sparse row groups from their lists: rows (dQ, delta), then keys (dK, dV) */
 };
 int entmax_attn_timer_enable(int on);
 int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);
+
+/*
+ * Sparse row groups (a handful of non-zeros per row: the regime Sec. 4 reports at long context)
+ * are by default not run through the block-sparse matrix kernels of Alg. 1-3 but evaluated entry by
+ * entry from lists of each row's support: forward, O_r as a sum over a few rows of V; backward,
+ * dQ row by row and dK, dV key by key (EA_STAT_GATHER_ROWS, EA_STAT_BWD_GATHER_ROWS count the rows
+ * that went that way).  Results are the same up to rounding.  entmax_attn_gather_enable(0) keeps
+ * every row group on the matrix kernels (measurement and test aid; process-wide, applies to the
+ * calls made after it); returns EA_OK.
+ */
+int entmax_attn_gather_enable(int on);
 
 /*
  * Matrix-core rate probe (measurement aid: the ceiling the benchmark prices the kernels against

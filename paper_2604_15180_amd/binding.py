@@ -16,9 +16,9 @@ EA_F32, EA_BF16 = 0, 1
 EA_STATS_WORDS = 16
 EA_STATS_COPIES = 64
 STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
-              "sweeps", "mask_subtiles", "out_pv_subtiles", "list_overflow_blocks", "gather_rows")
-EA_TIMER_SLOTS = 8
-TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "decode_scores")
+              "sweeps", "mask_subtiles", "out_pv_subtiles", "list_overflow_blocks", "gather_rows", "bwd_list_subtiles", "bwd_gather_rows")
+EA_TIMER_SLOTS = 10
+TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "decode_scores", "bwd_list", "bwd_gather")
 
 
 class EntmaxAttnError(RuntimeError):
@@ -60,6 +60,8 @@ def lib():
         L.entmax_attn_bwd_alpha_per_head.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, ctypes.POINTER(cf), ci, vp, sz, vp]
         L.entmax_attn_timer_enable.restype = ci
         L.entmax_attn_timer_enable.argtypes = [ci]
+        L.entmax_attn_gather_enable.restype = ci
+        L.entmax_attn_gather_enable.argtypes = [ci]
         L.entmax_attn_timer_read.restype = ci
         L.entmax_attn_timer_read.argtypes = [ctypes.POINTER(cf), ctypes.POINTER(ci), ci]
         L.entmax_attn_decode_workspace_bytes.restype = sz
@@ -222,6 +224,10 @@ def entmax_attn_mfma_probe(data, sink, groups, iters):
     _check(lib().entmax_attn_mfma_probe(_ptr(data), _ptr(sink), int(groups), int(iters),
                                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
     return float(groups) * 4 * iters * 32 * 32768.0
+
+
+def entmax_attn_gather_enable(on):
+    _check(lib().entmax_attn_gather_enable(int(bool(on))))
 
 
 def entmax_attn_timer_enable(on):

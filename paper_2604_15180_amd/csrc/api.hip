@@ -37,9 +37,10 @@ static_assert(STATS_WORDS == EA_STATS_WORDS && STATS_COPIES == EA_STATS_COPIES, 
 constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+bool g_gather_enabled = true;
 
 struct Layout {
-    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, kcnt, klist, total;
 };
 
 // element size of the stage-2 copies
@@ -79,6 +80,12 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.ntau = off; off += align256(BH * N * 4);
     L.mask = off; off += align256(BH * T * W * 4);               // rebuilt mask (mask == NULL)
     L.wmask = off; off += align256(BH * T * W * 4);
+    // sparse row groups: support lists (two per row), their lengths, group flags, lists by key
+    L.lists = off; off += align256(BH * N * (size_t)(2 * BWD_LIST_CAP * 8));
+    L.scnt = off; off += align256(BH * N * 2 * 4);
+    L.gflag = off; off += align256(BH * ((size_t)N / 128 + 1) * 4);
+    L.kcnt = off; off += align256(BH * N * 4 + 4);               // and the count of row groups on the matrix path
+    L.klist = off; off += align256(BH * N * (size_t)(KEY_LIST_CAP * 16));
     L.total = off;
     return L;
 }
@@ -235,7 +242,7 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
     p.lists = ws + L.lists;
     p.oflag = (int32_t*)(ws + L.oflag);
     p.scnt = (int32_t*)(ws + L.scnt);
-    p.gflag = (int32_t*)(ws + L.gflag);
+    p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, (unsigned int*)nullptr);
     EA_HIP(hipGetLastError());
@@ -273,6 +280,12 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
     const bool rebuild = (block_mask == nullptr);
     p.mask = rebuild ? (int32_t*)(ws + L.mask) : const_cast<int32_t*>(block_mask);
     p.scal = (unsigned int*)(ws + L.stats + STATS_BYTES);
+    p.lists = ws + L.lists;
+    p.scnt = (int32_t*)(ws + L.scnt);
+    p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
+    p.kcnt = (int32_t*)(ws + L.kcnt);
+    p.nplain = p.kcnt + (size_t)B * H * N;
+    p.klist = ws + L.klist;
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
     if (per_head == 2) {
@@ -308,6 +321,11 @@ int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, 
                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!alpha_per_head) return EA_ERR_NULL;
     return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
+}
+
+int entmax_attn_gather_enable(int on) {
+    g_gather_enabled = on != 0;
+    return EA_OK;
 }
 
 int entmax_attn_timer_enable(int on) {

@@ -141,6 +141,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
     map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
     const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
     const bool active = qw0 < N;
+    // row groups whose supports were listed get dQ and delta from bwd_rows_kernel
+    if (p.gflag && p.gflag[(long)bh * ((N + p.grows - 1) / p.grows) + q0 / p.grows]) return;
     const long hoff = (long)bh * N * D;
     const elem* Kh = (const elem*)p.K + hoff;
     const elem* Vh = (const elem*)p.V + hoff;
@@ -443,7 +445,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     for (int base = i_min; base < T; base += THREADS) {
         const int i = base + tid;
         int flags = 0;
-        if (i < T) {
+        // (query tiles of row groups whose supports were listed are left to bwd_cols_kernel)
+        if (i < T && !(p.gflag && p.gflag[(long)bh * ((N + p.grows - 1) / p.grows) + (i * 64) / p.grows])) {
 #pragma unroll
             for (int cidx = 0; cidx < MC; ++cidx) {
                 const int j = jc0 + cidx;
@@ -567,6 +570,342 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         const unsigned long long val[1] = {ntile_done * QB};
         flush_counters<1>(blk_stats, p.stats, slot, val, tid, lane);
     }
+}
+
+// ---- backward of sparse row groups by gather --------------------------------------------------
+// Where a row's support is a handful of keys, most tiles the mask marks hold one or two non-zeros,
+// and the four matrix products per tile of dq_kernel / dkdv_kernel are spent on zeros.  For such
+// row groups the backward of Sec. 3.3 is evaluated entry by entry instead:
+//   bwd_list_kernel : one matrix product per marked tile (the scores); every score above the
+//                     row's tau goes, with its key index, to a list private to the lane that
+//                     computed it (two lists per row, as in tau_list_kernel).  A group whose
+//                     lists stay short is flagged; dq_kernel and dkdv_kernel skip flagged groups.
+//   bwd_rows_kernel : per row, over its listed support: dP_j = <dO_r, V_j>, delta, dS_j, and
+//                     dQ_r = sum_j dS_j K_j / sqrt(d) (Alg. 3, row by row); every entry is also
+//                     filed under its key: (row, dS, P).
+//   bwd_cols_kernel : per key, over the entries filed under it: dK_j += sum dS Q_r / sqrt(d),
+//                     dV_j += sum P dO_r (Alg. 2, column by column), added to what dkdv_kernel
+//                     stored for the other row groups.  A key with more entries than its list
+//                     holds took the rest as atomic additions in bwd_rows_kernel.
+// All three read the caller's Q, K, V, dO (not the 16-bit copies) and work in fp32.
+// The gather path pays while a marked 64 x 64 tile holds only a few non-zeros: the group is flagged
+// when its lists hold at most BWD_ENTRIES_PER_TILE entries per marked tile (and no list is full);
+// or BWD_ENTRIES_PER_ROW per row (and no list is full); the sweep is left early once the entries
+// so far run a quarter above that rate.
+template <class E, int D, int QB, int AM, int NW>
+__global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
+    using elem = typename E::elem;
+    using KT = RowTile<E, D>;
+    constexpr int BR = 32 * QB * NW, MR = (BR + 63) / 64, THREADS = NW * 64;
+    __shared__ __align__(1024) char set0[KT::BYTES];
+    __shared__ __align__(1024) char set1[KT::BYTES];
+    __shared__ uint32_t fm[MR * MAX_W];
+    __shared__ int tl[MAX_T];
+    __shared__ int tl_count[4];
+    __shared__ int gsum[4];                  // [0] support entries so far, [1] marked tiles, [2] gave up
+    __shared__ unsigned long long blk_stats[4];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 31, h = lane >> 5;
+    const int N = p.N, T = p.T, W = p.W;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, (N + BR - 1) / BR, bh, I);
+    const long q0 = (long)I * BR, qw0 = q0 + wave * 32 * QB;
+    const bool active = qw0 < N;
+    const elem* Qh = (const elem*)p.Q + (long)bh * N * D;
+    const elem* Kh = (const elem*)p.K + (long)bh * N * D;
+    const int myrow = (wave * 32 * QB) / 64;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c;
+
+    if (tid < 4) gsum[tid] = 0;
+    __syncthreads();
+    {
+        int marked = 0;
+        for (int i = tid; i < MR * W; i += THREADS) {
+            fm[i] = (I * MR + i / W < T) ? (uint32_t)p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)] : 0u;
+            marked += __popc(fm[i]);
+        }
+        if (marked) atomicAdd(&gsum[1], marked);
+    }
+    build_tile_list(fm, MR, W, tl, tl_count, tid);
+    const int nt = *tl_count;
+    // entries the whole group may list (a group with few marked tiles - the first rows of a causal
+    // head - still has one entry or more per row, and is cheap either way)
+    // (the matrix kernels' time per tile goes with D, the gather's time per entry hardly does; the
+    // power functions of general alpha weigh on every entry)
+    constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D / (AM == ALPHA_GEN ? 2 : 1);
+    const int budget = max(PER_TILE_X128 * gsum[1] / 128, BWD_ENTRIES_PER_ROW * min(BR, N - (int)((long)I * BR)));
+
+    Owned<E, D, QB> qf;
+    load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
+    float thr[QB], floor_raw[QB];
+    char* lptr[QB];
+    int cnt[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        thr[qb] = active ? p.tau[(long)bh * N + qw0 + 32 * qb + n] : INFINITY;
+        const float thr_raw = thr[qb] / c;   // a score passes only if it is above about this
+        floor_raw[qb] = thr_raw - (1e-5f * fabsf(thr_raw) + 1e-30f);
+        lptr[qb] = (char*)p.lists + ((size_t)((long)bh * N + (active ? qw0 : 0) + 32 * qb + n) * 2 + h) * (size_t)(BWD_LIST_CAP * 8);
+        cnt[qb] = 0;
+    }
+    unsigned long long ntile = 0;
+    f32x16 C[2][QB];
+    auto issue = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
+    auto compute = [&](int it, const char* buf) {
+        const int j = tl[it];
+        if (!active || !mask_bit(fm, W, myrow, j)) return;
+        stage1<E, D, QB>(C, buf, qf, lane);
+        if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
+        ++ntile;
+        const int key0 = j * 64 + 8 * h;
+        bool full = false;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float gm[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                gm[g] = C[g >> 1][qb][8 * (g & 1)];
+#pragma unroll
+                for (int v = 1; v < 8; ++v) gm[g] = fmaxf(gm[g], C[g >> 1][qb][8 * (g & 1) + v]);
+            }
+            const float lm = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
+            if (!__any(lm > floor_raw[qb])) continue;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if (!__any(gm[g] > floor_raw[qb])) continue;
+#pragma unroll
+                for (int v = 0; v < 8; ++v) {
+                    const float sc = C[g >> 1][qb][8 * (g & 1) + v];
+                    if (fmaf(c, sc, -thr[qb]) > 0.f) {
+                        uint2 ent;          // tile row of register v of group g: see causal_hide
+                        ent.x = __float_as_uint(sc); ent.y = (uint32_t)(key0 + 32 * (g >> 1) + 16 * (g & 1) + v);
+                        *(uint2*)(lptr[qb] + 8 * min(cnt[qb], BWD_LIST_CAP - 1)) = ent;
+                        ++cnt[qb];
+                        lds_add_u32(&gsum[0], 1u);
+                    }
+                }
+            }
+            full |= cnt[qb] > BWD_LIST_CAP;
+        }
+        if (__any(full) && lane == 0) atomicOr(&gsum[2], 1);
+    };
+    // the walk of stream_tiles, left as soon as the gather path cannot pay any more (every wave
+    // reads the counters right after the barrier: all leave together)
+    auto hopeless = [&](int it) {
+        if (*(volatile int*)&gsum[2]) return true;
+        const int e = *(volatile int*)&gsum[0];
+        return e > budget || (it >= 8 && 4l * e * nt > 5l * budget * it);
+    };
+    bool gave_up = false;
+    if (nt > 0) issue(0, set0);
+    for (int it = 0; it < nt; it += 2) {
+        wait_loads();
+        __syncthreads();
+        if ((it & 7) == 0 && (gave_up = hopeless(it))) break;
+        if (it + 1 < nt) issue(it + 1, set1);
+        compute(it, set0);
+        if (it + 1 >= nt) break;
+        wait_loads();
+        __syncthreads();
+        if (it + 2 < nt) issue(it + 2, set0);
+        compute(it + 1, set1);
+    }
+    wait_loads();
+    __syncthreads();
+    const int nrows = min(BR, N - (int)q0);
+    const bool gather = !gave_up && !hopeless(nt);
+    if (active) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) p.scnt[((long)bh * N + qw0 + 32 * qb + n) * 2 + h] = gather ? cnt[qb] : 0;
+    }
+    if (tid == 0) {
+        p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = gather;
+        if (!gather) atomicAdd(p.nplain, 1);
+    }
+    {
+        const int slot[2] = {10, 11};
+        const unsigned long long val[2] = {ntile * QB, (tid == 0 && gather) ? (unsigned long long)nrows : 0ull};
+        flush_counters<2>(blk_stats, p.stats, slot, val, tid, lane);
+    }
+}
+
+// Sixteen lanes per row; lane `sub` holds elements [sub * D/16, (sub + 1) * D/16) of the row's
+// vectors.  SCALED: dkdv_kernel works on dO / max|dO|, so the delta handed to it is in those units.
+template <class E, int D, int AM, bool SCALED>
+__global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
+    using elem = typename E::elem;
+    constexpr int EPT = D / 16;
+    typedef elem vvec __attribute__((ext_vector_type(EPT)));
+    typedef float ovec __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
+    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, G, bh, I);
+    if (!p.gflag[(long)bh * G + I]) return;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
+    float amax = 1.f;
+    if constexpr (SCALED) {
+        amax = __uint_as_float(p.scal[0]);
+        if (!(amax > 0.f)) amax = 1.f;
+    }
+    const long hoff = (long)bh * N * D;
+    const elem* Qh = (const elem*)p.Q + hoff;
+    const elem* Kh = (const elem*)p.K + hoff + sub * EPT;
+    const elem* Vh = (const elem*)p.V + hoff + sub * EPT;
+    const elem* Gh = (const elem*)p.dO + hoff;
+    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * BWD_LIST_CAP * 8);
+    const int row_end = min(N, (I + 1) * p.grows);
+    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+        const long gi = (long)bh * N + row;
+        const float tau = p.tau[gi];
+        const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
+        const char* l0 = lists_h + (size_t)row * (2 * BWD_LIST_CAP * 8);     // the second list follows the first
+        auto entry = [&](int i) { return *(const uint2*)(l0 + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8)); };
+        const vvec gv = *(const vvec*)(Gh + (long)row * D + sub * EPT);
+        float g[EPT];
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) g[k] = (float)gv[k];
+        // first pass: delta = sum u dP / sum u, and the two sums dQ is made of:
+        //   dQ sqrt(d) = sum_j u_j (dP_j - delta) K_j = XA - delta XB
+        float xa[EPT], xb[EPT], num = 0.f, den = 0.f;
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) { xa[k] = 0.f; xb[k] = 0.f; }
+        for (int i0 = 0; i0 < tot; i0 += 4) {
+            uint2 e[4];
+            vvec vv[4], kv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) { vv[u][k] = (elem)0.f; kv[u][k] = (elem)0.f; }
+                if (i0 + u < tot) {
+                    vv[u] = *(const vvec*)(Vh + (long)e[u].y * D);
+                    kv[u] = *(const vvec*)(Kh + (long)e[u].y * D);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float dot = 0.f;
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[u][k], dot);
+                const float dP = group_sum<16>(dot);
+                const float y = fmaf(c, __uint_as_float(e[u].x), -tau);
+                const float uu = (i0 + u < tot && y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                const float t = uu * dP;
+                num += t; den += uu;
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) { xa[k] = fmaf(t, (float)kv[u][k], xa[k]); xb[k] = fmaf(uu, (float)kv[u][k], xb[k]); }
+            }
+        }
+        const float delta = den > 0.f ? num / den : 0.f;
+        {
+            float* out = p.dQ + gi * D + sub * EPT;
+#pragma unroll
+            for (int k = 0; k < EPT; k += 4)
+                *(ovec*)(out + k) = ovec{(xa[k] - delta * xb[k]) * p.inv_sqrt_d, (xa[k + 1] - delta * xb[k + 1]) * p.inv_sqrt_d,
+                                         (xa[k + 2] - delta * xb[k + 2]) * p.inv_sqrt_d, (xa[k + 3] - delta * xb[k + 3]) * p.inv_sqrt_d};
+        }
+        if (sub == 0) {
+            p.delta[gi] = -delta / amax;
+            p.ntau[gi] = -tau / hc.rho;
+        }
+        // second pass: every entry filed under its key
+        for (int i = 0; i < tot; ++i) {
+            const uint2 e = entry(i);
+            const long kj = (long)bh * N + e.y;
+            const vvec vv = *(const vvec*)(Vh + (long)e.y * D);
+            float dot = 0.f;
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[k], dot);
+            const float dP = group_sum<16>(dot);
+            const float y = fmaf(c, __uint_as_float(e.x), -tau);
+            const float uu = y > 0.f ? pow_r1<AM>(y, r) : 0.f;
+            const float pr = y > 0.f ? pow_r<AM>(y, r) : 0.f;
+            const float dS = uu * (dP - delta);
+            int slot = 0;
+            if (sub == 0) slot = atomicAdd(&p.kcnt[kj], 1);
+            slot = __shfl(slot, (tid & 63) & ~15);
+            if (slot < KEY_LIST_CAP) {
+                if (sub == 0)
+                    ((uint4*)p.klist)[kj * KEY_LIST_CAP + slot] = make_uint4((uint32_t)row, __float_as_uint(dS), __float_as_uint(pr), 0u);
+            } else {
+                // a key that many rows attend to: its list is full, add this entry's share directly
+                const float ds = dS * p.inv_sqrt_d;
+                float* dk = p.dK + kj * D + sub;
+                float* dv = p.dV + kj * D + sub;
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) {
+                    unsafeAtomicAdd(dk + 16 * k, ds * (float)Qh[(long)row * D + sub + 16 * k]);
+                    unsafeAtomicAdd(dv + 16 * k, pr * (float)Gh[(long)row * D + sub + 16 * k]);
+                }
+            }
+        }
+    }
+}
+
+// Sixteen lanes per key; the key's dK, dV rows are read, added to, and written back.
+template <class E, int D>
+__global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
+    using elem = typename E::elem;
+    constexpr int EPT = D / 16;
+    typedef elem vvec __attribute__((ext_vector_type(EPT)));
+    typedef float ovec __attribute__((ext_vector_type(4)));
+    const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
+    const int N = p.N, G = (N + 255) / 256;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, G, bh, I);
+    const long hoff = (long)bh * N * D;
+    const elem* Qh = (const elem*)p.Q + hoff + sub * EPT;
+    const elem* Gh = (const elem*)p.dO + hoff + sub * EPT;
+    const int key_end = min(N, (I + 1) * 256);
+    for (int key = I * 256 + rsel; key < key_end; key += 16) {
+        const long kj = (long)bh * N + key;
+        const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
+        if (cnt == 0) continue;
+        const uint4* el = (const uint4*)p.klist + kj * KEY_LIST_CAP;
+        float ak[EPT], av[EPT];
+#pragma unroll
+        for (int k = 0; k < EPT; ++k) { ak[k] = 0.f; av[k] = 0.f; }
+        for (int i0 = 0; i0 < cnt; i0 += 4) {
+            uint4 e[4];
+            vvec qv[4], gv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) e[u] = i0 + u < cnt ? el[i0 + u] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) { qv[u][k] = (elem)0.f; gv[u][k] = (elem)0.f; }
+                if (i0 + u < cnt) {
+                    qv[u] = *(const vvec*)(Qh + (long)e[u].x * D);
+                    gv[u] = *(const vvec*)(Gh + (long)e[u].x * D);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float dS = __uint_as_float(e[u].y), pr = __uint_as_float(e[u].z);     // zero past the end
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) { ak[k] = fmaf(dS, (float)qv[u][k], ak[k]); av[k] = fmaf(pr, (float)gv[u][k], av[k]); }
+            }
+        }
+        float* dk = p.dK + kj * D + sub * EPT;
+        float* dv = p.dV + kj * D + sub * EPT;
+#pragma unroll
+        for (int k = 0; k < EPT; k += 4) {
+            ovec a = *(ovec*)(dk + k), b = *(ovec*)(dv + k);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) { a[q] = fmaf(ak[k + q], p.inv_sqrt_d, a[q]); b[q] += av[k + q]; }
+            *(ovec*)(dk + k) = a;
+            *(ovec*)(dv + k) = b;
+        }
+    }
+}
+
+static __global__ void zero_ints_kernel(int32_t* x, long n) {
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) x[i] = 0;
 }
 
 }  // namespace ea

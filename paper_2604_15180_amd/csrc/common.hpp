@@ -10,6 +10,9 @@ constexpr int MAX_W = 64;       // mask words per row
 // A row group's output comes from the gather kernel when its candidate lists average at most
 // GATHER_LIST_MAX entries per row and its supports at most GATHER_SUP_MAX keys per row.
 constexpr int GATHER_LIST_MAX = 96, GATHER_SUP_MAX = 32;
+// Backward: support entries per lane list (two lists per row), entries per key in the lists by key,
+// and the non-zeros per marked 64 x 64 tile up to which a row group takes the gather path.
+constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 64, BWD_ENTRIES_PER_TILE = 10, BWD_ENTRIES_PER_ROW = 4;
 constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 constexpr int LIST_CAP = 256;   // candidate entries per (row, lane half)
 
@@ -41,6 +44,9 @@ struct Params {
     int32_t* scnt;        // [BH][N][2] entries at the front of each list that are in the support at the final tau
     int32_t* gflag;       // [BH][ceil(N / grows)] 1 = the rows of this row group get their output by the gather kernel
     int grows;            // rows per row group of the candidate-list kernel
+    int32_t* kcnt;        // backward [BH][N]: entries in each key's list
+    int32_t* nplain;      // backward: number of row groups that stay with dq_kernel / dkdv_kernel
+    void* klist;          // backward [BH][N][KEY_LIST_CAP]: (query row, dS, P, -), 16 bytes each
     int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):

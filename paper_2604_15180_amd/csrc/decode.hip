@@ -41,22 +41,6 @@ EA_DEV unsigned int ordered_bits(float f) {
 }
 EA_DEV float from_ordered_bits(unsigned int u) { return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u); }
 
-// Sum of v over each aligned group of G lanes (G = 8, 16 or 32), left in all of the group's lanes.
-// Within a row of 16 lanes the exchanges are data-parallel-primitive modifiers of the add itself
-// (quad permutes, then mirrors: once every lane of a half holds its half's sum, the mirrored lane
-// holds the other half's), so a key row's dot product costs four ALU operations and no LDS traffic.
-template <int CTRL> EA_DEV float dpp_add(float v) {
-    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
-template <int G> EA_DEV float group_sum(float v) {
-    v = dpp_add<0xB1>(v);                       // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E>(v);                       // quad_perm [2,3,0,1]
-    v = dpp_add<0x141>(v);                      // row_half_mirror
-    if constexpr (G >= 16) v = dpp_add<0x140>(v);   // row_mirror
-    if constexpr (G >= 32) v += __shfl_xor(v, 16);
-    return v;
-}
-
 // A key row is D elements = LPR lanes x 16 bytes; a wave reads RPW = 64 / LPR rows per load and a
 // work-group 4 RPW.  U loads per lane form a batch; the next batch is requested before the current
 // one is reduced, so a wave always has loads in flight.  K is read once and never again: the loads

@@ -1088,7 +1088,8 @@ static __global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, in
 // Element-wise copy into another element type, optionally divided by a (bits of a float a >= 0).
 template <class Ein, class Eout>
 __global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* in, typename Eout::elem* out, long n,
-                                                      const unsigned int* amax_bits) {
+                                                      const unsigned int* amax_bits, const int32_t* needed) {
+    if (needed && *needed == 0) return;     // nobody will read the copy
     float mul = 1.f;
     if (amax_bits) {
         const float a = __uint_as_float(*amax_bits);
@@ -1109,8 +1110,9 @@ static __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsig
 // unsigned ints); n is a multiple of 8.  One atomic per block: thousands of them on one word
 // would take longer than reading the tensor.
 template <class E>
-__global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits) {
+__global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits, const int32_t* needed) {
     __shared__ float part[4];
+    if (needed && *needed == 0) return;     // nobody will read the maximum
     float m = 0.f;
     const long stride = (long)gridDim.x * 256 * 8;
     long i = (blockIdx.x * 256L + threadIdx.x) * 8;

@@ -18,6 +18,7 @@ constexpr int NW_TAUL = 4, NBUF_TAUL = 3;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
 constexpr int NW_DQ = 2, NBUF_DQ = 2;
 constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
+constexpr int NW_BLIST = 4;   // waves per row group of the backward's support lists
 
 inline int alpha_mode(float alpha) {
     if (alpha == 1.5f) return ALPHA_15;
@@ -39,9 +40,9 @@ int launch(K kernel, dim3 grid, int threads, hipStream_t s, Params p) {
 }
 
 template <class Ein, class Eout>
-int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, hipStream_t s) {
+int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, const int32_t* needed, hipStream_t s) {
     hipLaunchKernelGGL((convert_kernel<Ein, Eout>), dim3(2048), dim3(256), 0, s, (const typename Ein::elem*)in,
-                       (typename Eout::elem*)out, n, amax_bits);
+                       (typename Eout::elem*)out, n, amax_bits, needed);
     EA_HIP(hipGetLastError());
     return EA_OK;
 }
@@ -56,7 +57,7 @@ struct Ops {
         {
             ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
             if (COPY) {
-                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr, s);
+                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr, nullptr, s);
                 if (rc) return rc;
             }
         }
@@ -80,8 +81,10 @@ struct Ops {
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
         // sparse row groups: a gather over each row's support; all others: block-sparse matrix products
-        rc = launch(gather_out_kernel<E, D, AM>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, p);
-        if (rc) return rc;
+        if (p.gflag) {
+            rc = launch(gather_out_kernel<E, D, AM>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, p);
+            if (rc) return rc;
+        }
         return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
     }
     static dim3 groups(const Params& p, int nw, int qb = QB) {
@@ -98,19 +101,34 @@ struct Ops {
             rc = launch(out_kernel<E, E2, D, QB, AM, true, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
             if (rc) return rc;
         }
+        // sparse row groups: their supports listed from the caller's Q, K (before the 16-bit copies
+        // take their place in p); the flags make dq_kernel and dkdv_kernel skip those groups
+        constexpr int QBB = 1;                                   // rows per lane of the list kernel (two were measured: slower)
+        p.grows = 32 * QBB * NW_BLIST;
+        const Params po = p;
+        // the 16-bit copies and max|dO| are made only if some row group stays with the matrix kernels
+        const int32_t* needed = p.gflag ? p.nplain : nullptr;
+        if (p.gflag) {
+            ScopedKernelTime t(EA_TIMER_BWD_LIST, s);
+            static_assert((32 * QBB * NW_BLIST) % (32 * QB * NW_DQ) == 0 && (32 * QBB * NW_BLIST) % 64 == 0, "a dQ group and a query tile lie inside one row group");
+            hipLaunchKernelGGL(zero_ints_kernel, dim3(256), dim3(256), 0, s, p.kcnt, (long)p.BH * p.N + 1);   // and nplain, right behind
+            EA_HIP(hipGetLastError());
+            rc = launch(bwd_list_kernel<E, D, QBB, AM, NW_BLIST>, groups(p, NW_BLIST, QBB), NW_BLIST * 64, s, po);
+            if (rc) return rc;
+        }
         {
             ScopedKernelTime t(EA_TIMER_BWD_PREP, s);
             if (E2::SCALED) {
                 hipLaunchKernelGGL((amax_kernel<E>), dim3(1024), dim3(256), 0, s, (const typename E::elem*)p.dO,
-                                   (long)p.BH * p.N * D, p.scal);
+                                   (long)p.BH * p.N * D, p.scal, needed);
                 EA_HIP(hipGetLastError());
             }
             if (COPY) {
                 const long n = (long)p.BH * p.N * D;
-                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, needed, s))) return rc;
                 p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
             }
         }
@@ -119,9 +137,21 @@ struct Ops {
             rc = launch(dq_kernel<E2, E2, D, QB, AM, NW_DQ, NBUF_DQ>, groups(p, NW_DQ), NW_DQ * 64, s, p);
             if (rc) return rc;
         }
-        ScopedKernelTime t(EA_TIMER_DKDV, s);
-        constexpr int NB2 = (E2::EPL == 8) ? NBUF_DKDV : 1;     // fp32 tiles are twice as large
-        return launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
+        {
+            ScopedKernelTime t(EA_TIMER_DKDV, s);
+            constexpr int NB2 = (E2::EPL == 8) ? NBUF_DKDV : 1;     // fp32 tiles are twice as large
+            rc = launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
+            if (rc) return rc;
+        }
+        if (p.gflag) {
+            // after dkdv_kernel has stored dK, dV: the listed row groups add their share
+            ScopedKernelTime t(EA_TIMER_BWD_GATHER, s);
+            rc = launch(bwd_rows_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
+            if (rc) return rc;
+            rc = launch(bwd_cols_kernel<E, D>, dim3(p.BH * ((p.N + 255) / 256)), 256, s, po);
+            if (rc) return rc;
+        }
+        return EA_OK;
     }
 };
 

@@ -395,6 +395,22 @@ EA_DEV void store_owned_T(float* g, long row0, const f32x16 (&X)[D / 32][QB], fl
     store_owned_T<D, QB>(g, row0, X, scales, lane);
 }
 
+// Sum of v over each aligned group of G lanes (G = 8, 16 or 32), left in all of the group's lanes.
+// Within a row of 16 lanes the exchanges are data-parallel-primitive modifiers of the add itself
+// (quad permutes, then mirrors: once every lane of a half holds its half's sum, the mirrored lane
+// holds the other half's), so a key row's dot product costs four ALU operations and no LDS traffic.
+template <int CTRL> EA_DEV float dpp_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int G> EA_DEV float group_sum(float v) {
+    v = dpp_add<0xB1>(v);                       // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);                       // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);                      // row_half_mirror
+    if constexpr (G >= 16) v = dpp_add<0x140>(v);   // row_mirror
+    if constexpr (G >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
 EA_DEV float wave_max(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
