@@ -26,7 +26,8 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak (published)
 # HBM bytes per launch (fetched + written) on the default workload, from the FETCH_SIZE / WRITE_SIZE
 # passes summarised in profiles/bench_c3_n16k_counters.md (scaled by the library's own copy kernel)
-HBM_TRAFFIC_BYTES = {"tau": 1.45e9, "out": 1.39e9, "dq": 1.76e9, "dkdv": 1.60e9}
+HBM_TRAFFIC_BYTES = {"tau": 1.49e9, "out": 0.24e9, "dq": 0.22e9, "dkdv": 0.88e9, "bwd_list": 0.42e9}
+KERNEL_OF_TIMER = {"tau": "tau_list_kernel", "out": "out_kernel", "dq": "dq_kernel", "dkdv": "dkdv_kernel", "bwd_list": "bwd_list_kernel"}
 METRIC = "effective fwd+bwd TFLOP/s vs block sparsity at N=16k; mean τ iterations/row"
 
 
@@ -256,7 +257,7 @@ def main():
         torch.cuda.synchronize()
         st = ea.read_stats(pt["ws_f"])
         st_b = ea.read_stats(pt["ws_b"])
-        for kname in ("delta_subtiles", "dq_subtiles", "dkdv_subtiles"):
+        for kname in ("delta_subtiles", "dq_subtiles", "dkdv_subtiles", "bwd_list_subtiles", "bwd_gather_rows"):
             st[kname] = st_b[kname]
         per_point.append(dict(fwd_ms=e0.elapsed_time(e1), bwd_ms=e1.elapsed_time(e2), stats=st,
                               sparsity=block_sparsity(mask, T, causal), iters=float(iters.float().mean().item())))
@@ -285,6 +286,8 @@ def main():
         ex = sum(parts.values())
         sweep.append(dict(sigma=pt["sigma"], block_sparsity=round(pp["sparsity"], 4), mean_tau_iters=round(pp["iters"], 3),
                           fwd_ms=round(pp["fwd_ms"], 3), bwd_ms=round(pp["bwd_ms"], 3),
+                          rows_by_gather=dict(fwd=round(pp["stats"].get("gather_rows", 0) / (B * H * N), 3),
+                                              bwd=round(pp["stats"].get("bwd_gather_rows", 0) / (B * H * N), 3)),
                           effective_tflops=round(dense_flops_point / (tot_ms * 1e-3) / 1e12, 1),
                           executed_tflops=round(ex / (tot_ms * 1e-3) / 1e12, 1),
                           mfma_frac_executed=round(ex / (tot_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)))
@@ -296,7 +299,7 @@ def main():
     dom_avg_ms = dom_ms / dom_launches
     dom_flops_per_launch = exec_total[dom] / len(points)
     achieved = dom_flops_per_launch / (dom_avg_ms * 1e-3) / 1e12
-    roofline = dict(bound="mfma", kernel=dom + "_kernel", achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
+    roofline = dict(bound="mfma", kernel=KERNEL_OF_TIMER[dom], achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4),
                     traffic=(HBM_TRAFFIC_BYTES.get(dom) if (args.sigmas == "1,2,3,4" and not args.small
                                                            and args.block_rho == 0.0) else None),

@@ -813,34 +813,52 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
             p.delta[gi] = -delta / amax;
             p.ntau[gi] = -tau / hc.rho;
         }
-        // second pass: every entry filed under its key
-        for (int i = 0; i < tot; ++i) {
-            const uint2 e = entry(i);
-            const long kj = (long)bh * N + e.y;
-            const vvec vv = *(const vvec*)(Vh + (long)e.y * D);
-            float dot = 0.f;
+        // second pass: every entry filed under its key; four at a time, so that their chains of
+        // dependent memory operations (entry, row of V, slot in the key's list) overlap
+        for (int i0 = 0; i0 < tot; i0 += 4) {
+            uint2 e[4];
+            vvec vv[4];
+            float dS[4], pr[4];
+            int slot[4];
 #pragma unroll
-            for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[k], dot);
-            const float dP = group_sum<16>(dot);
-            const float y = fmaf(c, __uint_as_float(e.x), -tau);
-            const float uu = y > 0.f ? pow_r1<AM>(y, r) : 0.f;
-            const float pr = y > 0.f ? pow_r<AM>(y, r) : 0.f;
-            const float dS = uu * (dP - delta);
-            int slot = 0;
-            if (sub == 0) slot = atomicAdd(&p.kcnt[kj], 1);
-            slot = __shfl(slot, (tid & 63) & ~15);
-            if (slot < KEY_LIST_CAP) {
-                if (sub == 0)
-                    ((uint4*)p.klist)[kj * KEY_LIST_CAP + slot] = make_uint4((uint32_t)row, __float_as_uint(dS), __float_as_uint(pr), 0u);
-            } else {
-                // a key that many rows attend to: its list is full, add this entry's share directly
-                const float ds = dS * p.inv_sqrt_d;
-                float* dk = p.dK + kj * D + sub;
-                float* dv = p.dV + kj * D + sub;
+            for (int u = 0; u < 4; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
 #pragma unroll
-                for (int k = 0; k < EPT; ++k) {
-                    unsafeAtomicAdd(dk + 16 * k, ds * (float)Qh[(long)row * D + sub + 16 * k]);
-                    unsafeAtomicAdd(dv + 16 * k, pr * (float)Gh[(long)row * D + sub + 16 * k]);
+            for (int u = 0; u < 4; ++u) {
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) vv[u][k] = (elem)0.f;
+                if (i0 + u < tot) vv[u] = *(const vvec*)(Vh + (long)e[u].y * D);
+                slot[u] = 0;
+                if (i0 + u < tot && sub == 0) slot[u] = atomicAdd(&p.kcnt[(long)bh * N + e[u].y], 1);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float dot = 0.f;
+#pragma unroll
+                for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[u][k], dot);
+                const float dP = group_sum<16>(dot);
+                const float y = fmaf(c, __uint_as_float(e[u].x), -tau);
+                const float uu = y > 0.f ? pow_r1<AM>(y, r) : 0.f;
+                pr[u] = y > 0.f ? pow_r<AM>(y, r) : 0.f;
+                dS[u] = uu * (dP - delta);
+                slot[u] = __shfl(slot[u], (tid & 63) & ~15);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (i0 + u >= tot) continue;
+                const long kj = (long)bh * N + e[u].y;
+                if (slot[u] < KEY_LIST_CAP) {
+                    if (sub == 0)
+                        ((uint4*)p.klist)[kj * KEY_LIST_CAP + slot[u]] = make_uint4((uint32_t)row, __float_as_uint(dS[u]), __float_as_uint(pr[u]), 0u);
+                } else {
+                    // a key that many rows attend to: its list is full, add this entry's share directly
+                    const float ds = dS[u] * p.inv_sqrt_d;
+                    float* dk = p.dK + kj * D + sub;
+                    float* dv = p.dV + kj * D + sub;
+#pragma unroll
+                    for (int k = 0; k < EPT; ++k) {
+                        unsafeAtomicAdd(dk + 16 * k, ds * (float)Qh[(long)row * D + sub + 16 * k]);
+                        unsafeAtomicAdd(dv + 16 * k, pr[u] * (float)Gh[(long)row * D + sub + 16 * k]);
+                    }
                 }
             }
         }
