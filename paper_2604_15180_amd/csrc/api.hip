@@ -84,7 +84,7 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.lists = off; off += align256(BH * N * (size_t)(2 * BWD_LIST_CAP * 8));
     L.scnt = off; off += align256(BH * N * 2 * 4);
     L.gflag = off; off += align256(BH * ((size_t)N / 128 + 1) * 4);
-    L.kcnt = off; off += align256(BH * N * 4 + 4);               // and the count of row groups on the matrix path
+    L.kcnt = off; off += align256(BH * N * 4 + 8);               // and two counters: row groups on the matrix path, set mask bits
     L.klist = off; off += align256(BH * N * (size_t)(KEY_LIST_CAP * 16));
     L.total = off;
     return L;
@@ -285,6 +285,7 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
     p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
     p.kcnt = (int32_t*)(ws + L.kcnt);
     p.nplain = p.kcnt + (size_t)B * H * N;
+    p.nmarked = p.nplain + 1;
     p.klist = ws + L.klist;
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());

@@ -618,6 +618,15 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     const HeadConsts hc = head_consts(p, bh);
     const float c = hc.c;
 
+    // a mask with few marked tiles altogether: the matrix kernels are done before the gather
+    // kernels' passes over dK, dV would be
+    if ((long)*p.nmarked * D < (long)BWD_MIN_TILES_PER_BLOCK * 128 * p.BH * T) {
+        if (tid == 0) {
+            p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = 0;
+            atomicAdd(p.nplain, 1);
+        }
+        return;
+    }
     if (tid < 4) gsum[tid] = 0;
     __syncthreads();
     {
@@ -631,11 +640,14 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     build_tile_list(fm, MR, W, tl, tl_count, tid);
     const int nt = *tl_count;
     // entries the whole group may list (a group with few marked tiles - the first rows of a causal
-    // head - still has one entry or more per row, and is cheap either way)
-    // (the matrix kernels' time per tile goes with D, the gather's time per entry hardly does; the
-    // power functions of general alpha weigh on every entry)
-    constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D / (AM == ALPHA_GEN ? 2 : 1);
-    const int budget = max(PER_TILE_X128 * gsum[1] / 128, BWD_ENTRIES_PER_ROW * min(BR, N - (int)((long)I * BR)));
+    // head - still has one entry or more per row, and is cheap either way: it goes with the rest,
+    // so that the matrix kernels' input copies are not made for its sake alone)
+    // (the matrix kernels' time per tile goes with D, the gather's time per entry hardly does -
+    // measured break-even: about 16 entries per tile at D = 128, 4 at D = 64; the power functions
+    // of general alpha weigh on every entry)
+    constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
+    const int budget = max(PER_TILE_X128 * gsum[1] / 128,
+                           gsum[1] <= BWD_FEW_TILES ? BWD_ENTRIES_PER_ROW * min(BR, N - (int)((long)I * BR)) : 0);
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
@@ -920,6 +932,14 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
             *(ovec*)(dv + k) = b;
         }
     }
+}
+
+static __global__ void mask_popcount_kernel(const int32_t* mask, long nwords, int32_t* out) {
+    int c = 0;
+    for (long i = blockIdx.x * (long)blockDim.x + threadIdx.x; i < nwords; i += (long)gridDim.x * blockDim.x) c += __popc((uint32_t)mask[i]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off);
+    if ((threadIdx.x & 63) == 0 && c) atomicAdd(out, c);
 }
 
 static __global__ void zero_ints_kernel(int32_t* x, long n) {

@@ -12,7 +12,11 @@ constexpr int MAX_W = 64;       // mask words per row
 constexpr int GATHER_LIST_MAX = 96, GATHER_SUP_MAX = 32;
 // Backward: support entries per lane list (two lists per row), entries per key in the lists by key,
 // and the non-zeros per marked 64 x 64 tile up to which a row group takes the gather path.
-constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 64, BWD_ENTRIES_PER_TILE = 10, BWD_ENTRIES_PER_ROW = 4;
+constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 64, BWD_ENTRIES_PER_TILE = 16, BWD_ENTRIES_PER_ROW = 4, BWD_FEW_TILES = 16;
+// The gather kernels' fixed cost is a few passes over dK and dV; below this many marked tiles per
+// 64-row block (at head dim 128; twice as many at 64) the matrix kernels' whole time is less.
+constexpr int BWD_MIN_TILES_PER_BLOCK = 16;
+
 constexpr int ALPHA_15 = 0, ALPHA_20 = 1, ALPHA_GEN = 2;
 constexpr int LIST_CAP = 256;   // candidate entries per (row, lane half)
 
@@ -46,6 +50,7 @@ struct Params {
     int grows;            // rows per row group of the candidate-list kernel
     int32_t* kcnt;        // backward [BH][N]: entries in each key's list
     int32_t* nplain;      // backward: number of row groups that stay with dq_kernel / dkdv_kernel
+    int32_t* nmarked;     // backward: set bits of the whole mask
     void* klist;          // backward [BH][N][KEY_LIST_CAP]: (query row, dS, P, -), 16 bytes each
     int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;

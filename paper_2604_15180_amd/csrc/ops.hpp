@@ -111,7 +111,9 @@ struct Ops {
         if (p.gflag) {
             ScopedKernelTime t(EA_TIMER_BWD_LIST, s);
             static_assert((32 * QBB * NW_BLIST) % (32 * QB * NW_DQ) == 0 && (32 * QBB * NW_BLIST) % 64 == 0, "a dQ group and a query tile lie inside one row group");
-            hipLaunchKernelGGL(zero_ints_kernel, dim3(256), dim3(256), 0, s, p.kcnt, (long)p.BH * p.N + 1);   // and nplain, right behind
+            hipLaunchKernelGGL(zero_ints_kernel, dim3(256), dim3(256), 0, s, p.kcnt, (long)p.BH * p.N + 2);   // and nplain, nmarked, right behind
+            EA_HIP(hipGetLastError());
+            hipLaunchKernelGGL(mask_popcount_kernel, dim3(64), dim3(256), 0, s, p.mask, (long)p.BH * p.T * p.W, p.nmarked);
             EA_HIP(hipGetLastError());
             rc = launch(bwd_list_kernel<E, D, QBB, AM, NW_BLIST>, groups(p, NW_BLIST, QBB), NW_BLIST * 64, s, po);
             if (rc) return rc;
