@@ -191,6 +191,8 @@ def main():
                     help="block-correlated query variant of the generator (0 = i.i.d. rows as in the config)")
     ap.add_argument("--small", action="store_true", help="N=2048 instead of 16384 (plumbing check only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gather", action="store_true",
+                    help="keep every row group on the block-sparse matrix kernels (A/B measurement of the gather paths)")
     ap.add_argument("--workload", choices=["sparsity", "context", "decode"], default="sparsity",
                     help="sparsity: the sigma sweep at N=16k the metric is quoted on (default); "
                          "context: forward+backward time against context length 4K..128K at a fixed token budget; "
@@ -208,6 +210,8 @@ def main():
     import workloads
 
     ea.lib()
+    if args.no_gather:
+        ea.entmax_attn_gather_enable(False)
     dev = torch.device("cuda:0")
     if args.workload == "context":
         context_scaling(ea, workloads, dev, args)
@@ -302,7 +306,7 @@ def main():
     roofline = dict(bound="mfma", kernel=KERNEL_OF_TIMER[dom], achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4),
                     traffic=(HBM_TRAFFIC_BYTES.get(dom) if (args.sigmas == "1,2,3,4" and not args.small
-                                                           and args.block_rho == 0.0) else None),
+                                                           and args.block_rho == 0.0 and not args.no_gather) else None),
                     avg_launch_ms=round(dom_avg_ms, 3),
                     kernels={k: dict(avg_ms=round(v[0] / v[1], 3), launches=v[1],
                                      tflops=(round(exec_total[k] / len(points) / (v[0] / v[1] * 1e-3) / 1e12, 1)
@@ -333,7 +337,8 @@ def main():
                dtype="bf16", data="synthetic",
                config=dict(workload=f"configs[2]: alpha=1.5 bf16 B={B} H={H} N={N} d={d} causal, sigma sweep {sigmas}, "
                                     f"generator={'iid' if args.block_rho == 0 else 'block-correlated rho=%g' % args.block_rho}",
-                           step="forward+backward over each sigma batch", histogram_bins=ea.entmax_attn_histogram_bins()),
+                           step="forward+backward over each sigma batch", histogram_bins=ea.entmax_attn_histogram_bins(),
+                           gather_paths=not args.no_gather),
                mean_tau_iters=round(float(np.mean([pp["iters"] for pp in per_point])), 3),
                sweep=sweep, roofline=roofline, cpu_baseline=cpu_baseline)
     print(json.dumps(out), flush=True)
