@@ -40,7 +40,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 bool g_gather_enabled = true;
 
 struct Layout {
-    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, kcnt, klist, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
 };
 
 // element size of the stage-2 copies
@@ -86,6 +86,7 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.gflag = off; off += align256(BH * ((size_t)N / 128 + 1) * 4);
     L.kcnt = off; off += align256(BH * N * 4 + 8);               // and two counters: row groups on the matrix path, set mask bits
     L.klist = off; off += align256(BH * N * (size_t)(KEY_LIST_CAP * 16));
+    L.defer = off; off += align256(BH * N * 4);
     L.total = off;
     return L;
 }
@@ -287,6 +288,7 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
     p.nplain = p.kcnt + (size_t)B * H * N;
     p.nmarked = p.nplain + 1;
     p.klist = ws + L.klist;
+    p.defer = (int32_t*)(ws + L.defer);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
     if (per_head == 2) {

@@ -422,6 +422,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     int bh, J;
     map_block(blockIdx.x, p.BH, (N + BC - 1) / BC, bh, J);
     J = (N + BC - 1) / BC - 1 - J;            // causal: the first key tiles have the longest columns
+    // every row group went by gather: bwd_cols_kernel writes dK, dV itself
+    if (p.gflag && *p.nplain == 0) return;
     const long k0 = (long)J * BC, kw0 = k0 + wave * 32 * QB;
     const bool active = kw0 < N;
     const long hoff = (long)bh * N * D;
@@ -585,8 +587,10 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 //                     filed under its key: (row, dS, P).
 //   bwd_cols_kernel : per key, over the entries filed under it: dK_j += sum dS Q_r / sqrt(d),
 //                     dV_j += sum P dO_r (Alg. 2, column by column), added to what dkdv_kernel
-//                     stored for the other row groups.  A key with more entries than its list
-//                     holds took the rest as atomic additions in bwd_rows_kernel.
+//                     stored for the other row groups (or, when none was left to it, written as
+//                     dK_j, dV_j themselves).
+//   bwd_hot_kernel  : the entries of keys with more entries than a key's list holds, added to
+//                     dK, dV with atomics after bwd_cols_kernel.
 // All three read the caller's Q, K, V, dO (not the 16-bit copies) and work in fp32.
 // The gather path pays while a marked 64 x 64 tile holds only a few non-zeros: the group is flagged
 // when its lists hold at most BWD_ENTRIES_PER_TILE entries per marked tile (and no list is full);
@@ -826,7 +830,10 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
             p.ntau[gi] = -tau / hc.rho;
         }
         // second pass: every entry filed under its key; four at a time, so that their chains of
-        // dependent memory operations (entry, row of V, slot in the key's list) overlap
+        // dependent memory operations (entry, row of V, slot in the key's list) overlap.  An entry
+        // whose key's list is full is marked (top bit of its key index) and left to bwd_hot_kernel,
+        // which adds it to dK, dV atomically once bwd_cols_kernel has stored those rows.
+        int ndefer = 0;
         for (int i0 = 0; i0 < tot; i0 += 4) {
             uint2 e[4];
             vvec vv[4];
@@ -862,22 +869,78 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
                     if (sub == 0)
                         ((uint4*)p.klist)[kj * KEY_LIST_CAP + slot[u]] = make_uint4((uint32_t)row, __float_as_uint(dS[u]), __float_as_uint(pr[u]), 0u);
                 } else {
-                    // a key that many rows attend to: its list is full, add this entry's share directly
-                    const float ds = dS[u] * p.inv_sqrt_d;
-                    float* dk = p.dK + kj * D + sub;
-                    float* dv = p.dV + kj * D + sub;
-#pragma unroll
-                    for (int k = 0; k < EPT; ++k) {
-                        unsafeAtomicAdd(dk + 16 * k, ds * (float)Qh[(long)row * D + sub + 16 * k]);
-                        unsafeAtomicAdd(dv + 16 * k, pr[u] * (float)Gh[(long)row * D + sub + 16 * k]);
-                    }
+                    const int i = i0 + u;
+                    if (sub == 0)
+                        *(uint32_t*)(const_cast<char*>(l0) + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8) + 4) = e[u].y | 0x80000000u;
+                    ++ndefer;
                 }
+            }
+        }
+        if (sub == 0) p.defer[gi] = ndefer;
+    }
+}
+
+// The entries bwd_rows_kernel marked: keys that more rows attend to than a key's list holds.  Run
+// after bwd_cols_kernel; sixteen lanes per row recompute the entry's dS and P (delta is the row's
+// stored one) and add its share to the key's rows of dK, dV with fp32 atomics, lane-interleaved
+// (lane `sub` takes elements sub, sub + 16, ...: an instruction then covers whole 64-byte pieces).
+template <class E, int D, int AM, bool SCALED>
+__global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
+    using elem = typename E::elem;
+    constexpr int EPT = D / 16;
+    typedef elem vvec __attribute__((ext_vector_type(EPT)));
+    const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
+    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, G, bh, I);
+    if (!p.gflag[(long)bh * G + I]) return;
+    const HeadConsts hc = head_consts(p, bh);
+    const float c = hc.c, r = hc.r;
+    float amax = 1.f;
+    if constexpr (SCALED) {
+        amax = __uint_as_float(p.scal[0]);
+        if (!(amax > 0.f)) amax = 1.f;
+    }
+    const long hoff = (long)bh * N * D;
+    const elem* Qh = (const elem*)p.Q + hoff;
+    const elem* Vh = (const elem*)p.V + hoff + sub * EPT;
+    const elem* Gh = (const elem*)p.dO + hoff;
+    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * BWD_LIST_CAP * 8);
+    const int row_end = min(N, (I + 1) * p.grows);
+    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+        const long gi = (long)bh * N + row;
+        if (p.defer[gi] == 0) continue;
+        const float tau = p.tau[gi], delta = -p.delta[gi] * amax;
+        const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
+        const char* l0 = lists_h + (size_t)row * (2 * BWD_LIST_CAP * 8);
+        const vvec gv = *(const vvec*)(Gh + (long)row * D + sub * EPT);
+        for (int i = 0; i < tot; ++i) {
+            const uint2 e = *(const uint2*)(l0 + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8));
+            if (!(e.y >> 31)) continue;
+            const uint32_t key = e.y & 0x7fffffffu;
+            const vvec vv = *(const vvec*)(Vh + (long)key * D);
+            float dot = 0.f;
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) dot = fmaf((float)gv[k], (float)vv[k], dot);
+            const float dP = group_sum<16>(dot);
+            const float y = fmaf(c, __uint_as_float(e.x), -tau);
+            const float uu = y > 0.f ? pow_r1<AM>(y, r) : 0.f;
+            const float pr = y > 0.f ? pow_r<AM>(y, r) : 0.f;
+            const float ds = uu * (dP - delta) * p.inv_sqrt_d;
+            float* dk = p.dK + ((long)bh * N + key) * D + sub;
+            float* dv = p.dV + ((long)bh * N + key) * D + sub;
+#pragma unroll
+            for (int k = 0; k < EPT; ++k) {
+                unsafeAtomicAdd(dk + 16 * k, ds * (float)Qh[(long)row * D + sub + 16 * k]);
+                unsafeAtomicAdd(dv + 16 * k, pr * (float)Gh[(long)row * D + sub + 16 * k]);
             }
         }
     }
 }
 
-// Sixteen lanes per key; the key's dK, dV rows are read, added to, and written back.
+// Sixteen lanes per key.  Where dkdv_kernel has stored dK, dV for the other row groups, the key's
+// rows are read, added to, and written back; when no row group was left to dkdv_kernel (it then
+// stores nothing) the sums are the rows, and keys without entries get zeros.
 template <class E, int D>
 __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     using elem = typename E::elem;
@@ -892,10 +955,11 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     const elem* Qh = (const elem*)p.Q + hoff + sub * EPT;
     const elem* Gh = (const elem*)p.dO + hoff + sub * EPT;
     const int key_end = min(N, (I + 1) * 256);
+    const bool fresh = *p.nplain == 0;
     for (int key = I * 256 + rsel; key < key_end; key += 16) {
         const long kj = (long)bh * N + key;
         const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
-        if (cnt == 0) continue;
+        if (cnt == 0 && !fresh) continue;
         const uint4* el = (const uint4*)p.klist + kj * KEY_LIST_CAP;
         float ak[EPT], av[EPT];
 #pragma unroll
@@ -925,7 +989,8 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
         float* dv = p.dV + kj * D + sub * EPT;
 #pragma unroll
         for (int k = 0; k < EPT; k += 4) {
-            ovec a = *(ovec*)(dk + k), b = *(ovec*)(dv + k);
+            ovec a = ovec{0.f, 0.f, 0.f, 0.f}, b = a;
+            if (!fresh) { a = *(ovec*)(dk + k); b = *(ovec*)(dv + k); }
 #pragma unroll
             for (int q = 0; q < 4; ++q) { a[q] = fmaf(ak[k + q], p.inv_sqrt_d, a[q]); b[q] += av[k + q]; }
             *(ovec*)(dk + k) = a;

@@ -152,6 +152,8 @@ struct Ops {
             if (rc) return rc;
             rc = launch(bwd_cols_kernel<E, D>, dim3(p.BH * ((p.N + 255) / 256)), 256, s, po);
             if (rc) return rc;
+            rc = launch(bwd_hot_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
+            if (rc) return rc;
         }
         return EA_OK;
     }
