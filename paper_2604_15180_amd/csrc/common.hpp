@@ -9,7 +9,7 @@ constexpr int MAX_T = 2048;     // N <= 131072
 constexpr int MAX_W = 64;       // mask words per row
 // A row group's output comes from the gather kernel when its candidate lists average at most
 // GATHER_LIST_MAX entries per row and its supports at most GATHER_SUP_MAX keys per row.
-constexpr int GATHER_LIST_MAX = 96, GATHER_SUP_MAX = 32;
+constexpr int GATHER_LIST_MAX = 320, GATHER_SUP_MAX = 48;
 // Backward: support entries per lane list (two lists per row), entries per key in the lists by key,
 // and the non-zeros per marked 64 x 64 tile up to which a row group takes the gather path.
 constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 64, BWD_ENTRIES_PER_TILE = 16, BWD_ENTRIES_PER_ROW = 4, BWD_FEW_TILES = 16;
