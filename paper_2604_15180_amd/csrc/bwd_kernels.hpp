@@ -650,8 +650,9 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     // measured break-even: about 16 entries per tile at D = 128, 4 at D = 64; the power functions
     // of general alpha weigh on every entry)
     constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
+    constexpr int PER_ROW_X128 = BWD_ENTRIES_PER_ROW * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
     const int budget = max(PER_TILE_X128 * gsum[1] / 128,
-                           gsum[1] <= BWD_FEW_TILES ? BWD_ENTRIES_PER_ROW * min(BR, N - (int)((long)I * BR)) : 0);
+                           gsum[1] <= BWD_FEW_TILES ? PER_ROW_X128 * min(BR, N - (int)((long)I * BR)) / 128 : 0);
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
