@@ -245,7 +245,8 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
     p.scnt = (int32_t*)(ws + L.scnt);
     p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
-    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, (unsigned int*)nullptr);
+    p.scal = (unsigned int*)(ws + L.stats + STATS_BYTES);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
     if (per_head == 2) {
         p.hc_table = (const HeadConsts*)(ws + L.hc);

@@ -57,6 +57,7 @@ struct Params {
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
     // scal[0] = max |dO| (the backward uses dO divided by it)
+    // scal[1] = forward: number of row groups left to out_kernel (a plain counter)
     unsigned int* scal;
     int BH, N, T, W;
     int causal;

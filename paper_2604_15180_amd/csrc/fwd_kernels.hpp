@@ -784,7 +784,10 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     }
     __syncthreads();
     const bool gather = sparse && gsum[1] <= GATHER_SUP_MAX * nrows;
-    if (p.gflag && tid == 0) p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = gather;
+    if (p.gflag && tid == 0) {
+        p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = gather;
+        if (!gather) atomicAdd(&p.scal[1], 1u);       // a row group out_kernel will have to serve
+    }
     if (gather) {
         if (active && h == 0 && p.iters) {
 #pragma unroll

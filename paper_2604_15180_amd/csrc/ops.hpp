@@ -55,13 +55,6 @@ struct Ops {
     static int fwd(Params p, hipStream_t s) {
         int rc;
         {
-            ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
-            if (COPY) {
-                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr, nullptr, s);
-                if (rc) return rc;
-            }
-        }
-        {
             ScopedKernelTime t(EA_TIMER_TAU, s);
             // one dense sweep that lists each row's candidate scores, then histogram, solve and
             // refinement on the lists
@@ -78,6 +71,16 @@ struct Ops {
             else
                 rc = launch(tau_kernel<E, D, 1, AM, NBINS, NW_TAU, NBUF_TAU>, groups(p, NW_TAU), NW_TAU * 64, s, p);
             if (rc) return rc;
+        }
+        {
+            // the fp16 copy of V is for out_kernel: not made when every row group goes by gather
+            // (scal[1] counts the row groups that do not)
+            ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
+            if (COPY) {
+                rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr,
+                                           p.gflag ? (const int32_t*)(p.scal + 1) : nullptr, s);
+                if (rc) return rc;
+            }
         }
         ScopedKernelTime t(EA_TIMER_OUT, s);
         // sparse row groups: a gather over each row's support; all others: block-sparse matrix products
