@@ -582,11 +582,12 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 //                     row's tau goes, with its key index, to a list private to the lane that
 //                     computed it (two lists per row, as in tau_list_kernel).  A group whose
 //                     lists stay short is flagged; dq_kernel and dkdv_kernel skip flagged groups.
-//   bwd_rows_kernel : per row, over its listed support: dP_j = <dO_r, V_j>, delta, dS_j, and
+//   bwd_rows_kernel : per row, over its listed support: dP_j = <dO_r, V_j>, delta, and
 //                     dQ_r = sum_j dS_j K_j / sqrt(d) (Alg. 3, row by row); every entry is also
-//                     filed under its key: (row, dS, P).
-//   bwd_cols_kernel : per key, over the entries filed under it: dK_j += sum dS Q_r / sqrt(d),
-//                     dV_j += sum P dO_r (Alg. 2, column by column), added to what dkdv_kernel
+//                     filed under its key: (row, u dP, u, P).
+//   bwd_cols_kernel : per key, over the entries filed under it, with dS = u dP - u delta_row:
+//                     dK_j += sum dS Q_r / sqrt(d), dV_j += sum P dO_r (Alg. 2, column by
+//                     column), added to what dkdv_kernel
 //                     stored for the other row groups (or, when none was left to it, written as
 //                     dK_j, dV_j themselves).
 //   bwd_hot_kernel  : the entries of keys with more entries than a key's list holds, added to
@@ -785,23 +786,33 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
         float g[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) g[k] = (float)gv[k];
-        // first pass: delta = sum u dP / sum u, and the two sums dQ is made of:
-        //   dQ sqrt(d) = sum_j u_j (dP_j - delta) K_j = XA - delta XB
+        // One pass over the entries, four at a time so that their chains of dependent memory
+        // operations (entry, rows of V and K, slot in the key's list) overlap:
+        //   delta = sum u dP / sum u, and the two sums dQ is made of:
+        //   dQ sqrt(d) = sum_j u_j (dP_j - delta) K_j = XA - delta XB;
+        // every entry is filed under its key as (row, u dP, u, P): dS = u dP - u delta is formed
+        // by bwd_cols_kernel, which reads the row's delta once this kernel has stored it.  An
+        // entry whose key's list is full is marked (top bit of its key index) and left to
+        // bwd_hot_kernel, which adds it to dK, dV atomically once bwd_cols_kernel has stored them.
         float xa[EPT], xb[EPT], num = 0.f, den = 0.f;
+        int ndefer = 0;
 #pragma unroll
         for (int k = 0; k < EPT; ++k) { xa[k] = 0.f; xb[k] = 0.f; }
         for (int i0 = 0; i0 < tot; i0 += 4) {
             uint2 e[4];
             vvec vv[4], kv[4];
+            int slot[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { vv[u][k] = (elem)0.f; kv[u][k] = (elem)0.f; }
+                slot[u] = 0;
                 if (i0 + u < tot) {
                     vv[u] = *(const vvec*)(Vh + (long)e[u].y * D);
                     kv[u] = *(const vvec*)(Kh + (long)e[u].y * D);
+                    if (sub == 0) slot[u] = atomicAdd(&p.kcnt[(long)bh * N + e[u].y], 1);
                 }
             }
 #pragma unroll
@@ -811,11 +822,26 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
                 for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[u][k], dot);
                 const float dP = group_sum<16>(dot);
                 const float y = fmaf(c, __uint_as_float(e[u].x), -tau);
-                const float uu = (i0 + u < tot && y > 0.f) ? pow_r1<AM>(y, r) : 0.f;
+                const bool in = i0 + u < tot && y > 0.f;
+                const float uu = in ? pow_r1<AM>(y, r) : 0.f;
+                const float pr = in ? pow_r<AM>(y, r) : 0.f;
                 const float t = uu * dP;
                 num += t; den += uu;
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { xa[k] = fmaf(t, (float)kv[u][k], xa[k]); xb[k] = fmaf(uu, (float)kv[u][k], xb[k]); }
+                const int sl = __shfl(slot[u], (tid & 63) & ~15);
+                if (i0 + u < tot) {
+                    if (sl < KEY_LIST_CAP) {
+                        if (sub == 0)
+                            ((uint4*)p.klist)[((long)bh * N + e[u].y) * KEY_LIST_CAP + sl] =
+                                make_uint4((uint32_t)row, __float_as_uint(t), __float_as_uint(uu), __float_as_uint(pr));
+                    } else {
+                        const int i = i0 + u;
+                        if (sub == 0)
+                            *(uint32_t*)(const_cast<char*>(l0) + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8) + 4) = e[u].y | 0x80000000u;
+                        ++ndefer;
+                    }
+                }
             }
         }
         const float delta = den > 0.f ? num / den : 0.f;
@@ -829,53 +855,6 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
         if (sub == 0) {
             p.delta[gi] = -delta / amax;
             p.ntau[gi] = -tau / hc.rho;
-        }
-        // second pass: every entry filed under its key; four at a time, so that their chains of
-        // dependent memory operations (entry, row of V, slot in the key's list) overlap.  An entry
-        // whose key's list is full is marked (top bit of its key index) and left to bwd_hot_kernel,
-        // which adds it to dK, dV atomically once bwd_cols_kernel has stored those rows.
-        int ndefer = 0;
-        for (int i0 = 0; i0 < tot; i0 += 4) {
-            uint2 e[4];
-            vvec vv[4];
-            float dS[4], pr[4];
-            int slot[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-#pragma unroll
-                for (int k = 0; k < EPT; ++k) vv[u][k] = (elem)0.f;
-                if (i0 + u < tot) vv[u] = *(const vvec*)(Vh + (long)e[u].y * D);
-                slot[u] = 0;
-                if (i0 + u < tot && sub == 0) slot[u] = atomicAdd(&p.kcnt[(long)bh * N + e[u].y], 1);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float dot = 0.f;
-#pragma unroll
-                for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[u][k], dot);
-                const float dP = group_sum<16>(dot);
-                const float y = fmaf(c, __uint_as_float(e[u].x), -tau);
-                const float uu = y > 0.f ? pow_r1<AM>(y, r) : 0.f;
-                pr[u] = y > 0.f ? pow_r<AM>(y, r) : 0.f;
-                dS[u] = uu * (dP - delta);
-                slot[u] = __shfl(slot[u], (tid & 63) & ~15);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (i0 + u >= tot) continue;
-                const long kj = (long)bh * N + e[u].y;
-                if (slot[u] < KEY_LIST_CAP) {
-                    if (sub == 0)
-                        ((uint4*)p.klist)[kj * KEY_LIST_CAP + slot[u]] = make_uint4((uint32_t)row, __float_as_uint(dS[u]), __float_as_uint(pr[u]), 0u);
-                } else {
-                    const int i = i0 + u;
-                    if (sub == 0)
-                        *(uint32_t*)(const_cast<char*>(l0) + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8) + 4) = e[u].y | 0x80000000u;
-                    ++ndefer;
-                }
-            }
         }
         if (sub == 0) p.defer[gi] = ndefer;
     }
@@ -942,7 +921,7 @@ __global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
 // Sixteen lanes per key.  Where dkdv_kernel has stored dK, dV for the other row groups, the key's
 // rows are read, added to, and written back; when no row group was left to dkdv_kernel (it then
 // stores nothing) the sums are the rows, and keys without entries get zeros.
-template <class E, int D>
+template <class E, int D, bool SCALED>
 __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     using elem = typename E::elem;
     constexpr int EPT = D / 16;
@@ -957,6 +936,11 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     const elem* Gh = (const elem*)p.dO + hoff + sub * EPT;
     const int key_end = min(N, (I + 1) * 256);
     const bool fresh = *p.nplain == 0;
+    float amax = 1.f;                        // the stored deltas are in units of max|dO| (see bwd_rows_kernel)
+    if constexpr (SCALED) {
+        amax = __uint_as_float(p.scal[0]);
+        if (!(amax > 0.f)) amax = 1.f;
+    }
     for (int key = I * 256 + rsel; key < key_end; key += 16) {
         const long kj = (long)bh * N + key;
         const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
@@ -968,20 +952,24 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
         for (int i0 = 0; i0 < cnt; i0 += 4) {
             uint4 e[4];
             vvec qv[4], gv[4];
+            float nd[4];                     // -delta / max|dO| of the entry's row
 #pragma unroll
             for (int u = 0; u < 4; ++u) e[u] = i0 + u < cnt ? el[i0 + u] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { qv[u][k] = (elem)0.f; gv[u][k] = (elem)0.f; }
+                nd[u] = 0.f;
                 if (i0 + u < cnt) {
                     qv[u] = *(const vvec*)(Qh + (long)e[u].x * D);
                     gv[u] = *(const vvec*)(Gh + (long)e[u].x * D);
+                    nd[u] = p.delta[(long)bh * N + e[u].x];
                 }
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const float dS = __uint_as_float(e[u].y), pr = __uint_as_float(e[u].z);     // zero past the end
+                // dS = u dP - u delta; P (all zero past the end)
+                const float dS = fmaf(__uint_as_float(e[u].z), nd[u] * amax, __uint_as_float(e[u].y)), pr = __uint_as_float(e[u].w);
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { ak[k] = fmaf(dS, (float)qv[u][k], ak[k]); av[k] = fmaf(pr, (float)gv[u][k], av[k]); }
             }

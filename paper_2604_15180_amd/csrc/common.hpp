@@ -52,7 +52,7 @@ struct Params {
     int32_t* nplain;      // backward: number of row groups that stay with dq_kernel / dkdv_kernel
     int32_t* nmarked;     // backward: set bits of the whole mask
     int32_t* defer;       // backward [BH][N]: entries of the row left to bwd_hot_kernel
-    void* klist;          // backward [BH][N][KEY_LIST_CAP]: (query row, dS, P, -), 16 bytes each
+    void* klist;          // backward [BH][N][KEY_LIST_CAP]: (query row, u dP, u, P), 16 bytes each
     int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):

@@ -153,7 +153,7 @@ struct Ops {
             ScopedKernelTime t(EA_TIMER_BWD_GATHER, s);
             rc = launch(bwd_rows_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
             if (rc) return rc;
-            rc = launch(bwd_cols_kernel<E, D>, dim3(p.BH * ((p.N + 255) / 256)), 256, s, po);
+            rc = launch(bwd_cols_kernel<E, D, E2::SCALED>, dim3(p.BH * ((p.N + 255) / 256)), 256, s, po);
             if (rc) return rc;
             rc = launch(bwd_hot_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
             if (rc) return rc;
