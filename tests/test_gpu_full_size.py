@@ -29,9 +29,21 @@ def test_c3_full_size_sampled_heads(ea, sigma):
     print(f"case c3 full size sigma={sigma}", flush=True)
     q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sigma, seed=3000 + int(sigma))
     Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
-    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
-    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask)
+    wf = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=wf)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=wb)
     torch.cuda.synchronize()
+    # which path served the rows, as in the launch configuration bench.py times: at sigma = 4 every
+    # row group goes by gather in both passes, at sigma = 1 the backward is split between the gather
+    # and the matrix kernels
+    sf, sb = ea.read_stats(wf), ea.read_stats(wb)
+    print("  rows by gather: forward", sf["gather_rows"], "backward", sb["bwd_gather_rows"], "of", B * H * N, flush=True)
+    if sigma == 4.0:
+        assert sf["gather_rows"] == B * H * N and sb["bwd_gather_rows"] == B * H * N
+    else:
+        assert 0 < sb["bwd_gather_rows"] < B * H * N and sb["dq_subtiles"] > 0
+    del wf, wb
     # properties over all heads
     assert torch.isfinite(O).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all() and torch.isfinite(dV).all()
     # rows of P sum to one  ->  sum_j dV_j = sum_r dO_r   (per head and channel)
