@@ -1109,8 +1109,8 @@ static __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsig
     if (scal && threadIdx.x < 4) scal[threadIdx.x] = 0u;
 }
 
-// max |x| over a tensor -> atomicMax on the float's bit pattern (non-negative floats order as
-// unsigned ints); n is a multiple of 8.  One atomic per block: thousands of them on one word
+// max |x| over a tensor, rounded up to a power of two -> atomicMax on the float's bit pattern
+// (non-negative floats order as unsigned ints); n is a multiple of 8.  One atomic per block: thousands of them on one word
 // would take longer than reading the tensor.
 template <class E>
 __global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, long n, unsigned int* out_bits, const int32_t* needed) {
@@ -1138,7 +1138,14 @@ __global__ __launch_bounds__(256) void amax_kernel(const typename E::elem* x, lo
     m = wave_max(m);
     if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0) atomicMax(out_bits, __float_as_uint(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3]))));
+    if (threadIdx.x == 0) {
+        // rounded up to a power of two: dividing by it is exact, so the fp16 copy of dO / max|dO|
+        // holds the caller's bf16 values exactly (a scale with mantissa bits would round every
+        // element, and dP - delta, a difference of nearly equal sums, multiplies that rounding)
+        unsigned int bits = __float_as_uint(fmaxf(fmaxf(part[0], part[1]), fmaxf(part[2], part[3])));
+        if ((bits & 0x007fffffu) && bits < 0x7f000000u) bits = (bits & 0x7f800000u) + 0x00800000u;
+        atomicMax(out_bits, bits);
+    }
 }
 
 }  // namespace ea
