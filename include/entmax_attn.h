@@ -182,7 +182,7 @@ enum {
     EA_TIMER_TAU = 1,       /* dense sweep (maximum, histogram, candidate lists), solve, refinement; fallback kernel */
     EA_TIMER_OUT = 2,       /* phase 4 and the rest of the refinement */
     EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
-    EA_TIMER_BWD_PREP = 4,  /* max |dO| and the fp16 copies of K, Q, V, dO (bf16 inputs) */
+    EA_TIMER_BWD_PREP = 4,  /* max |dO| (rounded up to a power of two) and the fp16 copies of K, Q, V, dO (bf16 inputs) */
     EA_TIMER_DQ = 5,        /* delta and dQ, one sweep */
     EA_TIMER_DKDV = 6,      /* dK, dV */
     EA_TIMER_DECODE_SCORES = 7, /* entmax_attn_decode: the kernel that reads K and keeps the logits near the maximum */

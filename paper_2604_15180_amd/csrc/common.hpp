@@ -56,7 +56,7 @@ struct Params {
     int32_t* oflag;       // [BH][T] 1 = some row of this 64-row block has more candidates than its lists hold
     unsigned long long* stats;
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
-    // scal[0] = max |dO| (the backward uses dO divided by it)
+    // scal[0] = max |dO| rounded up to a power of two (the backward uses dO divided by it: exact)
     // scal[1] = forward: number of row groups left to out_kernel (a plain counter)
     unsigned int* scal;
     int BH, N, T, W;
