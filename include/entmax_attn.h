@@ -178,16 +178,16 @@ int entmax_attn_last_hip_error(void);
  */
 #define EA_TIMER_SLOTS 10
 enum {
-    EA_TIMER_FWD_PREP = 0,  /* fp16 copy of V (bf16 inputs) */
+    EA_TIMER_FWD_PREP = 0,  /* fp16 copy of V (bf16 inputs; made after the threshold kernel, and only if some row group needs it) */
     EA_TIMER_TAU = 1,       /* dense sweep (maximum, histogram, candidate lists), solve, refinement; fallback kernel */
-    EA_TIMER_OUT = 2,       /* phase 4 and the rest of the refinement */
+    EA_TIMER_OUT = 2,       /* phase 4 (gather over listed supports, block-sparse matrix products) and the rest of the refinement */
     EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
     EA_TIMER_BWD_PREP = 4,  /* max |dO| (rounded up to a power of two) and the fp16 copies of K, Q, V, dO (bf16 inputs) */
     EA_TIMER_DQ = 5,        /* delta and dQ, one sweep */
     EA_TIMER_DKDV = 6,      /* dK, dV */
     EA_TIMER_DECODE_SCORES = 7, /* entmax_attn_decode: the kernel that reads K and keeps the logits near the maximum */
     EA_TIMER_BWD_LIST = 8,  /* backward: supports of the sparse row groups listed (one matrix product per marked tile) */
-    EA_TIMER_BWD_GATHER = 9 /* backward of the sparse row groups from their lists: rows (dQ, delta), then keys (dK, dV) */
+    EA_TIMER_BWD_GATHER = 9 /* backward of the sparse row groups from their lists: rows (dQ, delta), then keys (dK, dV), then the entries of overfull keys */
 };
 int entmax_attn_timer_enable(int on);
 int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);
