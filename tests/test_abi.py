@@ -53,6 +53,19 @@ def test_workspace_query(L):
     assert f(1, 1, 256, 64, "int8", True, False) == 0
 
 
+def test_gather_switch_and_its_workspace(L):
+    # the switch is a host-side flag (no GPU call); the backward's workspace holds the support
+    # lists, two per row, and the lists by key, whichever way the switch stands
+    assert L.entmax_attn_gather_enable(0) == 0
+    assert L.entmax_attn_gather_enable(1) == 0
+    B, H, N, d = 1, 2, 4096, 128
+    rows = B * H * N
+    bwd = ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", True, True)
+    assert bwd > 4 * rows * d * 2 + rows * 2 * 64 * 8 + rows * 64 * 16      # fp16 copies + both kinds of lists
+    fwd = ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", True, False)
+    assert fwd > rows * 2 * 256 * 8                                         # candidate lists
+
+
 def call_fwd(L, ptrs, B=1, H=1, N=64, d=64, dtype=1, alpha=1.5, ws=0x1000, ws_bytes=1 << 30):
     vp = ctypes.c_void_p
     q, k, v, o, tau, m = (vp(x) for x in ptrs)
