@@ -605,7 +605,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     __shared__ __align__(1024) char set0[KT::BYTES];
     __shared__ __align__(1024) char set1[KT::BYTES];
     __shared__ uint32_t fm[MR * MAX_W];
-    __shared__ int tl[MAX_T];
+    __shared__ unsigned short tl[MAX_T];
     __shared__ int tl_count[4];
     __shared__ int gsum[4];                  // [0] support entries so far, [1] marked tiles, [2] gave up
     __shared__ unsigned long long blk_stats[4];
@@ -674,7 +674,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     auto compute = [&](int it, const char* buf) {
         const int j = tl[it];
         if (!active || !mask_bit(fm, W, myrow, j)) return;
-        stage1<E, D, QB>(C, buf, qf, lane);
+        stage1<E, D, QB, EA_FENCE, 2>(C, buf, qf, lane);    // fragments of two k-steps at a time: four waves per SIMD fit
         if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
         ++ntile;
         const int key0 = j * 64 + 8 * h;

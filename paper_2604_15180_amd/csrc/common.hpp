@@ -216,7 +216,8 @@ EA_DEV void flush_counters(unsigned long long* blk, unsigned long long* stats, c
 // Union of `rows` mask rows (LDS, `W` words each) -> ascending list of tile indices in LDS.
 // Called by all threads; the first wave does the work.  Uses one wave-wide exclusive scan of
 // the per-word popcounts (W <= 64).
-EA_DEV void build_tile_list(const uint32_t* words, int rows, int W, int* list, int* count, int tid) {
+template <class ListT>
+EA_DEV void build_tile_list(const uint32_t* words, int rows, int W, ListT* list, int* count, int tid) {
     __syncthreads();
     if (tid < 64) {
         uint32_t u = 0;
@@ -233,7 +234,7 @@ EA_DEV void build_tile_list(const uint32_t* words, int rows, int W, int* list, i
         while (u) {
             const int b = __ffs(u) - 1;
             u &= u - 1;
-            list[pos++] = tid * 32 + b;
+            list[pos++] = (ListT)(tid * 32 + b);
         }
         if (tid == 63) *count = incl;
     }

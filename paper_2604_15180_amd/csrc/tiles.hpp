@@ -200,7 +200,7 @@ EA_DEV void load_owned(Owned<E, D, QB>& o, const typename E::elem* g, long row0,
 #ifndef EA_FENCE
 #define EA_FENCE true
 #endif
-template <class E, int D, int QB, bool FENCE = EA_FENCE>
+template <class E, int D, int QB, bool FENCE = EA_FENCE, int PFMAX = 8>
 EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, QB>& own, int lane) {
     using L = RowTile<E, D>;
     constexpr int ES = (int)sizeof(typename E::elem);
@@ -220,7 +220,7 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
         // then start as the first fragments land, with the rest of the LDS latency behind them
         // (left alone, the compiler waits for each pair of reads right before its two MFMAs).
         constexpr int NS = D / E::KSTEP;
-        constexpr int PF = NS < 8 ? NS : 8;
+        constexpr int PF = NS < PFMAX ? NS : PFMAX;
         typename E::frag a0[PF], a1[PF];
 #pragma unroll
         for (int s0 = 0; s0 < NS; s0 += PF) {
