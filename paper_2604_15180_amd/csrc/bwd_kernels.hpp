@@ -754,7 +754,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
 template <class E, int D, int AM, bool SCALED>
 __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
     using elem = typename E::elem;
-    constexpr int EPT = D / 16;
+    constexpr int EPT = D / 16, CH = 2;      // entries in flight per lane group
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
         float g[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) g[k] = (float)gv[k];
-        // One pass over the entries, four at a time so that their chains of dependent memory
+        // One pass over the entries, CH at a time so that their chains of dependent memory
         // operations (entry, rows of V and K, slot in the key's list) overlap:
         //   delta = sum u dP / sum u, and the two sums dQ is made of:
         //   dQ sqrt(d) = sum_j u_j (dP_j - delta) K_j = XA - delta XB;
@@ -798,14 +798,14 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
         int ndefer = 0;
 #pragma unroll
         for (int k = 0; k < EPT; ++k) { xa[k] = 0.f; xb[k] = 0.f; }
-        for (int i0 = 0; i0 < tot; i0 += 4) {
-            uint2 e[4];
-            vvec vv[4], kv[4];
-            int slot[4];
+        for (int i0 = 0; i0 < tot; i0 += CH) {
+            uint2 e[CH];
+            vvec vv[CH], kv[CH];
+            int slot[CH];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
+            for (int u = 0; u < CH; ++u) e[u] = i0 + u < tot ? entry(i0 + u) : make_uint2(0u, 0u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CH; ++u) {
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { vv[u][k] = (elem)0.f; kv[u][k] = (elem)0.f; }
                 slot[u] = 0;
@@ -816,7 +816,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CH; ++u) {
                 float dot = 0.f;
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) dot = fmaf(g[k], (float)vv[u][k], dot);
@@ -924,7 +924,7 @@ __global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
 template <class E, int D, bool SCALED>
 __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     using elem = typename E::elem;
-    constexpr int EPT = D / 16;
+    constexpr int EPT = D / 16, CH = 4;      // entries in flight per lane group
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
@@ -949,14 +949,14 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
         float ak[EPT], av[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) { ak[k] = 0.f; av[k] = 0.f; }
-        for (int i0 = 0; i0 < cnt; i0 += 4) {
-            uint4 e[4];
-            vvec qv[4], gv[4];
-            float nd[4];                     // -delta / max|dO| of the entry's row
+        for (int i0 = 0; i0 < cnt; i0 += CH) {
+            uint4 e[CH];
+            vvec qv[CH], gv[CH];
+            float nd[CH];                     // -delta / max|dO| of the entry's row
 #pragma unroll
-            for (int u = 0; u < 4; ++u) e[u] = i0 + u < cnt ? el[i0 + u] : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < CH; ++u) e[u] = i0 + u < cnt ? el[i0 + u] : make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CH; ++u) {
 #pragma unroll
                 for (int k = 0; k < EPT; ++k) { qv[u][k] = (elem)0.f; gv[u][k] = (elem)0.f; }
                 nd[u] = 0.f;
@@ -967,7 +967,7 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CH; ++u) {
                 // dS = u dP - u delta; P (all zero past the end)
                 const float dS = fmaf(__uint_as_float(e[u].z), nd[u] * amax, __uint_as_float(e[u].y)), pr = __uint_as_float(e[u].w);
 #pragma unroll
