@@ -443,15 +443,21 @@ EA_DEV float histogram_edge_bound(const uint32_t* H, int rot, int shift, float h
 // A list that fills up (attention close to uniform: hundreds of non-zeros per row) flags its 64-row
 // block; flagged blocks are redone by the sweep-based tau_kernel, which runs right after and exits
 // at once everywhere else.
-template <class E, int D, int QB, int AM, int NB, int NW, int NBUF>
-__global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
+// PAIR (one row per lane only): waves 2w and 2w+1 share the words of one histogram buffer, 16 bits
+// each - what two rows per lane do within a wave - so that eight one-row waves need the LDS of
+// four and, with half the accumulator and operand registers, four waves fit a SIMD.
+template <class E, int D, int QB, int AM, int NB, int NW, int NBUF, int PAIR = 0>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 4 : 1))) void tau_list_kernel(Params p) {
+    static_assert(!PAIR || (QB == 1 && NW % 2 == 0), "paired histograms: one row per lane, an even number of waves");
     using SM = TauSmem<E, D, QB, NB, NW, NBUF>;
     using KT = RowTile<E, D>;
     using elem = typename E::elem;
     constexpr int THREADS = NW * 64, BR = SM::BR, MR = SM::MR, SLOTS = SM::SLOTS;
     constexpr int GROW = 24;              // list growth (entries per lane) between two histogram solves
     __shared__ __align__(1024) char kring[NBUF * KT::BYTES];
-    __shared__ __align__(256) uint32_t hist[SM::HIST_WORDS];
+    constexpr int HIST_WORDS = PAIR ? SM::HIST_WORDS / 2 : SM::HIST_WORDS;
+    constexpr int CB = PAIR ? 16 : SM::CBITS;            // bits per counter
+    __shared__ __align__(256) uint32_t hist[HIST_WORDS];
     __shared__ float pw[AM == ALPHA_GEN ? SLOTS : 1];             // (m h)^r, general alpha only
     // used only once the sweep is over: they live in the key-tile ring
     static_assert(2 * MR * MAX_W * 4 + MR * 4 + 96 <= NBUF * KT::BYTES, "post-sweep arrays must fit in the ring");
@@ -479,7 +485,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
 
     Owned<E, D, QB> qf;
     load_owned<E, D, QB>(qf, Qh, active ? qw0 : 0, lane);
-    for (int i = tid; i < SM::HIST_WORDS; i += THREADS) hist[i] = 0u;
+    for (int i = tid; i < HIST_WORDS; i += THREADS) hist[i] = 0u;
     if constexpr (AM == ALPHA_GEN) {
         if (tid < SLOTS) pw[tid] = tid == 0 ? 0.f : pow_r<AM>((float)tid * (1.f / NB), r);
     }
@@ -497,7 +503,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
         run[qb] = -INFINITY; lowraw[qb] = -3.0e38f;
         k4[qb] = 0.f; bottom4[qb] = 0; a_top[qb] = INT_MIN;
     }
-    char* const hrow = (char*)(hist + (wave * 32 + n) * SLOTS);
+    const int hwave = PAIR ? (wave >> 1) : wave;         // whose buffer, and which half of its words
+    auto hshift = [&](int qb) { return PAIR ? 16 * (wave & 1) : (CB * qb & 31); };
+    char* const hrow = (char*)(hist + (hwave * 32 + n) * SLOTS);
 
     // Root of the row's histogram (Eq. 9) as it stands: lane (n, h) solves row block qb = h of row n
     // (with one row per lane, both lanes solve the same), then the two lanes of a row swap.  Returns
@@ -514,9 +522,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
         const float origin = (float)a_lo * hb;                        // left edge of the window
         float tau_h;
         if (AM == ALPHA_GEN && coarse)
-            tau_h = histogram_edge_bound<SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1), SM::CBITS * sq & 31, hb, pw) + origin;
+            tau_h = histogram_edge_bound<SLOTS, CB>((const uint32_t*)hrow, a_lo & (SLOTS - 1), hshift(sq), hb, pw) + origin;
         else
-            tau_h = solve_histogram<AM, SLOTS, SM::CBITS>((const uint32_t*)hrow, a_lo & (SLOTS - 1), SM::CBITS * sq & 31, hb, r) + origin;
+            tau_h = solve_histogram<AM, SLOTS, CB>((const uint32_t*)hrow, a_lo & (SLOTS - 1), hshift(sq), hb, r) + origin;
         const float slack = 1e-6f + 2.5e-7f * fabsf(origin);          // fp32 rounding of bins and closed form
         const float my_lo = fmaxf(tau_h - slack, fmaf(c, mx, -1.f)), my_up = tau_h + hb + slack;
         const float o_lo = xhalf_other(my_lo, h), o_up = xhalf_other(my_up, h);
@@ -533,7 +541,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
     const float inv_c = 1.f / c, cb = c * NB, c4 = 4.f * cb;
     auto sweep_tile = [&](int j, const char* buf) {
             if (j >= wjt) return;
-            stage1<E, D, QB>(C, buf, qf, lane);
+            stage1<E, D, QB, EA_FENCE, PAIR ? 2 : 8>(C, buf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
             // per row block: maxima of the four groups of 8 registers, of the lane, of the row
@@ -579,9 +587,9 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                         const int f0 = __builtin_amdgcn_readlane(first, src);
                         const int ncl = __builtin_amdgcn_readlane(last - first, src);
                         if (((lane - f0) & (SLOTS - 1)) <= ncl) {
-                            uint32_t* word = hist + (wave * 32 + src) * SLOTS + lane;
-                            if constexpr (QB == 1) *word = 0u;
-                            else lds_and_b32(word, qb == 0 ? 0xffff0000u : 0x0000ffffu);
+                            uint32_t* word = hist + (hwave * 32 + src) * SLOTS + lane;
+                            if constexpr (QB == 1 && !PAIR) *word = 0u;
+                            else lds_and_b32(word, hshift(qb) == 0 ? 0xffff0000u : 0x0000ffffu);
                         }
                     }
                 }
@@ -612,7 +620,7 @@ __global__ __launch_bounds__(NW * 64) void tau_list_kernel(Params p) {
                             // slot of the score's bin, times 4 (a score that rounding puts a hair
                             // below the window goes to its lowest bin)
                             const int rel = max((int)fmaf(c4, sc, k4[qb]), bottom4[qb]);
-                            lds_add_u32(hrow + (rel & (4 * SLOTS - 4)), 1u << (SM::CBITS * qb & 31));
+                            lds_add_u32(hrow + (rel & (4 * SLOTS - 4)), 1u << hshift(qb));
                             // a full list keeps overwriting its last entry (its block is redone anyway)
                             uint2 ent;          // tile row of register v of group g: see causal_hide
                             ent.x = __float_as_uint(sc); ent.y = (uint32_t)(key0 + 32 * (g >> 1) + 16 * (g & 1) + v);

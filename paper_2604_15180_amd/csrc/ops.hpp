@@ -15,6 +15,10 @@ constexpr int NW_TAU = 4, NBUF_TAU = 2, QB_TAU = 2;
 // list-based threshold kernel: 8 waves (512 rows with two rows per lane), one group per CU, a ring
 // of 4 key tiles so that a tile has three tile times to arrive
 constexpr int NW_TAUL = 4, NBUF_TAUL = 3;
+// 16-bit inputs, alpha 1.5 or 2: the list kernel runs as 8 waves x 32 rows with the histograms of
+// two waves sharing words (four waves per SIMD: 3.3 / 2.0 / 1.7 / 1.6 -> 3.2 / 1.7 / 1.5 / 1.5 ms over
+// the benchmark's sigma sweep against 4 waves x 64 rows at two per SIMD)
+constexpr bool TAUL_PAIRED = true;
 constexpr int NW_OUT = 4, NBUF_OUT = 2;
 constexpr int NW_DQ = 2, NBUF_DQ = 2;
 constexpr int NW_DKDV = 2, NBUF_DKDV = 2;
@@ -62,6 +66,12 @@ struct Ops {
             constexpr int NBL = (E::EPL == 8) ? NBUF_TAUL : 2;       // fp32 tiles are twice as large
             static_assert((32 * QBL * NW_TAUL) % (32 * QB * NW_OUT) == 0, "an output group lies inside one row group of the list kernel");
             p.grows = 32 * QBL * NW_TAUL;
+            if constexpr (E::EPL == 8 && TAUL_PAIRED && AM != ALPHA_GEN) {
+                // eight one-row waves, paired histograms, two tile buffers: four waves per SIMD
+                // (general alpha, with its table of powers and heavier solves, measured slower so)
+                p.grows = 32 * 8;
+                rc = launch(tau_list_kernel<E, D, 1, AM, NBINS, 8, 2, 1>, groups(p, 8, 1), 8 * 64, s, p);
+            } else
             rc = launch(tau_list_kernel<E, D, QBL, AM, NBINS, NW_TAUL, NBL>, groups(p, NW_TAUL, QBL), NW_TAUL * 64, s, p);
             if (rc) return rc;
             // sweep-based fallback for row blocks whose lists overflowed (exits at once elsewhere);
