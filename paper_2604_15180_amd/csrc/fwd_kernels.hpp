@@ -541,7 +541,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
     const float inv_c = 1.f / c, cb = c * NB, c4 = 4.f * cb;
     auto sweep_tile = [&](int j, const char* buf) {
             if (j >= wjt) return;
-            stage1<E, D, QB, EA_FENCE, PAIR ? 2 : 8>(C, buf, qf, lane);
+            stage1<E, D, QB, EA_FENCE, PAIR ? 0 : 8>(C, buf, qf, lane);
             if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
             ++ntile_done;
             // per row block: maxima of the four groups of 8 registers, of the lane, of the row

@@ -200,6 +200,8 @@ EA_DEV void load_owned(Owned<E, D, QB>& o, const typename E::elem* g, long row0,
 #ifndef EA_FENCE
 #define EA_FENCE true
 #endif
+// PFMAX = 0: rolling - the fragments of k-step s+1 are requested before the MFMAs of k-step s, so
+// that their LDS latency passes behind those MFMAs (registers for two k-steps, as with PFMAX = 2).
 template <class E, int D, int QB, bool FENCE = EA_FENCE, int PFMAX = 8>
 EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, QB>& own, int lane) {
     using L = RowTile<E, D>;
@@ -220,7 +222,28 @@ EA_DEV void stage1(f32x16 (&C)[2][QB], const char* lds_tile, const Owned<E, D, Q
         // then start as the first fragments land, with the rest of the LDS latency behind them
         // (left alone, the compiler waits for each pair of reads right before its two MFMAs).
         constexpr int NS = D / E::KSTEP;
-        constexpr int PF = NS < PFMAX ? NS : PFMAX;
+        if constexpr (PFMAX == 0) {
+            typename E::frag a0[2], a1[2];
+            a0[0] = *(const typename E::frag*)(lds_tile + lane_off);
+            a1[0] = *(const typename E::frag*)(lds_tile + lane_off + 32 * L::ROW_BYTES);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (s + 1 < NS) {
+                    const char* a = lds_tile + (lane_off ^ ((s + 1) * 32));
+                    a0[(s + 1) & 1] = *(const typename E::frag*)a;
+                    a1[(s + 1) & 1] = *(const typename E::frag*)(a + 32 * L::ROW_BYTES);
+                }
+                if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb) {
+                    C[0][qb] = E::mma(a0[s & 1], own.f[qb][s], C[0][qb]);
+                    C[1][qb] = E::mma(a1[s & 1], own.f[qb][s], C[1][qb]);
+                }
+                if constexpr (FENCE) __builtin_amdgcn_sched_barrier(0);
+            }
+            return;
+        }
+        constexpr int PF = PFMAX == 0 ? 1 : (NS < PFMAX ? NS : PFMAX);
         typename E::frag a0[PF], a1[PF];
 #pragma unroll
         for (int s0 = 0; s0 < NS; s0 += PF) {
