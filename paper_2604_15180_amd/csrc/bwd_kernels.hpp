@@ -674,7 +674,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     auto compute = [&](int it, const char* buf) {
         const int j = tl[it];
         if (!active || !mask_bit(fm, W, myrow, j)) return;
-        stage1<E, D, QB, EA_FENCE, 2>(C, buf, qf, lane);    // fragments of two k-steps at a time: four waves per SIMD fit
+        stage1<E, D, QB, EA_FENCE, 0>(C, buf, qf, lane);    // rolling fragments (registers of two k-steps): four waves per SIMD fit
         if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
         ++ntile;
         const int key0 = j * 64 + 8 * h;
