@@ -66,6 +66,15 @@ def test_bf16_causal(ea, d, N, sigma):
     run_case(ea, 2, 2, N, d, "bf16", True, 1.5, sigma, seed=21)
 
 
+@pytest.mark.parametrize("N,causal,alpha,d", [(64, True, 1.5, 128), (192, True, 2.0, 64), (320, False, 1.5, 64),
+                                              (576, True, 2.0, 128)])
+def test_bf16_ragged_sizes(ea, N, causal, alpha, d):
+    # N not a multiple of the 256-row group of the threshold kernel for 16-bit inputs at alpha 1.5
+    # and 2: its last group runs with some of its eight waves (and of the wave pairs that share
+    # histogram words) idle; N = 64 is a single key tile
+    run_case(ea, 1, 2, N, d, "bf16", causal, alpha, 2.0, seed=300 + N)
+
+
 def test_bf16_noncausal(ea):
     run_case(ea, 1, 2, 384, 128, "bf16", False, 1.5, 1.5, seed=22)
 
