@@ -126,9 +126,9 @@ def attn_bwd(Q, K, V, dO, alpha, causal):
 
 
 def attn_decode(q, K, V, alpha):
-    """Inference variant on materialised logits (appendix on language modelling: "a simplified
-    variant that operates on fully materialized logits z in R^n"): one query row per head against
-    all N cached keys.  z = K q / sqrt(d), p = alpha-entmax(z) (Eq. 3), o = p V.
+    """Inference variant on materialised logits (the paper's appendix on language modelling runs
+    inference on the whole logit vector of one query): one query row per head against all N
+    cached keys.  z = K q / sqrt(d), p = alpha-entmax(z) (Eq. 3), o = p V.
 
     q: [B,H,d], K, V: [B,H,N,d].  Returns dict(O [B,H,d], tau [B,H] (raw convention:
     p = [(alpha-1) z - tau]_+^(1/(alpha-1))), P [B,H,N], z [B,H,N])."""

@@ -607,7 +607,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     __shared__ uint32_t fm[MR * MAX_W];
     __shared__ unsigned short tl[MAX_T];
     __shared__ int tl_count[4];
-    __shared__ int gsum[4];                  // [0] support entries so far, [1] marked tiles, [2] gave up
+    __shared__ int gsum[4];                  // [0] support entries so far, [1] marked tiles, [2] a list is full, [3] the group's decision to leave
     __shared__ unsigned long long blk_stats[4];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -709,8 +709,11 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
         }
         if (__any(full) && lane == 0) atomicOr(&gsum[2], 1);
     };
-    // the walk of stream_tiles, left as soon as the gather path cannot pay any more (every wave
-    // reads the counters right after the barrier: all leave together)
+    // the walk of stream_tiles, left as soon as the gather path cannot pay any more.  The counters
+    // keep moving while the waves of a group work on a tile, so the group's decision is taken by
+    // one thread, from the values it finds right after a barrier, and published in gsum[3]; every
+    // wave reads it after the NEXT barrier, before which nobody writes it again: all waves leave
+    // at the same tile, or none does.
     auto hopeless = [&](int it) {
         if (*(volatile int*)&gsum[2]) return true;
         const int e = *(volatile int*)&gsum[0];
@@ -721,19 +724,23 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     for (int it = 0; it < nt; it += 2) {
         wait_loads();
         __syncthreads();
-        if ((it & 7) == 0 && (gave_up = hopeless(it))) break;
+        if ((it & 7) == 0 && tid == 0) gsum[3] = hopeless(it);
         if (it + 1 < nt) issue(it + 1, set1);
         compute(it, set0);
         if (it + 1 >= nt) break;
         wait_loads();
         __syncthreads();
+        if ((it & 7) == 0 && *(volatile int*)&gsum[3]) { gave_up = true; break; }
         if (it + 2 < nt) issue(it + 2, set0);
         compute(it + 1, set1);
     }
+    lds_settle();            // this wave's counter updates have reached LDS
     wait_loads();
     __syncthreads();
+    if (tid == 0) gsum[3] = gave_up || hopeless(nt);
+    __syncthreads();
     const int nrows = min(BR, N - (int)q0);
-    const bool gather = !gave_up && !hopeless(nt);
+    const bool gather = !*(volatile int*)&gsum[3];
     if (active) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) p.scnt[((long)bh * N + qw0 + 32 * qb + n) * 2 + h] = gather ? cnt[qb] : 0;
