@@ -48,7 +48,8 @@ enum {
     EA_ERR_SHAPE = -3,      /* B, H <= 0, N not a positive multiple of 64 or > 131072, d not in {64, 128} */
     EA_ERR_DTYPE = -4,      /* unknown ea_dtype */
     EA_ERR_WORKSPACE = -5,  /* workspace NULL, misaligned or too small */
-    EA_ERR_HIP = -6         /* a HIP call failed; see entmax_attn_last_hip_error() */
+    EA_ERR_HIP = -6,        /* a HIP call failed; see entmax_attn_last_hip_error() */
+    EA_ERR_TOO_LARGE = -7   /* the problem needs more scratch than an allocation-free entry point holds */
 };
 
 /* The workspace starts with EA_STATS_COPIES copies of EA_STATS_WORDS 64-bit counters
@@ -160,6 +161,24 @@ int entmax_attn_decode(const void* q, const void* K, const void* V,
                        float* O, float* tau, int32_t* support, int32_t* iters,
                        int B, int H, int N, int d, ea_dtype dtype, float alpha,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * entmax_attn_decode for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
+ * kernels and results as entmax_attn_decode; the scratch (per-group maxima and counts, kept logits)
+ * is an array inside the library's code object, entmax_attn_decode_static_max_bytes() bytes
+ * (33 MiB) per GPU, held until the process ends; its device address is looked up on the first call
+ * on each device.  The call allocates and frees nothing and clears nothing (the kernels write every
+ * scratch word before they read it).
+ *   - EA_ERR_TOO_LARGE, nothing enqueued, when entmax_attn_decode_workspace_bytes(B, H, N, d, dtype)
+ *     exceeds entmax_attn_decode_static_max_bytes() (about B*H*N <= 4 Mi keys, e.g. 32 heads x 128k).
+ *   - All calls on one GPU share that GPU's array: calls that overlap on one GPU (different streams
+ *     without ordering, or several host threads) race.  Order them on one stream.
+ */
+size_t entmax_attn_decode_static_max_bytes(void);
+int entmax_attn_decode_static(const void* q, const void* K, const void* V,
+                              float* O, float* tau, int32_t* support, int32_t* iters,
+                              int B, int H, int N, int d, ea_dtype dtype, float alpha, void* hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char* entmax_attn_strerror(int code);

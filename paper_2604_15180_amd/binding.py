@@ -68,6 +68,10 @@ def lib():
         L.entmax_attn_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
         L.entmax_attn_decode.restype = ci
         L.entmax_attn_decode.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, vp, sz, vp]
+        L.entmax_attn_decode_static_max_bytes.restype = sz
+        L.entmax_attn_decode_static_max_bytes.argtypes = []
+        L.entmax_attn_decode_static.restype = ci
+        L.entmax_attn_decode_static.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, vp]
         L.entmax_attn_mfma_probe.restype = ci
         L.entmax_attn_mfma_probe.argtypes = [vp, vp, ci, ci, vp]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
@@ -193,21 +197,44 @@ def entmax_attn_decode_workspace_bytes(B, H, N, d, dtype):
     return int(lib().entmax_attn_decode_workspace_bytes(B, H, N, d, _dtype_code(dtype)))
 
 
-def entmax_attn_decode(q, K, V, alpha, workspace=None):
-    """One query per head against all cached keys: q [B,H,d], K, V [B,H,N,d] -> (O [B,H,d], tau [B,H],
-    support [B,H], iters [B,H])."""
+def entmax_attn_decode_static_max_bytes():
+    return int(lib().entmax_attn_decode_static_max_bytes())
+
+
+def entmax_attn_decode_static(q, K, V, alpha, out=None):
+    """entmax_attn_decode through the entry point that allocates nothing: the scratch is the
+    library's own static array.  `out` = (O, tau, support, iters) tensors to write into (then this
+    function allocates nothing either); without it they are made here with torch."""
+    B, H, N, d = _check_decode_args(q, K, V)
+    dev = K.device
+    O, tau, support, iters = out if out is not None else _decode_outputs(B, H, d, dev)
+    _check(lib().entmax_attn_decode_static(_ptr(q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(support), _ptr(iters),
+                                           B, H, N, d, _dtype_code(K.dtype), float(alpha),
+                                           ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)))
+    return O, tau, support, iters
+
+
+def _decode_outputs(B, H, d, dev):
+    return (torch.empty((B, H, d), dtype=torch.float32, device=dev), torch.empty((B, H), dtype=torch.float32, device=dev),
+            torch.empty((B, H), dtype=torch.int32, device=dev), torch.empty((B, H), dtype=torch.int32, device=dev))
+
+
+def _check_decode_args(q, K, V):
     for t in (q, K, V):
         if not t.is_cuda:
             raise ValueError("entmax_attn_decode: tensors must live on the GPU (there is no CPU path)")
     if K.dim() != 4 or K.shape != V.shape or q.shape != K.shape[:2] + K.shape[3:] or not (
             q.is_contiguous() and K.is_contiguous() and V.is_contiguous()) or not (q.dtype == K.dtype == V.dtype):
         raise ValueError("entmax_attn_decode: q [B,H,d], K, V [B,H,N,d], contiguous, of one dtype")
-    B, H, N, d = K.shape
+    return K.shape
+
+
+def entmax_attn_decode(q, K, V, alpha, workspace=None):
+    """One query per head against all cached keys: q [B,H,d], K, V [B,H,N,d] -> (O [B,H,d], tau [B,H],
+    support [B,H], iters [B,H])."""
+    B, H, N, d = _check_decode_args(q, K, V)
     dev = K.device
-    O = torch.empty((B, H, d), dtype=torch.float32, device=dev)
-    tau = torch.empty((B, H), dtype=torch.float32, device=dev)
-    support = torch.empty((B, H), dtype=torch.int32, device=dev)
-    iters = torch.empty((B, H), dtype=torch.int32, device=dev)
+    O, tau, support, iters = _decode_outputs(B, H, d, dev)
     ws = workspace if workspace is not None else _workspace(entmax_attn_decode_workspace_bytes(B, H, N, d, K.dtype), dev)
     _check(lib().entmax_attn_decode(_ptr(q), _ptr(K), _ptr(V), _ptr(O), _ptr(tau), _ptr(support), _ptr(iters),
                                     B, H, N, d, _dtype_code(K.dtype), float(alpha), _ptr(ws), ws.numel(),

@@ -378,6 +378,7 @@ const char* entmax_attn_strerror(int code) {
         case EA_ERR_DTYPE: return "unknown dtype";
         case EA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
         case EA_ERR_HIP: return "a HIP call failed (see entmax_attn_last_hip_error)";
+        case EA_ERR_TOO_LARGE: return "the problem needs more scratch than the allocation-free entry point holds (see entmax_attn_decode_static_max_bytes)";
         default: return "unknown error code";
     }
 }

@@ -15,6 +15,7 @@
 //                          and o = sum_j p_j v_j over the support only (a gather of a few rows of V).
 #include <math.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "fwd_kernels.hpp"
@@ -349,6 +350,63 @@ size_t decode_groups_bytes(int BH, int N) { return align256((size_t)BH * decode_
 bool decode_shape_ok(int B, int H, int N, int d, ea_dtype t) {
     return (t == EA_F32 || t == EA_BF16) && B > 0 && H > 0 && (long)B * H <= 65535 && N > 0 && N <= (1 << 22) && (d == 64 || d == 128);
 }
+
+// Scratch of the allocation-free entry point: one array per GPU, in the library's code object, held
+// until the process ends.  Host code never uses the array's name as an address: the address on a
+// device is asked for once, with that device current, and kept.
+constexpr size_t DECODE_SCRATCH_BYTES = (size_t)33 << 20;     // 33 MiB: 4 Mi kept-logit slots of 8 bytes + the per-group words
+static __device__ __align__(256) unsigned char scratch[DECODE_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+int decode_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { ea::set_last_hip_error((int)e); return EA_ERR_HIP; }
+    if (dev < 0 || dev >= MAX_DEVICES) return EA_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) { ea::set_last_hip_error((int)e); return EA_ERR_HIP; }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return EA_OK;
+}
+
+int decode_check(const void* q, const void* K, const void* V, const float* O, const float* tau, int B, int H, int N, int d,
+                 ea_dtype t, float alpha) {
+    if (!q || !K || !V || !O || !tau) return EA_ERR_NULL;
+    if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
+    if (!decode_shape_ok(B, H, N, d, t)) return EA_ERR_SHAPE;
+    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > 2.f) return EA_ERR_ALPHA;
+    if (decode_groups(B * H, N) > 1024) return EA_ERR_SHAPE;      // decode_entmax_kernel indexes the groups by thread
+    return EA_OK;
+}
+
+// `workspace`: device memory of at least entmax_attn_decode_workspace_bytes(...) bytes, 256-byte aligned
+int decode_enqueue(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support, int32_t* iters,
+                   int B, int H, int N, int d, ea_dtype t, float alpha, void* workspace, void* hip_stream) {
+    using namespace ea;
+    DecodeParams p{};
+    p.q = q; p.K = K; p.V = V; p.O = O; p.tau = tau; p.support = support; p.iters = iters;
+    p.BH = B * H; p.N = N;
+    p.chunk = decode_chunk(p.BH, N);
+    p.ngrp = decode_groups(p.BH, N);
+    p.gmax = (float*)workspace;
+    p.ccnt = (int*)((char*)workspace + decode_groups_bytes(p.BH, N));
+    p.cand = (uint2*)((char*)workspace + 2 * decode_groups_bytes(p.BH, N));
+    p.inv_sqrt_d = 1.f / sqrtf((float)d);
+    p.alpha = alpha; p.r = 1.f / (alpha - 1.f);
+    p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
+    p.zwin = p.r * (1.f + 1e-5f);
+    p.max_iters = 16;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (t == EA_BF16) return d == 64 ? decode_run<Bf16, 64>(p, s) : decode_run<Bf16, 128>(p, s);
+    return d == 64 ? decode_run<F32, 64>(p, s) : decode_run<F32, 128>(p, s);
+}
 }  // namespace
 
 extern "C" {
@@ -362,30 +420,26 @@ size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype t
 int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
                        int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {
-    using namespace ea;
-    if (!q || !K || !V || !O || !tau) return EA_ERR_NULL;
-    if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
-    if (!decode_shape_ok(B, H, N, d, t)) return EA_ERR_SHAPE;
-    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > 2.f) return EA_ERR_ALPHA;
+    const int rc = decode_check(q, K, V, O, tau, B, H, N, d, t, alpha);
+    if (rc) return rc;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < entmax_attn_decode_workspace_bytes(B, H, N, d, t))
         return EA_ERR_WORKSPACE;
-    DecodeParams p{};
-    p.q = q; p.K = K; p.V = V; p.O = O; p.tau = tau; p.support = support; p.iters = iters;
-    p.BH = B * H; p.N = N;
-    p.chunk = decode_chunk(p.BH, N);
-    p.ngrp = decode_groups(p.BH, N);
-    if (p.ngrp > 1024) return EA_ERR_SHAPE;               // decode_entmax_kernel indexes the groups by thread
-    p.gmax = (float*)workspace;
-    p.ccnt = (int*)((char*)workspace + decode_groups_bytes(p.BH, N));
-    p.cand = (uint2*)((char*)workspace + 2 * decode_groups_bytes(p.BH, N));
-    p.inv_sqrt_d = 1.f / sqrtf((float)d);
-    p.alpha = alpha; p.r = 1.f / (alpha - 1.f);
-    p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
-    p.zwin = p.r * (1.f + 1e-5f);
-    p.max_iters = 16;
-    hipStream_t s = (hipStream_t)hip_stream;
-    if (t == EA_BF16) return d == 64 ? decode_run<Bf16, 64>(p, s) : decode_run<Bf16, 128>(p, s);
-    return d == 64 ? decode_run<F32, 64>(p, s) : decode_run<F32, 128>(p, s);
+    return decode_enqueue(q, K, V, O, tau, support, iters, B, H, N, d, t, alpha, workspace, hip_stream);
+}
+
+size_t entmax_attn_decode_static_max_bytes(void) { return DECODE_SCRATCH_BYTES; }
+
+int entmax_attn_decode_static(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
+                              int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, void* hip_stream) {
+    const int rc = decode_check(q, K, V, O, tau, B, H, N, d, t, alpha);
+    if (rc) return rc;
+    if (entmax_attn_decode_workspace_bytes(B, H, N, d, t) > DECODE_SCRATCH_BYTES) return EA_ERR_TOO_LARGE;
+    void* ws = nullptr;
+    const int rs = decode_scratch_of_current_device(&ws);
+    if (rs) return rs;
+    // the kernels write every word of the scratch they later read (per-group maxima, counts and
+    // kept logits): nothing has to start at zero, so what the previous call left needs no clearing
+    return decode_enqueue(q, K, V, O, tau, support, iters, B, H, N, d, t, alpha, ws, hip_stream);
 }
 
 }  // extern "C"
