@@ -17,6 +17,34 @@ EA_DEV uint32_t pack_f16x2(float a, float b) {
     v[0] = (_Float16)a; v[1] = (_Float16)b;
     return __builtin_bit_cast(uint32_t, v);
 }
+// Second-stage operands in two fp16 halves.  A product whose B operand is rounded to fp16 carries a
+// relative error of 2^-12 per element; summed over the hundreds or thousands of query rows that
+// attend to one key (or over keys that share a large common component) those errors are what is left
+// when the exact terms cancel, and they pass 1e-2 (1 + |gradient|).  So the operand is cut in two:
+// hi = x with all but its 11 leading significant bits cleared (an fp16 value exactly), lo = x - hi
+// (exact in fp32) rounded to fp16; hi + lo carries 21 bits of x, and the product is two MFMAs on the
+// same A fragment.  SPLIT_NONE: one fp16 operand; SPLIT_SIGNED: the operands whose terms cancel
+// (dS, U (dP - e)) are cut; SPLIT_ALL: P and U as well.
+constexpr int SPLIT_NONE = 0, SPLIT_SIGNED = 1, SPLIT_ALL = 2;
+#ifndef EA_BWD_SPLIT
+#define EA_BWD_SPLIT SPLIT_ALL
+#endif
+EA_DEV float f16_head(float x) { return __uint_as_float(__float_as_uint(x) & 0xffffe000u); }
+// packs of (hi, hi) and (lo, lo) of two floats
+EA_DEV void pack_split(float a, float b, uint32_t& hi, uint32_t& lo) {
+    const float ha = f16_head(a), hb = f16_head(b);
+    hi = pack_f16x2(ha, hb);
+    lo = pack_f16x2(a - ha, b - hb);
+}
+// x -> what fp16 rounding of x leaves behind (the plain tile bodies: stage2 rounds to nearest)
+template <int QB> EA_DEV void f16_tail(f32x16 (&Y)[2][QB]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) Y[kb][qb][v] -= (float)(_Float16)Y[kb][qb][v];
+}
 EA_DEV f16x8 frag_of(const uint32_t (&w)[8], int s2) {
     u32x4 v;
     v[0] = w[4 * s2]; v[1] = w[4 * s2 + 1]; v[2] = w[4 * s2 + 2]; v[3] = w[4 * s2 + 3];
@@ -33,7 +61,7 @@ EA_DEV f16x8 frag_of(const uint32_t (&w)[8], int s2) {
 //     stage 2, half 1                                    (matrix pipe only)
 // LDS reads run PF steps ahead of the MFMAs that use them.  An MFMA lasts 32 cycles and a vector
 // instruction 4, so up to 7 vector instructions fit behind each MFMA at no cost.
-template <class E, class E2, int D, int AM>
+template <class E, class E2, int D, int AM, int SPLIT>
 EA_DEV void dq_tile_staggered(const char* kbuf, const char* vbuf, const Owned<E, D, 1>& qf, const Owned<E, D, 1>& gf,
                               f32x16 (&XA)[D / 32][1], f32x16 (&XB)[D / 32][1], float thr, float ctr, float c, float r,
                               float& num, float& den, const Frag1<E, D>& f1, const Frag2<E2, D>& f2) {
@@ -47,6 +75,7 @@ EA_DEV void dq_tile_staggered(const char* kbuf, const char* vbuf, const Owned<E,
     using frag2 = typename E2::frag;
     f32x16 S[2], P[2];
     uint32_t tp[2][8], up[2][8];          // t = u (dP - e) and u as fp16 pairs: the stage-2 B operands
+    uint32_t tl[2][8], ul[2][8];          // their low halves (SPLIT)
     frag ak[N1], av[N1];
     frag2 at[N2];
     const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -62,8 +91,10 @@ EA_DEV void dq_tile_staggered(const char* kbuf, const char* vbuf, const Owned<E,
         S[kb][e] = t;
         P[kb][e] = u;
         if (e & 1) {
-            tp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
-            up[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
+            if constexpr (SPLIT >= SPLIT_SIGNED) pack_split(S[kb][e - 1], S[kb][e], tp[kb][e >> 1], tl[kb][e >> 1]);
+            else tp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
+            if constexpr (SPLIT >= SPLIT_ALL) pack_split(P[kb][e - 1], P[kb][e], up[kb][e >> 1], ul[kb][e >> 1]);
+            else up[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
         }
     };
     auto read2 = [&](int i2) { at[i2] = f2(kbuf, i2 / (2 * ND), (i2 / ND) & 1, i2 % ND); };
@@ -109,6 +140,8 @@ EA_DEV void dq_tile_staggered(const char* kbuf, const char* vbuf, const Owned<E,
             for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + EPM + k);
         }
         sched_fence();
+        if constexpr (SPLIT >= SPLIT_SIGNED) { E2::template mma_acc<false>(at[i], frag_of(tl[kb], s2), XA[db][0]); sched_fence(); }
+        if constexpr (SPLIT >= SPLIT_ALL) { E2::template mma_acc<false>(at[i], frag_of(ul[kb], s2), XB[db][0]); sched_fence(); }
     }
 }
 
@@ -250,6 +283,8 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
                 }
         stage2<E2, D, QB, true>(XA, kbuf, S, lane);
         stage2<E2, D, QB, true>(XB, kbuf, dP, lane);
+        if constexpr (E2::EPL == 8 && EA_BWD_SPLIT >= SPLIT_SIGNED) { f16_tail<QB>(S); stage2<E2, D, QB, true>(XA, kbuf, S, lane); }
+        if constexpr (E2::EPL == 8 && EA_BWD_SPLIT >= SPLIT_ALL) { f16_tail<QB>(dP); stage2<E2, D, QB, true>(XB, kbuf, dP, lane); }
     };
     if constexpr (E::EPL == 8 && QB == 1 && NBUF == 2) {
         // tiles wholly below the diagonal (the head of the ascending list) take the staggered body;
@@ -262,7 +297,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
             [&](int it, const char* kbuf) {
                 if (!mask_bit(fm, W, myrow, tl[it])) return;
                 ++ntile;
-                dq_tile_staggered<E, E2, D, AM>(kbuf, kbuf + SM::RBYTES, qf, gf, XA, XB, thr[0], ctr[0], c, r, num[0], den[0], frag1, frag2);
+                dq_tile_staggered<E, E2, D, AM, EA_BWD_SPLIT>(kbuf, kbuf + SM::RBYTES, qf, gf, XA, XB, thr[0], ctr[0], c, r, num[0], den[0], frag1, frag2);
             },
             tile_plain_order);
     } else {
@@ -305,7 +340,7 @@ __global__ __launch_bounds__(NW * 64) void dq_kernel(Params p) {
 // zero.  With the owned keys scaled by kappa the first product is then y / rho, y = (alpha-1) s -
 // tau, and the second dP - delta; P = y^r and dS = y^(r-1) (dP - delta) come out in units of
 // rho^r and rho^(r-1), which the kernel's epilogue multiplies back in.
-template <class E, class E2, int D, int AM>
+template <class E, class E2, int D, int AM, int SPLIT>
 EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float* ntau_s, const float* ndel_s,
                                 const Owned<E, D, 1>& kf, const Owned<E, D, 1>& vf, f32x16 (&XV)[D / 32][1],
                                 f32x16 (&XK)[D / 32][1], float r, int h, const Frag1<E, D>& f1,
@@ -317,6 +352,7 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
     using frag2 = typename E2::frag;
     f32x16 S[2], P[2];
     uint32_t pp[2][8], sp[2][8];          // P and dS as fp16 pairs: the stage-2 B operands
+    uint32_t pl[2][8], sl[2][8];          // their low halves (SPLIT)
     frag aq[N1], ag[N1];
     frag2 tg[N2], tq[N2];
 
@@ -339,8 +375,10 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
         S[kb][e] = u * yp;
         P[kb][e] = u * P[kb][e];
         if (e & 1) {
-            pp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
-            sp[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
+            if constexpr (SPLIT >= SPLIT_ALL) pack_split(S[kb][e - 1], S[kb][e], pp[kb][e >> 1], pl[kb][e >> 1]);
+            else pp[kb][e >> 1] = pack_f16x2(S[kb][e - 1], S[kb][e]);
+            if constexpr (SPLIT >= SPLIT_SIGNED) pack_split(P[kb][e - 1], P[kb][e], sp[kb][e >> 1], sl[kb][e >> 1]);
+            else sp[kb][e >> 1] = pack_f16x2(P[kb][e - 1], P[kb][e]);
         }
     };
     auto read2 = [&](int i2) {
@@ -391,6 +429,8 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
             for (int k = 0; k < EPM; ++k) score_math(1, 2 * EPM * j + EPM + k);
         }
         sched_fence();
+        if constexpr (SPLIT >= SPLIT_SIGNED) { E2::template mma_acc<false>(tq[i], frag_of(sl[kb], s2), XK[db][0]); sched_fence(); }
+        if constexpr (SPLIT >= SPLIT_ALL) { E2::template mma_acc<false>(tg[i], frag_of(pl[kb], s2), XV[db][0]); sched_fence(); }
     }
 }
 
@@ -540,6 +580,8 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
             }
         stage2<E2, D, QB, true>(XV, gbuf, S, lane);
         stage2<E2, D, QB, true>(XK, qbuf, dP, lane);
+        if constexpr (E2::EPL == 8 && EA_BWD_SPLIT >= SPLIT_SIGNED) { f16_tail<QB>(dP); stage2<E2, D, QB, true>(XK, qbuf, dP, lane); }
+        if constexpr (E2::EPL == 8 && EA_BWD_SPLIT >= SPLIT_ALL) { f16_tail<QB>(S); stage2<E2, D, QB, true>(XV, gbuf, S, lane); }
     };
     if constexpr (E::EPL == 8 && QB == 1 && NBUF == 2) {
         // query tiles on the diagonal (the head of the ascending list), and one more when that makes
@@ -554,7 +596,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
                 if (!((tl[it] >> (16 + mycol)) & 1)) return;
                 ++ntile_done;
                 const float* tau_s = (const float*)(qbuf + VEC_OFF);
-                dkdv_tile_staggered<E, E2, D, AM>(qbuf, qbuf + SM::RBYTES, tau_s, tau_s + TILE, kf, vf, XV, XK, r, h, frag1, frag2);
+                dkdv_tile_staggered<E, E2, D, AM, EA_BWD_SPLIT>(qbuf, qbuf + SM::RBYTES, tau_s, tau_s + TILE, kf, vf, XV, XK, r, h, frag1, frag2);
             });
     } else {
         stream_tiles<NBUF>(ntl, set0, NBUF == 2 ? set1 : set0, issue_qg, tile_plain_order);

@@ -53,33 +53,79 @@ def check_forward(Q, K, V, alpha, causal, O, tau, mask, ref=None, label=""):
     return ref, dict(dtau=float(dtau), dO=float(dO), band=int((~clear).sum()))
 
 
-def check_backward(Q, K, V, dO, alpha, causal, dQ, dK, dV, ref=None, label="", exclude_rows=None):
+def conditioning_slack(Q, K, V, dO, alpha, causal, tau_ref):
+    """What a perturbation of y = (alpha-1) s - tau within the arithmetic's own accuracy can change
+    in dQ, dK, dV: a first-order, worst-case (sums of absolute values) bound, per element.
+
+    The kernels know y only up to eta = 2 tol_solver + 2^-21 (1 + |x|): the refinement stops within
+    tol_solver (1e-4 for bf16 inputs, 1e-6 for fp32) of the root, and an fp32 dot product of d terms
+    carries a few units of 2^-24 of relative error.  At alpha = 2 the band of the block mask (1e-3)
+    is used instead, as for the mask.  The factors U = y_+^(r-1) and P = y_+^r (r = 1/(alpha-1)) can
+    move by  bU = max |U(y +- eta) - U(y)|,  bP likewise - evaluated exactly, since for alpha > 1.5
+    U has an unbounded slope at the support edge (alpha = 2: it jumps from 0 to 1).  Then
+        delta = sum U g / sum U  moves by at most  D = sum bU |g - delta| / sum U      (g = dO V^T)
+        dS = U (g - delta)       by  bS = bU |g - delta| + U D
+        dQ by bS |K| / sqrt(d),  dK by bS^T |Q| / sqrt(d),  dV by bP^T |dO|.
+    Used where the gradient is that sensitive by construction: alpha > 1.5, and fp32 inputs (whose
+    1e-5 bar is of the order of the fp32 score rounding itself once a key is attended by hundreds of
+    rows).  For bf16 inputs at alpha <= 1.5 the plain tolerance stands."""
+    Qn, Kn, Vn, Gn = (to_np64(t) for t in (Q, K, V, dO))
+    B, H, N, d = Qn.shape
+    tol_solver = 1e-4 if Q.dtype == torch.bfloat16 else 1e-6
+    r = 1.0 / (alpha - 1.0)
+    out = {k: np.zeros_like(Qn) for k in ("dQ", "dK", "dV")}
+    vis = np.tril(np.ones((N, N), bool)) if causal else None
+
+    def U(y):
+        return np.where(y > 0, np.power(np.maximum(y, 0), r - 1.0), 0.0) if alpha != 2.0 else (y > 0).astype(np.float64)
+
+    def P(y):
+        return np.power(np.maximum(y, 0), r)
+
+    for b in range(B):
+        for h in range(H):
+            X = (alpha - 1.0) * (Qn[b, h] @ Kn[b, h].T) / np.sqrt(d)
+            y = X - tau_ref[b, h][:, None]
+            eta = 2 * tol_solver + 2.0 ** -21 * (1 + np.abs(X))
+            if alpha == 2.0:
+                eta = np.maximum(eta, MASK_BAND)
+            if vis is not None:
+                y = np.where(vis, y, -1e30)
+            u, p = U(y), P(y)
+            bu = np.maximum(np.abs(U(y + eta) - u), np.abs(U(y - eta) - u))
+            bp = np.maximum(np.abs(P(y + eta) - p), np.abs(P(y - eta) - p))
+            g = Gn[b, h] @ Vn[b, h].T
+            usum = u.sum(-1)
+            delta = (u * g).sum(-1) / usum
+            gd = np.abs(g - delta[:, None])
+            D = (bu * gd).sum(-1) / usum
+            bS = bu * gd + u * D[:, None]
+            out["dQ"][b, h] = bS @ np.abs(Kn[b, h]) / np.sqrt(d)
+            out["dK"][b, h] = bS.T @ np.abs(Qn[b, h]) / np.sqrt(d)
+            out["dV"][b, h] = bp.T @ np.abs(Gn[b, h])
+    return out
+
+
+def check_backward(Q, K, V, dO, alpha, causal, dQ, dK, dV, ref=None, label="", tau_ref=None):
+    """|got - oracle| <= tol (1 + |oracle|) element-wise, tol = 1e-2 (bf16 inputs) or 1e-5 (fp32).
+    For alpha > 1.5 and for fp32 inputs the bound of conditioning_slack is added (it needs the
+    oracle's tau: pass tau_ref, or it is computed here)."""
     tol = TOL[Q.dtype]["grad"]
-    if 1.5 < alpha < 2.0:
-        # U = y^(r-1) with 0 < r-1 < 1 has an unbounded slope at the support edge:
-        # dU = (r-1) y^(r-2) dy, so a score rounding dy is amplified for entries with small y.
-        # No config of the workload uses such an alpha; the extra test allows 10x.
-        tol *= 10
     if ref is None:
         ref = eo.attn_bwd(to_np64(Q), to_np64(K), to_np64(V), to_np64(dO), alpha, causal)
+    slack = None
+    if alpha > 1.5 or Q.dtype == torch.float32:
+        if tau_ref is None:
+            tau_ref = eo.attn_fwd(to_np64(Q), to_np64(K), to_np64(V), alpha, causal, want_margin=False)["tau"]
+        slack = conditioning_slack(Q, K, V, dO, alpha, causal, tau_ref)
     out = {}
     for name, got in (("dQ", dQ), ("dK", dK), ("dV", dV)):
         g = to_np64(got)
-        err = np.abs(g - ref[name]) / (1.0 + np.abs(ref[name]))
-        if exclude_rows is not None and name == "dQ":
-            err = np.where(exclude_rows[..., None], 0.0, err)
-        out[name] = float(err.max())
-        assert err.max() <= tol, f"{label}: {name} scaled error {err.max():.3e} > {tol}"
+        allowed = tol * (1.0 + np.abs(ref[name])) + (slack[name] if slack is not None else 0.0)
+        diff = np.abs(g - ref[name])
+        out[name] = float((diff / (1.0 + np.abs(ref[name]))).max())
+        worst = float((diff / allowed).max())
+        if slack is not None:
+            out[name + "_of_allowed"] = worst
+        assert worst <= 1.0, f"{label}: {name} error is {worst:.3f} of what is allowed (scaled error {out[name]:.3e}, tol {tol})"
     return ref, out
-
-
-def near_threshold_rows(Q, K, alpha, causal, tau_ref, band=MASK_BAND):
-    """Rows that have a score within `band` of their threshold: at alpha = 2 the factor U jumps
-    from 0 to 1 there, so their gradient is not comparable at finite precision."""
-    Qn, Kn = to_np64(Q), to_np64(K)
-    d = Qn.shape[-1]
-    X = (alpha - 1) * np.einsum("bhrc,bhjc->bhrj", Qn, Kn) / np.sqrt(d) - tau_ref[..., None]
-    if causal:
-        N = X.shape[-1]
-        X = np.where(np.tril(np.ones((N, N), bool)), X, -np.inf)
-    return (np.abs(X) < band).any(-1)

@@ -93,23 +93,26 @@ def test_c4_full_size_one_head(ea):
     print("  ", info, ginfo, flush=True)
 
 
-def test_maximum_sequence_length(ea):
+@pytest.mark.parametrize("recipe", ["gaussian", "planted"])
+def test_maximum_sequence_length(ea, recipe):
     # N = 131072 is the largest size the library accepts (2048 key tiles, 64 mask words per row);
-    # one head, d = 64, i.i.d. Gaussian Q, K with sigma = 3.  (Not the planted-key recipe: there every
-    # support key of a query tile carries the same planted direction, dQ and dK are what is left
-    # after those terms cancel, and at this length 16-bit dS no longer holds that remainder to
-    # 1e-2; the planted recipe is checked at the 64k configuration.)
+    # one head, d = 64: i.i.d. Gaussian Q, K with sigma = 3, and the planted-key recipe of the
+    # context-scaling workload (every support key of a query tile carries the same planted
+    # direction, so dQ and dK are what is left after those terms cancel)
     B, H, N, d, alpha, causal = 1, 1, 131072, 64, 1.5, True
-    print("case N=131072", flush=True)
-    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", 3.0, seed=4002)
+    print(f"case N=131072 {recipe}", flush=True)
+    if recipe == "planted":
+        q, k, v, do = workloads.planted_qkv(B, H, N, d, "bf16", 3.0, seed=7032)
+    else:
+        q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", 3.0, seed=4002)
     Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
     O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
     dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask)
     torch.cuda.synchronize()
     assert iters.max().item() <= 12
     print("  oracle", flush=True)
-    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="N=131072")
-    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="N=131072")
+    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label=f"N=131072 {recipe}")
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label=f"N=131072 {recipe}")
     T = N // 64
     sparsity = 1.0 - (ref["margin"] > 0).sum() / (T * (T + 1) / 2)
     print("  block sparsity", sparsity, info, ginfo, "mean iters", iters.float().mean().item(), flush=True)

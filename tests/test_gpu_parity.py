@@ -33,8 +33,7 @@ def run_case(ea, B, H, N, d, dtype, causal, alpha, sigma, seed, block_rho=0.0, b
     if backward:
         dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask if mask_arg else None)
         torch.cuda.synchronize()
-        excl = parity.near_threshold_rows(q, k, alpha, causal, ref["tau"]) if alpha == 2.0 else None
-        _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label=label, exclude_rows=excl)
+        _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label=label, tau_ref=ref["tau"])
         print("  bwd", ginfo, flush=True)
     return info
 
@@ -131,16 +130,14 @@ def test_drifting_row_maximum(ea, dtype, rise, causal):
     torch.cuda.synchronize()
     _, info = parity.check_forward(q, k, v, 1.5, causal, O, tau, mask, label="ramp")
     print("  ramp", info, "mean iters", iters.float().mean().item(), flush=True)
-    if dtype == "bf16" and rise == 0.25:
-        # (all queries share one direction here, so rounding errors of dS add up coherently in
-        # dK over hundreds of rows: the fp32 1e-5 gradient bar is checked on the Gaussian cases;
-        # the steep ramp has |K| up to 50 along that direction and dQ cancels to a small
-        # remainder of such terms, which no 16-bit dS can hold to 1e-2; so does dK on the dense
-        # non-causal falling ramp)
-        dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, 1.5, causal, block_mask=mask)
-        torch.cuda.synchronize()
-        _, ginfo = parity.check_backward(q, k, v, do, 1.5, causal, dQ, dK, dV, label="ramp")
-        print("  ramp bwd", ginfo, flush=True)
+    # the backward in every case: all queries share one direction here and |K| reaches 50 along it,
+    # so dQ is what is left after large terms cancel and dK sums hundreds of like-signed rows -
+    # which second-stage operands of 11 significant bits did not hold to 1e-2 (they are cut in two
+    # fp16 halves since)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, 1.5, causal, block_mask=mask)
+    torch.cuda.synchronize()
+    _, ginfo = parity.check_backward(q, k, v, do, 1.5, causal, dQ, dK, dV, label="ramp")
+    print("  ramp bwd", ginfo, flush=True)
     assert iters.max().item() <= 12
 
 
@@ -211,8 +208,7 @@ def test_sparse_row_groups_gather_their_gradients(ea, dtype, d, alpha, sigma, ma
     # test_gather_and_matrix_paths_agree)
     assert st["bwd_gather_rows"] > 0 or dtype == "f32"
     ref, _ = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label=f"fwd {dtype} {alpha}")
-    excl = parity.near_threshold_rows(q, k, alpha, causal, ref["tau"]) if alpha == 2.0 else None
-    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label=f"bwd gather {dtype} {alpha}", exclude_rows=excl)
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label=f"bwd gather {dtype} {alpha}", tau_ref=ref["tau"])
     print("  ", ginfo, flush=True)
 
 
@@ -248,12 +244,15 @@ def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma, otol, gtol):
         assert err <= tol
 
 
-def test_keys_that_many_rows_attend_to(ea, dtype="bf16"):
-    # two hub keys that every query attends to (a common direction added to all queries and to
-    # those keys) on top of peaked Gaussian attention: a hub collects far more entries than a
-    # key's list holds, and the rest arrive as atomic additions
-    B, H, N, d, alpha, causal = 1, 2, 3072, 128, 1.5, False
-    sigma = 3.0
+@pytest.mark.parametrize("dtype,d,N,sigma,causal,hubs", [("bf16", 128, 3072, 3.0, False, (5, 1777)),
+                                                         ("bf16", 64, 6144, 2.5, True, (7, 300, 900)),
+                                                         ("f32", 64, 3072, 1.0, False, (5, 1777))])
+def test_keys_that_many_rows_attend_to(ea, dtype, d, N, sigma, causal, hubs):
+    # hub keys that most queries attend to (a common direction added to all queries and to those
+    # keys) on top of peaked Gaussian attention.  On the gather path a hub collects far more entries
+    # than a key's list holds, and the rest arrive as atomic additions; on the matrix kernels dK, dV of
+    # a hub sum thousands of rows (the d = 64 case missed 1e-2 with 11-bit second-stage operands).
+    B, H, alpha = 1, 2, 1.5
     q, k, v, do = workloads.gaussian_qkv(B, H, N, d, dtype, sigma, seed=95)
     g = torch.Generator().manual_seed(96)
     dirn = torch.randn(d, generator=g)
@@ -261,7 +260,7 @@ def test_keys_that_many_rows_attend_to(ea, dtype="bf16"):
     amp = (sigma * sigma * 3.5 * d ** 0.5) ** 0.5          # amp^2 / sqrt(d) = 3.5 sigma^2: near the row maximum, so a hub is in the support of many rows, not all
     q = (q.float() + amp * dirn).to(q.dtype)
     k = k.clone()
-    for hub in (5, 1777):
+    for hub in hubs:
         k[:, :, hub] = (k[:, :, hub].float() + amp * dirn).to(k.dtype)
     Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
     O, tau, mask, _ = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
@@ -270,10 +269,18 @@ def test_keys_that_many_rows_attend_to(ea, dtype="bf16"):
     torch.cuda.synchronize()
     st = ea.read_stats(ws)
     print("  backward gather rows", st["bwd_gather_rows"], "of", B * H * N, flush=True)
-    assert st["bwd_gather_rows"] > 0
-    parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="hubs")
-    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="hubs")
+    if dtype == "bf16" and d == 128:
+        assert st["bwd_gather_rows"] > 0
+    ref, _ = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="hubs")
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="hubs", tau_ref=ref["tau"])
     print("  ", ginfo, flush=True)
+
+
+def test_sparsemax_with_near_uniform_attention(ea):
+    # alpha = 2 with small scores: thousands of keys per row, many of them within the band around
+    # the threshold where U jumps between 0 and 1; what those entries may change in dQ, dK, dV is
+    # the slack the comparison derives, everything else must meet the plain bar
+    run_case(ea, 1, 2, 2048, 64, "bf16", True, 2.0, 0.5, seed=12)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -292,9 +299,8 @@ def test_alpha_per_head(ea, dtype):
         sl = slice(hh, hh + 1)
         ref, info = parity.check_forward(q[:, sl], k[:, sl], v[:, sl], a, causal, O[:, sl], tau[:, sl], mask[:, sl],
                                          label=f"head {hh} alpha {a}")
-        excl = parity.near_threshold_rows(q[:, sl], k[:, sl], a, causal, ref["tau"]) if a == 2.0 else None
         _, ginfo = parity.check_backward(q[:, sl], k[:, sl], v[:, sl], do[:, sl], a, causal, dQ[:, sl], dK[:, sl],
-                                         dV[:, sl], label=f"head {hh} alpha {a}", exclude_rows=excl)
+                                         dV[:, sl], label=f"head {hh} alpha {a}", tau_ref=ref["tau"])
         print(f"  head {hh} alpha {a}:", info, ginfo, flush=True)
     # equal values take the single-alpha path and must give its result bit for bit
     O1, tau1, mask1 = ea.entmax_attn_fwd(Q, K, V, [1.5] * H, causal)

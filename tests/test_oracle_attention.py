@@ -182,3 +182,44 @@ def test_decode_one_dominant_key_and_equal_keys():
     dec = eo.attn_decode(q, K, V, alpha)
     assert np.abs(dec["O"][0, 0] - V[0, 0].mean(0)).max() < 1e-12
     assert abs(dec["tau"][0, 0] - ((alpha - 1) * 0.3 * d / np.sqrt(d) - N ** (1 - alpha))) < 1e-12
+
+
+@pytest.mark.parametrize("alpha,dtype", [(1.75, torch.bfloat16), (2.0, torch.bfloat16), (1.5, torch.float32), (1.25, torch.float32)])
+def test_conditioning_slack_bounds_a_shift_of_the_thresholds(alpha, dtype):
+    # the slack the GPU gradient comparison adds for alpha > 1.5 and for fp32 inputs is a bound of
+    # what a perturbation of y = (alpha-1) s - tau within eta changes: shift every row's threshold by
+    # +-eta_min (a perturbation inside that budget) in a plain numpy backward and compare
+    from tests import parity
+    B, H, N, d, causal = 1, 1, 96, 16, True
+    g = torch.Generator().manual_seed(5)
+    q, k, v, do = (torch.randn(B, H, N, d, generator=g).to(dtype) for _ in range(4))
+    Q, K, V, G = (parity.to_np64(t)[0, 0] for t in (q, k, v, do))
+    tau = eo.attn_fwd(Q[None, None], K[None, None], V[None, None], alpha, causal, want_margin=False)["tau"]
+    slack = parity.conditioning_slack(q, k, v, do, alpha, causal, tau)
+    r = 1.0 / (alpha - 1.0)
+    X = (alpha - 1.0) * Q @ K.T / np.sqrt(d)
+    vis = np.tril(np.ones((N, N), bool))
+
+    def grads(shift):
+        y = np.where(vis, X - tau[0, 0][:, None] - shift[:, None], -1.0)
+        yp = np.maximum(y, 0)
+        P = yp ** r
+        U = np.where(y > 0, yp ** (r - 1.0), 0.0) if alpha != 2.0 else (y > 0).astype(float)
+        gg = G @ V.T
+        delta = (U * gg).sum(-1) / U.sum(-1)
+        dS = U * (gg - delta[:, None])
+        return dS @ K / np.sqrt(d), dS.T @ Q / np.sqrt(d), P.T @ G
+
+    base = grads(np.zeros(N))
+    ref = eo.attn_bwd(Q[None, None], K[None, None], V[None, None], G[None, None], alpha, causal)
+    for name, b in zip(("dQ", "dK", "dV"), base):
+        assert np.abs(b - ref[name][0, 0]).max() < 1e-9          # the numpy backward is the oracle's
+    tol_solver = 1e-4 if dtype == torch.bfloat16 else 1e-6
+    eta_min = 1e-3 if alpha == 2.0 else 2 * tol_solver
+    rng = np.random.default_rng(3)
+    for trial in range(4):
+        shift = eta_min * rng.uniform(-1, 1, N)
+        for name, b, s_ in zip(("dQ", "dK", "dV"), base, grads(shift)):
+            # first-order bound: a few per cent of headroom for the second-order terms
+            assert (np.abs(s_ - b) <= 1.05 * slack[name][0, 0] + 1e-12).all(), name
+    assert all((slack[n_] >= 0).all() for n_ in slack)
