@@ -8,6 +8,10 @@ One step = forward + backward over each of the four sigma batches.  `value` is t
 dense-equivalent (FlashAttention convention, causal half) FLOPs of a step over its time.
 Per sigma point the line also carries measured block sparsity, mean tau iterations per row,
 the MFMA flops actually issued and their fraction of the bf16 dense MFMA peak.
+Beside the timed sweep (never inside the timed region, never part of `value`) the line carries:
+the same sweep on block-correlated rows (64 - 96 % block sparsity, where the backward runs on the
+block-sparse matrix kernels), that sweep once more with the gather paths switched off (per-kernel
+TFLOP/s of out / dq / dkdv), and the context-scaling rows of the second workload.
 
 Prints ONE JSON line on stdout.
 """
@@ -77,7 +81,7 @@ def block_sparsity(mask, T, causal):
     return 1.0 - set_bits / visible
 
 
-def context_scaling(ea, workloads, dev, args):
+def context_rows(ea, workloads, dev, steps, warmup):
     """Second workload (Sec. 4.2 "Context scaling"): forward+backward time against context length
     at a fixed token budget.  The paper drives this with block-sparsity ratios learned by its 1B
     model (Fig. 6), which are not available; the planted-key recipe of the 64k configuration stands
@@ -92,7 +96,7 @@ def context_scaling(ea, workloads, dev, args):
         ws_f = torch.empty(ea.entmax_attn_workspace_bytes(1, H, N, d, "bf16", causal, False), dtype=torch.uint8, device=dev)
         ws_b = torch.empty(ea.entmax_attn_workspace_bytes(1, H, N, d, "bf16", causal, True), dtype=torch.uint8, device=dev)
         fwd_ms, bwd_ms = [], []
-        for it in range(args.warmup + args.steps):
+        for it in range(warmup + steps):
             e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
             e0.record()
             O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=ws_f)
@@ -100,7 +104,7 @@ def context_scaling(ea, workloads, dev, args):
             ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws_b)
             e2.record()
             torch.cuda.synchronize()
-            if it >= args.warmup:
+            if it >= warmup:
                 fwd_ms.append(e0.elapsed_time(e1)); bwd_ms.append(e1.elapsed_time(e2))
         f, b = float(np.median(fwd_ms)), float(np.median(bwd_ms))
         dense = 14.0 * H * N * N * d * 0.5
@@ -110,6 +114,11 @@ def context_scaling(ea, workloads, dev, args):
         log(rows[-1])
         del Q, K, V, dO, ws_f, ws_b, O, tau, mask, iters
         torch.cuda.empty_cache()
+    return rows
+
+
+def context_scaling(ea, workloads, dev, args):
+    rows = context_rows(ea, workloads, dev, args.steps, args.warmup)
     print(json.dumps(dict(metric="fwd+bwd ms vs context length at 256k tokens (planted-key stand-in for learned sparsity)",
                           unit="ms", n_gpus=1, steps=args.steps, warmup=args.warmup, dtype="bf16", data="synthetic",
                           config=dict(workload="context scaling: alpha=1.5 bf16 d=64 causal, B*H*N = 262144 tokens, "
@@ -191,6 +200,8 @@ def main():
                     help="block-correlated query variant of the generator (0 = i.i.d. rows as in the config)")
     ap.add_argument("--small", action="store_true", help="N=2048 instead of 16384 (plumbing check only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--brief", action="store_true",
+                    help="only the timed sweep: leave out the block-correlated sweep, the gather-off pass and the context-scaling rows")
     ap.add_argument("--no-gather", action="store_true",
                     help="keep every row group on the block-sparse matrix kernels (A/B measurement of the gather paths)")
     ap.add_argument("--workload", choices=["sparsity", "context", "decode"], default="sparsity",
@@ -225,92 +236,119 @@ def main():
     B, H, N, d, alpha, causal = cfg["B"], cfg["H"], cfg["N"], cfg["d"], cfg["alpha"], cfg["causal"]
     T = N // 64
     sigmas = [float(s) for s in args.sigmas.split(",")]
+    dense_flops_point = 14.0 * B * H * N * N * d * (0.5 if causal else 1.0)
 
-    points = []
-    for i, sg in enumerate(sigmas):
-        q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sg, seed=3000 + i, block_rho=args.block_rho)
-        pt = dict(sigma=sg, cpu=(q, k, v, do) if i == min(1, len(sigmas) - 1) else None,
-                  Q=q.to(dev), K=k.to(dev), V=v.to(dev), dO=do.to(dev))
-        pt["ws_f"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device=dev)
-        pt["ws_b"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device=dev)
-        points.append(pt)
-        log(f"generated sigma={sg}")
+    def make_points(block_rho, keep_cpu):
+        pts = []
+        for i, sg in enumerate(sigmas):
+            q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sg, seed=3000 + i, block_rho=block_rho)
+            pt = dict(sigma=sg, cpu=(q, k, v, do) if (keep_cpu and i == min(1, len(sigmas) - 1)) else None,
+                      Q=q.to(dev), K=k.to(dev), V=v.to(dev), dO=do.to(dev))
+            pt["ws_f"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device=dev)
+            pt["ws_b"] = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device=dev)
+            pts.append(pt)
+            log(f"generated sigma={sg} block_rho={block_rho}")
+        return pts
 
-    def step(record=None):
-        for pt in points:
+    def step(pts):
+        for pt in pts:
             O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True,
                                                       workspace=pt["ws_f"])
-            dQ, dK, dV = ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal,
-                                            block_mask=mask, workspace=pt["ws_b"])
-            if record is not None:
-                record.append((mask, iters))
+            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
 
+    def measure_points(pts):
+        """Per sigma point, outside any timed region: forward and backward time (events on the stream the
+        library launches on), the kernels' own executed-tile counters, block sparsity, tau iterations;
+        and the per-kernel times (HIP events inside the library) summed over the points."""
+        rows = []
+        ea.entmax_attn_timer_enable(True)
+        for pt in pts:
+            e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            e0.record()
+            O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True, workspace=pt["ws_f"])
+            e1.record()
+            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
+            e2.record()
+            torch.cuda.synchronize()
+            st = ea.read_stats(pt["ws_f"])
+            st_b = ea.read_stats(pt["ws_b"])
+            for kname in ("delta_subtiles", "dq_subtiles", "dkdv_subtiles", "bwd_list_subtiles", "bwd_gather_rows"):
+                st[kname] = st_b[kname]
+            rows.append(dict(fwd_ms=e0.elapsed_time(e1), bwd_ms=e1.elapsed_time(e2), stats=st,
+                             sparsity=block_sparsity(mask, T, causal), iters=float(iters.float().mean().item())))
+        kt = ea.entmax_attn_timer_read()
+        ea.entmax_attn_timer_enable(False)
+        return rows, kt
+
+    def sweep_rows(pts, rows):
+        out, exec_total = [], {"tau": 0.0, "out": 0.0, "dq": 0.0, "dkdv": 0.0, "bwd_list": 0.0}
+        for pt, pp in zip(pts, rows):
+            parts = executed_flops(pp["stats"], d)
+            for kname in exec_total:
+                exec_total[kname] += parts[kname]
+            tot_ms = pp["fwd_ms"] + pp["bwd_ms"]
+            ex = sum(parts.values())
+            out.append(dict(sigma=pt["sigma"], block_sparsity=round(pp["sparsity"], 4), mean_tau_iters=round(pp["iters"], 3),
+                            fwd_ms=round(pp["fwd_ms"], 3), bwd_ms=round(pp["bwd_ms"], 3),
+                            rows_by_gather=dict(fwd=round(pp["stats"].get("gather_rows", 0) / (B * H * N), 3),
+                                                bwd=round(pp["stats"].get("bwd_gather_rows", 0) / (B * H * N), 3)),
+                            list_overflow_blocks=pp["stats"].get("list_overflow_blocks", 0),
+                            effective_tflops=round(dense_flops_point / (tot_ms * 1e-3) / 1e12, 1),
+                            executed_tflops=round(ex / (tot_ms * 1e-3) / 1e12, 1),
+                            mfma_frac_executed=round(ex / (tot_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)))
+        return out, exec_total
+
+    def kernel_table(kt, exec_total):
+        """Per kernel: average launch time, and for the kernels that issue MFMAs the algorithmic flops
+        of the tiles they visited (their own counters) over that time, as TFLOP/s and as a fraction
+        of the published peak."""
+        tab = {}
+        for kname, (ms, launches) in kt.items():
+            row = dict(avg_ms=round(ms / launches, 3), launches=launches)
+            if kname in exec_total and exec_total[kname] > 0:
+                tf = exec_total[kname] / launches / (ms / launches * 1e-3) / 1e12
+                row["tflops"] = round(tf, 1)
+                row["frac"] = round(tf / MFMA_PEAK_TFLOPS, 4)
+            tab[kname] = row
+        return tab
+
+    points = make_points(args.block_rho, keep_cpu=True)
     for _ in range(args.warmup):
-        step()
+        step(points)
     torch.cuda.synchronize()
-
-    # per-point wall time (events on the stream the library launches on), outside the timed region
-    per_point = []
-    for pt in points:
-        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        e0.record()
-        O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True, workspace=pt["ws_f"])
-        e1.record()
-        ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
-        e2.record()
-        torch.cuda.synchronize()
-        st = ea.read_stats(pt["ws_f"])
-        st_b = ea.read_stats(pt["ws_b"])
-        for kname in ("delta_subtiles", "dq_subtiles", "dkdv_subtiles", "bwd_list_subtiles", "bwd_gather_rows"):
-            st[kname] = st_b[kname]
-        per_point.append(dict(fwd_ms=e0.elapsed_time(e1), bwd_ms=e1.elapsed_time(e2), stats=st,
-                              sparsity=block_sparsity(mask, T, causal), iters=float(iters.float().mean().item())))
+    per_point, _ = measure_points(points)
 
     # ---- timed region: exactly K steps -----------------------------------------------------
     ea.entmax_attn_timer_enable(True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        step(points)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kt = ea.entmax_attn_timer_read()
     ea.entmax_attn_timer_enable(False)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-
-    dense_flops_point = 14.0 * B * H * N * N * d * (0.5 if causal else 1.0)
     value = dense_flops_point * len(points) / (ms_per_step * 1e-3) / 1e12
 
-    sweep, exec_total = [], {"tau": 0.0, "out": 0.0, "dq": 0.0, "dkdv": 0.0, "bwd_list": 0.0}
-    for pt, pp in zip(points, per_point):
-        parts = executed_flops(pp["stats"], d)
-        for kname in exec_total:
-            exec_total[kname] += parts[kname]
-        tot_ms = pp["fwd_ms"] + pp["bwd_ms"]
-        ex = sum(parts.values())
-        sweep.append(dict(sigma=pt["sigma"], block_sparsity=round(pp["sparsity"], 4), mean_tau_iters=round(pp["iters"], 3),
-                          fwd_ms=round(pp["fwd_ms"], 3), bwd_ms=round(pp["bwd_ms"], 3),
-                          rows_by_gather=dict(fwd=round(pp["stats"].get("gather_rows", 0) / (B * H * N), 3),
-                                              bwd=round(pp["stats"].get("bwd_gather_rows", 0) / (B * H * N), 3)),
-                          effective_tflops=round(dense_flops_point / (tot_ms * 1e-3) / 1e12, 1),
-                          executed_tflops=round(ex / (tot_ms * 1e-3) / 1e12, 1),
-                          mfma_frac_executed=round(ex / (tot_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4)))
-
+    sweep, exec_total = sweep_rows(points, per_point)
     # dominant kernel: largest summed time in the timed region; flops per launch from the counters
     # (the counters of one step, averaged over the sigma points it launches on)
     dom = max((k for k in kt if k in exec_total), key=lambda k: kt[k][0])
     dom_ms, dom_launches = kt[dom]
     dom_avg_ms = dom_ms / dom_launches
-    dom_flops_per_launch = exec_total[dom] / len(points)
-    achieved = dom_flops_per_launch / (dom_avg_ms * 1e-3) / 1e12
+    achieved = exec_total[dom] / len(points) / (dom_avg_ms * 1e-3) / 1e12
+    default_mix = args.sigmas == "1,2,3,4" and not args.small and args.block_rho == 0.0 and not args.no_gather
+    # per step every kernel runs once per sigma point, so the flops of the per-point pass are those of one step
+    step_exec = {k: v * args.steps for k, v in exec_total.items()}
     roofline = dict(bound="mfma", kernel=KERNEL_OF_TIMER[dom], achieved=round(achieved, 1), peak=MFMA_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / MFMA_PEAK_TFLOPS, 4),
-                    traffic=(HBM_TRAFFIC_BYTES.get(dom) if (args.sigmas == "1,2,3,4" and not args.small
-                                                           and args.block_rho == 0.0 and not args.no_gather) else None),
-                    avg_launch_ms=round(dom_avg_ms, 3),
-                    kernels={k: dict(avg_ms=round(v[0] / v[1], 3), launches=v[1],
-                                     tflops=(round(exec_total[k] / len(points) / (v[0] / v[1] * 1e-3) / 1e12, 1)
-                                             if k in exec_total else None)) for k, v in kt.items()})
+                    # HBM bytes per launch are not measured inside this run (they need hardware counters);
+                    # the figure of the committed rocprofv3 passes for this kernel and workload is quoted beside it
+                    traffic=None,
+                    traffic_profiled=(dict(bytes=HBM_TRAFFIC_BYTES.get(dom), source="profiles/bench_c3_n16k_counters.md")
+                                      if default_mix and HBM_TRAFFIC_BYTES.get(dom) else None),
+                    avg_launch_ms=round(dom_avg_ms, 3), kernels=kernel_table(kt, step_exec))
 
     # the same matrix cores without any of the kernels' other work, for context: Gaussian operands,
     # sustained; `peak` above stays the published figure
@@ -332,6 +370,36 @@ def main():
                             sample=f"float64 oracle, forward+backward, {n_heads} whole heads (b=0, h<{n_heads}) of the "
                                    f"sigma={src['sigma']:g} batch ({n_heads} of {B * H} heads of one of {len(points)} batches)")
 
+    # ---- beside the timed line (none of this enters `value`) --------------------------------------
+    extra = {}
+    if not args.brief and args.block_rho == 0.0:
+        # (a) the same sweep on block-correlated rows (the 64 rows of a query tile share a direction):
+        #     the high block-sparsity end that i.i.d. rows cannot reach at this length
+        del points
+        torch.cuda.empty_cache()
+        bc_points = make_points(0.98, keep_cpu=False)
+        step(bc_points)
+        torch.cuda.synchronize()
+        bc_rows, bc_kt = measure_points(bc_points)
+        bc_sweep, bc_exec = sweep_rows(bc_points, bc_rows)
+        extra["sweep_block_correlated"] = dict(generator="block-correlated rho=0.98", sweep=bc_sweep,
+                                               kernels=kernel_table(bc_kt, bc_exec))
+        # (b) every row group on the block-sparse matrix kernels of Alg. 1-3 (gather paths off), same
+        #     inputs: what out / dq / dkdv reach where the backward is theirs
+        if not args.no_gather:
+            ea.entmax_attn_gather_enable(False)
+            step(bc_points)
+            torch.cuda.synchronize()
+            off_rows, off_kt = measure_points(bc_points)
+            ea.entmax_attn_gather_enable(True)
+            off_sweep, off_exec = sweep_rows(bc_points, off_rows)
+            extra["matrix_kernels_gather_off"] = dict(generator="block-correlated rho=0.98", sweep=off_sweep,
+                                                      kernels=kernel_table(off_kt, off_exec))
+        del bc_points
+        torch.cuda.empty_cache()
+        # (c) context scaling at a fixed token budget (second workload), three steps per length
+        extra["context"] = context_rows(ea, workloads, dev, steps=3, warmup=1)
+
     out = dict(metric=METRIC, value=round(value, 2), unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=round(ms_per_step, 3), higher_is_better=True, scaling="weak", vs_baseline=None,
                dtype="bf16", data="synthetic",
@@ -340,7 +408,7 @@ def main():
                            step="forward+backward over each sigma batch", histogram_bins=ea.entmax_attn_histogram_bins(),
                            gather_paths=not args.no_gather),
                mean_tau_iters=round(float(np.mean([pp["iters"] for pp in per_point])), 3),
-               sweep=sweep, roofline=roofline, cpu_baseline=cpu_baseline)
+               sweep=sweep, roofline=roofline, cpu_baseline=cpu_baseline, **extra)
     print(json.dumps(out), flush=True)
 
 
