@@ -233,9 +233,23 @@ int entmax_attn_gather_enable(int on);
  */
 int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters, void* hip_stream);
 
-/* Histogram bins B and work-group query rows used by the threshold kernel (introspection for
- * tests and the benchmark report). */
+/* Histogram bins B per unit of (alpha-1) s used by the threshold kernels (introspection for tests
+ * and the benchmark report): the bracket after the histogram solve is 1/B wide (Prop. 1). */
 int entmax_attn_histogram_bins(void);
+
+/*
+ * What the histogram stage alone produced in the last entmax_attn_fwd call that used `workspace`
+ * (Eq. 6-9, App. C.3, before any refinement; for tests of Prop. 1): per row, in the raw convention
+ * of `tau`,
+ *   tau0   out [B,H,N] float32: max(tau_h, max - 1) less a rounding slack of about 1e-6 - the point
+ *                              the refinement starts from, never above the true threshold;
+ *   upper  out [B,H,N] float32: tau_h + 1/B plus the same slack - the bracket's upper end.
+ * Copies the two arrays out of the workspace on `hip_stream` (device to device, nothing allocated).
+ * Shape arguments as in the forward call; error codes as above.
+ */
+int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes,
+                                     int B, int H, int N, int d, ea_dtype dtype,
+                                     float* tau0, float* upper, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -72,6 +72,8 @@ def lib():
         L.entmax_attn_decode_static_max_bytes.argtypes = []
         L.entmax_attn_decode_static.restype = ci
         L.entmax_attn_decode_static.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, vp]
+        L.entmax_attn_fwd_histogram_bounds.restype = ci
+        L.entmax_attn_fwd_histogram_bounds.argtypes = [vp, sz, ci, ci, ci, ci, ci, vp, vp, vp]
         L.entmax_attn_mfma_probe.restype = ci
         L.entmax_attn_mfma_probe.argtypes = [vp, vp, ci, ci, vp]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
@@ -167,6 +169,17 @@ def entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=False, workspace=None):
     _check(rc)
     entmax_attn_fwd.last_workspace = ws
     return (O, tau, mask, iters) if want_iters else (O, tau, mask)
+
+
+def entmax_attn_fwd_histogram_bounds(workspace, B, H, N, d, dtype):
+    """-> (tau0, upper) [B,H,N]: what the histogram stage alone gave in the last forward call that
+    used `workspace` (start of the refinement and upper end of its bracket, raw convention)."""
+    dev = workspace.device
+    tau0 = torch.empty((B, H, N), dtype=torch.float32, device=dev)
+    upper = torch.empty_like(tau0)
+    _check(lib().entmax_attn_fwd_histogram_bounds(_ptr(workspace), workspace.numel(), B, H, N, d, _dtype_code(dtype),
+                                                  _ptr(tau0), _ptr(upper), ctypes.c_void_p(torch.cuda.current_stream(dev).cuda_stream)))
+    return tau0, upper
 
 
 def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspace=None):

@@ -40,7 +40,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 bool g_gather_enabled = true;
 
 struct Layout {
-    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, rs_t0, rs_up0, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
 };
 
 // element size of the stage-2 copies
@@ -59,6 +59,8 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.rs_hi = off; off += align256(BH * N * 4);
     L.rs_f1 = off; off += align256(BH * N * 4);
     L.rs_state = off; off += align256(BH * N * 4);
+    L.rs_t0 = off; off += align256(BH * N * 4);                  // tau_0 and bracket end of the histogram stage
+    L.rs_up0 = off; off += align256(BH * N * 4);
     L.oflag = off; off += align256(BH * T * 4);                  // 64-row blocks whose candidate lists overflowed
     L.scnt = off; off += align256(BH * N * 2 * 4);               // support entries at the front of each list
     L.gflag = off; off += align256(BH * ((size_t)N / 128 + 1) * 4);   // row groups that take the gather kernel
@@ -245,6 +247,7 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
     p.scnt = (int32_t*)(ws + L.scnt);
     p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
+    p.rs_t0 = (float*)(ws + L.rs_t0); p.rs_up0 = (float*)(ws + L.rs_up0);
     p.scal = (unsigned int*)(ws + L.stats + STATS_BYTES);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
@@ -325,6 +328,19 @@ int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, 
                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!alpha_per_head) return EA_ERR_NULL;
     return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
+}
+
+int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d, ea_dtype t,
+                                     float* tau0, float* upper, void* hip_stream) {
+    if (!workspace || !tau0 || !upper) return EA_ERR_NULL;
+    const int rc = check_common(B, H, N, d, t, 1.5f);
+    if (rc) return rc;
+    const Layout L = fwd_layout(B, H, N, d, t);
+    if (((uintptr_t)workspace & 255) || workspace_bytes < L.total) return EA_ERR_WORKSPACE;
+    const size_t bytes = (size_t)B * H * N * sizeof(float);
+    EA_HIP(hipMemcpyAsync(tau0, (const char*)workspace + L.rs_t0, bytes, hipMemcpyDeviceToDevice, (hipStream_t)hip_stream));
+    EA_HIP(hipMemcpyAsync(upper, (const char*)workspace + L.rs_up0, bytes, hipMemcpyDeviceToDevice, (hipStream_t)hip_stream));
+    return EA_OK;
 }
 
 int entmax_attn_gather_enable(int on) {

@@ -43,6 +43,7 @@ struct Params {
     int32_t* wmask;       // working mask (superset) [BH][T][W]
     int32_t* iters;       // nullable
     float* rs_lo; float* rs_hi; float* rs_f1; int* rs_state;   // [BH][N] solver state handed from tau_kernel to out_kernel
+    float* rs_t0; float* rs_up0;   // [BH][N] what the histogram stage alone gave: tau_0 and the bracket's upper end (read out by tests)
     _Float16* tmax;       // [BH][T][N] per-row key-tile maxima of the raw scores (forward scratch)
     void* lists;          // [BH][N][2][LIST_CAP] candidate scores (raw score, key index), 8 bytes each
     int32_t* scnt;        // [BH][N][2] entries at the front of each list that are in the support at the final tau

@@ -314,6 +314,10 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             thr[qb] = mine ? my_t0 : o_t0;
             blo[qb] = thr[qb];
             bhi[qb] = mine ? my_hi : o_hi;
+            if (active && h == 0) {
+                p.rs_t0[(long)bh * N + qw0 + 32 * qb + n] = thr[qb];
+                p.rs_up0[(long)bh * N + qw0 + 32 * qb + n] = bhi[qb];
+            }
         }
     }
     // candidate tiles of this wave's rows: those holding a score above tau_0.  64 tiles per
@@ -660,6 +664,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
     if (active) {
         float blo[QB], bhi[QB];
         histogram_bound(thr, bhi, false);
+        if (h == 0) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) {
+                p.rs_t0[(long)bh * N + qw0 + 32 * qb + n] = thr[qb];
+                p.rs_up0[(long)bh * N + qw0 + 32 * qb + n] = bhi[qb];
+            }
+        }
         float f1_last[QB];
         int nmax = 0;
 #pragma unroll
