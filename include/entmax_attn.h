@@ -18,8 +18,9 @@
  *     contiguous [B, H, N, d] with d fastest.  Inputs Q, K, V, dO have the element type
  *     named by `dtype`; O, dQ, dK, dV, tau are always float32.
  *   - N must be a positive multiple of 64 and at most 131072; d must be 64 or 128;
- *     1 < alpha <= 2.  With bf16 inputs, values of magnitude 65504 or more are outside the
- *     library's domain (second-stage products run on fp16 copies).
+ *     1 < alpha <= 2.  With bf16 inputs, values of magnitude above 65504 are outside the
+ *     library's domain (second-stage products run on fp16 copies): they enter those copies as
+ *     +-65504 and are counted in EA_STAT_F16_CLAMPED.
  *   - Causal masking: key j is visible to query r iff j <= r.
  *   - The library allocates nothing and never synchronises: all work is enqueued on
  *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).  Scratch
@@ -70,7 +71,8 @@ enum {
     EA_STAT_LIST_OVERFLOW = 8, /* 64-row blocks whose candidate lists overflowed (redone by the sweep-based kernel) */
     EA_STAT_GATHER_ROWS = 9,  /* rows whose output was gathered from their listed support (no output-phase matmuls) */
     EA_STAT_BWD_LIST_TILES = 10, /* sub-tiles scored when the backward lists the supports of sparse row groups (1 matmul each) */
-    EA_STAT_BWD_GATHER_ROWS = 11 /* rows whose gradients were formed entry by entry from their listed support */
+    EA_STAT_BWD_GATHER_ROWS = 11, /* rows whose gradients were formed entry by entry from their listed support */
+    EA_STAT_F16_CLAMPED = 12  /* bf16 input values of magnitude above 65504 that were copied as +-65504 into the fp16 operands of the matrix kernels: non-zero means the inputs were outside the library's domain */
 };
 
 /* Edge of the square score tiles that one bit of the block mask stands for (64). */
@@ -83,7 +85,8 @@ size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, i
 /*
  * Forward (Alg. 1): row maximum, histogram and candidate lists (one dense sweep) -> histogram
  * solve and refinement on the lists (+ working mask) -> output, whose row sums check f once more.
- * Rows with more candidates than a list holds (512 per row) are redone by sweep-based refinement.
+ * A 64-row block with a row that has more candidates than its two lists hold (256 each, one per
+ * half of the lanes that computed its scores) is redone by the sweep-based threshold kernel.
  *   Q, K, V     in   [B,H,N,d] of `dtype`
  *   O           out  [B,H,N,d] float32
  *   tau         out  [B,H,N]   float32, raw convention: P = [(alpha-1) S - tau]_+^{1/(alpha-1)}
@@ -151,9 +154,11 @@ int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, 
  *   tau         out  [B,H]   float32, raw convention as in entmax_attn_fwd
  *   support     out  [B,H]   int32, may be NULL: number of keys with p > 0
  *   iters       out  [B,H]   int32, may be NULL: evaluations of f the refinement took
- * The logits are written to the workspace (N floats per head) by a kernel that reads K once; a second
- * kernel solves tau per head (histogram of the scores within one unit of the maximum, Eq. 5-9, then
- * the hybrid refinement of Sec. 3.2) and gathers the rows of V in the support.  Conventions, error
+ * A first kernel reads K once and keeps, per work-group, only the logits within the window of Eq. 5
+ * below the largest logit it has met so far (value and key index, in per-group lists in the workspace)
+ * and its own maximum; a second kernel solves tau per head from the kept logits (histogram of the
+ * scores within one unit of the maximum, Eq. 5-9, then the hybrid refinement of Sec. 3.2) and gathers
+ * the rows of V in the support.  Conventions, error
  * codes and workspace rules as above; entmax_attn_decode_workspace_bytes returns 0 for a bad shape.
  */
 size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype);
@@ -187,69 +192,9 @@ const char* entmax_attn_strerror(int code);
  * thread, 0 if none. */
 int entmax_attn_last_hip_error(void);
 
-/*
- * Optional per-kernel timing (measurement aid, used by the benchmark; Sec. 4.2 reports forward
- * and backward times separately).  While enabled, every entmax_attn_fwd / entmax_attn_bwd call
- * records HIP events on its stream around each of its kernels, for up to 256 calls between
- * reads.  entmax_attn_timer_read waits for the recorded events, writes per slot the summed
- * kernel time in ms and the number of launches (arrays of at least EA_TIMER_SLOTS entries), and
- * starts a new recording window.  Enabling creates the events once; not thread-safe.
- */
-#define EA_TIMER_SLOTS 10
-enum {
-    EA_TIMER_FWD_PREP = 0,  /* fp16 copy of V (bf16 inputs; made after the threshold kernel, and only if some row group needs it) */
-    EA_TIMER_TAU = 1,       /* dense sweep (maximum, histogram, candidate lists), solve, refinement; fallback kernel */
-    EA_TIMER_OUT = 2,       /* phase 4 (gather over listed supports, block-sparse matrix products) and the rest of the refinement */
-    EA_TIMER_MASK = 3,      /* mask rebuild of the backward (only when block_mask == NULL) */
-    EA_TIMER_BWD_PREP = 4,  /* max |dO| (rounded up to a power of two) and the fp16 copies of K, Q, V, dO (bf16 inputs) */
-    EA_TIMER_DQ = 5,        /* delta and dQ, one sweep */
-    EA_TIMER_DKDV = 6,      /* dK, dV */
-    EA_TIMER_DECODE_SCORES = 7, /* entmax_attn_decode: the kernel that reads K and keeps the logits near the maximum */
-    EA_TIMER_BWD_LIST = 8,  /* backward: supports of the sparse row groups listed (one matrix product per marked tile) */
-    EA_TIMER_BWD_GATHER = 9 /* backward of the sparse row groups from their lists: rows (dQ, delta), then keys (dK, dV), then the entries of overfull keys */
-};
-int entmax_attn_timer_enable(int on);
-int entmax_attn_timer_read(float* ms_sum, int* launches, int slots);
-
-/*
- * Sparse row groups (a handful of non-zeros per row: the regime Sec. 4 reports at long context)
- * are by default not run through the block-sparse matrix kernels of Alg. 1-3 but evaluated entry by
- * entry from lists of each row's support: forward, O_r as a sum over a few rows of V; backward,
- * dQ row by row and dK, dV key by key (EA_STAT_GATHER_ROWS, EA_STAT_BWD_GATHER_ROWS count the rows
- * that went that way).  Results are the same up to rounding.  entmax_attn_gather_enable(0) keeps
- * every row group on the matrix kernels (measurement and test aid; process-wide, applies to the
- * calls made after it); returns EA_OK.
- */
-int entmax_attn_gather_enable(int on);
-
-/*
- * Matrix-core rate probe (measurement aid: the ceiling the benchmark prices the kernels against
- * besides the published peak).  Launches `groups` work-groups of 4 wavefronts; every wavefront
- * issues iters * 32 independent 32x32x16 fp16 MFMAs (32768 flops each) on operands taken from
- * `data` (device pointer to 8192 fp16 values filled by the caller; the sustained clock depends on
- * the operand values) and writes one float per thread to `sink` (groups * 256 floats).  256 groups
- * put one wavefront on every SIMD of an MI355X, 512 two.  The caller times the launch.
- * Total flops = groups * 4 * iters * 32 * 32768.
- */
-int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters, void* hip_stream);
-
-/* Histogram bins B per unit of (alpha-1) s used by the threshold kernels (introspection for tests
- * and the benchmark report): the bracket after the histogram solve is 1/B wide (Prop. 1). */
-int entmax_attn_histogram_bins(void);
-
-/*
- * What the histogram stage alone produced in the last entmax_attn_fwd call that used `workspace`
- * (Eq. 6-9, App. C.3, before any refinement; for tests of Prop. 1): per row, in the raw convention
- * of `tau`,
- *   tau0   out [B,H,N] float32: max(tau_h, max - 1) less a rounding slack of about 1e-6 - the point
- *                              the refinement starts from, never above the true threshold;
- *   upper  out [B,H,N] float32: tau_h + 1/B plus the same slack - the bracket's upper end.
- * Copies the two arrays out of the workspace on `hip_stream` (device to device, nothing allocated).
- * Shape arguments as in the forward call; error codes as above.
- */
-int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes,
-                                     int B, int H, int N, int d, ea_dtype dtype,
-                                     float* tau0, float* upper, void* hip_stream);
+/* Measurement and test aids (per-kernel timers, the gather switch, the matrix-core rate probe, the
+ * histogram stage's read-out) are declared in entmax_attn_aids.h: none of them is needed to use the
+ * library. */
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,8 @@ EA_F32, EA_BF16 = 0, 1
 EA_STATS_WORDS = 16
 EA_STATS_COPIES = 64
 STAT_NAMES = ("tau_subtiles", "out_subtiles", "delta_subtiles", "dq_subtiles", "dkdv_subtiles",
-              "sweeps", "mask_subtiles", "out_pv_subtiles", "list_overflow_blocks", "gather_rows", "bwd_list_subtiles", "bwd_gather_rows")
+              "sweeps", "mask_subtiles", "out_pv_subtiles", "list_overflow_blocks", "gather_rows", "bwd_list_subtiles", "bwd_gather_rows",
+              "f16_clamped")
 EA_TIMER_SLOTS = 10
 TIMER_NAMES = ("fwd_prep", "tau", "out", "mask", "bwd_prep", "dq", "dkdv", "decode_scores", "bwd_list", "bwd_gather")
 

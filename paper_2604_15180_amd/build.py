@@ -14,7 +14,8 @@ LIB = os.path.join(HERE, "libentmax_attn.so")
 UNITS = ["api", "decode", "inst_bf16_d64", "inst_bf16_d128", "inst_f32_d64", "inst_f32_d128"]
 HEADERS = [os.path.join(CSRC, f) for f in
            ("tiles.hpp", "common.hpp", "fwd_kernels.hpp", "bwd_kernels.hpp", "launch.hpp", "ops.hpp")] + [
-    os.path.join(os.path.dirname(HERE), "include", "entmax_attn.h")]
+    os.path.join(os.path.dirname(HERE), "include", "entmax_attn.h"),
+    os.path.join(os.path.dirname(HERE), "include", "entmax_attn_aids.h")]
 
 BASE = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -21,7 +21,7 @@ struct KernelTimer {
     int ncalls = 0;                                   // calls recorded since the last reset
     hipEvent_t ev[TIMER_MAX_CALLS][TIMER_SLOTS][2];
     unsigned char used[TIMER_MAX_CALLS][TIMER_SLOTS];
-    bool created = false;
+    unsigned char created[TIMER_MAX_CALLS][TIMER_SLOTS];    // events exist (made when a slot is first recorded, kept)
 } g_timer;
 int g_timer_call = -1;                                // slot row of the call in flight, -1 = off
 
@@ -37,7 +37,7 @@ static_assert(STATS_WORDS == EA_STATS_WORDS && STATS_COPIES == EA_STATS_COPIES, 
 constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-bool g_gather_enabled = true;
+thread_local bool g_gather_enabled = true;      // the gather switch of the calling host thread
 
 struct Layout {
     size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, rs_t0, rs_up0, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
@@ -181,6 +181,11 @@ void set_last_hip_error(int e) { g_last_hip_error = e; }
 void timer_begin() { timer_begin_call(); }
 void timer_mark(int slot, int which, hipStream_t s) {
     if (g_timer_call < 0) return;
+    if (!g_timer.created[g_timer_call][slot]) {
+        if (hipEventCreate(&g_timer.ev[g_timer_call][slot][0]) != hipSuccess) return;
+        if (hipEventCreate(&g_timer.ev[g_timer_call][slot][1]) != hipSuccess) { (void)hipEventDestroy(g_timer.ev[g_timer_call][slot][0]); return; }
+        g_timer.created[g_timer_call][slot] = 1;
+    }
     (void)hipEventRecord(g_timer.ev[g_timer_call][slot][which], s);
     if (which == 1) g_timer.used[g_timer_call][slot] = 1;
 }
@@ -349,12 +354,6 @@ int entmax_attn_gather_enable(int on) {
 }
 
 int entmax_attn_timer_enable(int on) {
-    if (on && !g_timer.created) {
-        for (int c = 0; c < TIMER_MAX_CALLS; ++c)
-            for (int k = 0; k < TIMER_SLOTS; ++k)
-                for (int e = 0; e < 2; ++e) EA_HIP(hipEventCreate(&g_timer.ev[c][k][e]));
-        g_timer.created = true;
-    }
     g_timer.enabled = on != 0;
     g_timer.ncalls = 0;
     g_timer_call = -1;

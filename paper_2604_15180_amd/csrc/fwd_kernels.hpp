@@ -8,6 +8,8 @@
 // One work-group = 32*QB*NW query rows of one head; wave w owns rows 32*QB*w .. of them as MFMA
 // B operands in registers; 64-key tiles of K (and V) stream through LDS.
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace ea {
@@ -1108,18 +1110,37 @@ static __global__ void full_mask_kernel(int32_t* wmask, int BH, int T, int W, in
 }
 
 // Element-wise copy into another element type, optionally divided by a (bits of a float a >= 0).
+// A value whose magnitude the narrower type cannot hold (fp16: 65504) is copied as the largest finite
+// value of its sign and counted in *clamped (so that the caller can see that the result is not the
+// one of its inputs: the fp16 copies are the operands of every second-stage product).
 template <class Ein, class Eout>
 __global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* in, typename Eout::elem* out, long n,
-                                                      const unsigned int* amax_bits, const int32_t* needed) {
+                                                      const unsigned int* amax_bits, const int32_t* needed,
+                                                      unsigned long long* clamped) {
     if (needed && *needed == 0) return;     // nobody will read the copy
     float mul = 1.f;
     if (amax_bits) {
         const float a = __uint_as_float(*amax_bits);
         if (a > 0.f) mul = 1.f / a;
     }
+    constexpr bool NARROW = std::is_same<Eout, F16>::value && !std::is_same<Ein, F16>::value;
+    int nclamped = 0;
     for (long i = (blockIdx.x * 256L + threadIdx.x) * 8; i < n; i += (long)gridDim.x * 256 * 8) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) out[i + e] = Eout::from_float((float)in[i + e] * mul);
+        for (int e = 0; e < 8; ++e) {
+            float x = (float)in[i + e] * mul;
+            if constexpr (NARROW) {
+                if (fabsf(x) > 65504.f) { x = copysignf(65504.f, x); ++nclamped; }     // (NaN compares false and stays NaN)
+            }
+            out[i + e] = Eout::from_float(x);
+        }
+    }
+    if constexpr (NARROW) {
+        if (__any(nclamped != 0)) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) nclamped += __shfl_xor(nclamped, off);
+            if ((threadIdx.x & 63) == 0 && clamped) atomicAdd(clamped, (unsigned long long)nclamped);
+        }
     }
 }
 

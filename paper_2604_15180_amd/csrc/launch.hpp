@@ -4,7 +4,7 @@
 // The kernels are instantiated in one translation unit per (type, head dim): they compile in
 // parallel, and each type gets the code-generation flags that suit it.
 #pragma once
-#include "../../include/entmax_attn.h"
+#include "../../include/entmax_attn_aids.h"
 #include "common.hpp"
 
 namespace ea {

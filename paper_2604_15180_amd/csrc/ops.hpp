@@ -44,9 +44,11 @@ int launch(K kernel, dim3 grid, int threads, hipStream_t s, Params p) {
 }
 
 template <class Ein, class Eout>
-int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, const int32_t* needed, hipStream_t s) {
+int launch_convert(const void* in, void* out, long n, const unsigned int* amax_bits, const int32_t* needed,
+                   unsigned long long* stats, hipStream_t s) {
+    // values clamped on the way into the narrower type are counted in the first copy of the counters
     hipLaunchKernelGGL((convert_kernel<Ein, Eout>), dim3(2048), dim3(256), 0, s, (const typename Ein::elem*)in,
-                       (typename Eout::elem*)out, n, amax_bits, needed);
+                       (typename Eout::elem*)out, n, amax_bits, needed, stats + EA_STAT_F16_CLAMPED);
     EA_HIP(hipGetLastError());
     return EA_OK;
 }
@@ -88,7 +90,7 @@ struct Ops {
             ScopedKernelTime t(EA_TIMER_FWD_PREP, s);
             if (COPY) {
                 rc = launch_convert<E, E2>(p.V, const_cast<void*>(p.V2), (long)p.BH * p.N * D, nullptr,
-                                           p.gflag ? (const int32_t*)(p.scal + 1) : nullptr, s);
+                                           p.gflag ? (const int32_t*)(p.scal + 1) : nullptr, p.stats, s);
                 if (rc) return rc;
             }
         }
@@ -140,10 +142,10 @@ struct Ops {
             }
             if (COPY) {
                 const long n = (long)p.BH * p.N * D;
-                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, needed, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, needed, p.stats, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, needed, p.stats, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, needed, p.stats, s))) return rc;
+                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, needed, p.stats, s))) return rc;
                 p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
             }
         }

@@ -9,7 +9,7 @@ import pytest
 import paper_2604_15180_amd as ea
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-HEADER = os.path.join(ROOT, "include", "entmax_attn.h")
+HEADERS = [os.path.join(ROOT, "include", "entmax_attn.h"), os.path.join(ROOT, "include", "entmax_attn_aids.h")]
 
 
 @pytest.fixture(scope="module")
@@ -21,9 +21,11 @@ def L():
 
 
 def declared_symbols():
-    text = open(HEADER).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(entmax_attn_\w+)\s*\(", text)))
+    names = set()
+    for header in HEADERS:
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(entmax_attn_\w+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(L):

@@ -348,3 +348,65 @@ def test_c4_shape_planted_keys(ea):
     sparsity = 1.0 - (ref["margin"] > 0).sum() / (2 * 64 * 65 / 2)
     print("  planted: block sparsity", sparsity, info, ginfo, flush=True)
     assert sparsity > 0.5
+
+
+def test_backward_twice_gives_the_same_gradients(ea):
+    # run-to-run stability.  The matrix kernels accumulate in a fixed order: bit-identical.  On the
+    # gather path a key's entries are filed in the order an integer atomic hands out slots and the
+    # entries of overfull keys arrive as fp32 atomic additions, so dK, dV may differ in the last bits
+    # between runs; dQ is formed row by row in list order and must not.
+    B, H, N, d, alpha, causal, sigma = 1, 2, 3072, 128, 1.5, False, 3.0
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sigma, seed=97)
+    g = torch.Generator().manual_seed(98)
+    dirn = torch.randn(d, generator=g)
+    dirn = dirn / dirn.norm()
+    amp = (sigma * sigma * 3.5 * d ** 0.5) ** 0.5
+    q = (q.float() + amp * dirn).to(q.dtype)
+    k = k.clone()
+    k[:, :, 11] = (k[:, :, 11].float() + amp * dirn).to(k.dtype)        # one hub key: more entries than its list holds
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    O, tau, mask = ea.entmax_attn_fwd(Q, K, V, alpha, causal)
+    try:
+        for on in (True, False):
+            ea.entmax_attn_gather_enable(on)
+            ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
+            runs = []
+            for rep in range(2):
+                runs.append(ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws))
+                torch.cuda.synchronize()
+            rows = ea.read_stats(ws)["bwd_gather_rows"]
+            spread = {n_: ((a - b).abs() / (1 + a.abs())).max().item() for n_, a, b in zip(("dQ", "dK", "dV"), runs[0], runs[1])}
+            print(f"  gather paths {'on' if on else 'off'}: rows by gather {rows}, spread between two runs {spread}", flush=True)
+            assert (rows > 0) == on
+            assert spread["dQ"] == 0.0
+            if on:
+                assert spread["dK"] <= 1e-5 and spread["dV"] <= 1e-5
+            else:
+                assert spread["dK"] == 0.0 and spread["dV"] == 0.0
+    finally:
+        ea.entmax_attn_gather_enable(True)
+
+
+def test_values_beyond_fp16_range_are_clamped_and_counted(ea):
+    # bf16 inputs above 65504 do not fit the fp16 operands of the matrix kernels: they are copied as
+    # +-65504 and counted, so that the caller can tell; in-range inputs count nothing
+    B, H, N, d, alpha, causal = 1, 1, 256, 64, 1.5, True
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", 1.0, seed=99)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    try:
+        ea.entmax_attn_gather_enable(False)            # the matrix kernels, which need the copies, serve every row
+        for big in (False, True):
+            V2 = V.clone()
+            if big:
+                V2[0, 0, 3, 5] = 1.0e5
+                V2[0, 0, 9, 7] = -2.0e5
+            O, tau, mask = ea.entmax_attn_fwd(Q, K, V2, alpha, causal)
+            wf = ea.entmax_attn_fwd.last_workspace
+            ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
+            ea.entmax_attn_bwd(Q, K, V2, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws)
+            torch.cuda.synchronize()
+            got = (ea.read_stats(wf)["f16_clamped"], ea.read_stats(ws)["f16_clamped"])
+            print("  clamped values counted (forward, backward):", got, flush=True)
+            assert got == ((2, 2) if big else (0, 0))
+    finally:
+        ea.entmax_attn_gather_enable(True)
