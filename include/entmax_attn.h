@@ -40,6 +40,8 @@
 extern "C" {
 #endif
 
+/* Element type of Q, K, V, dO.  Entry points take it as a plain int (any other value is answered
+ * with EA_ERR_DTYPE, or a size of 0). */
 typedef enum { EA_F32 = 0, EA_BF16 = 1 } ea_dtype;
 
 enum {
@@ -80,7 +82,7 @@ int entmax_attn_mask_tile(void);
 
 /* Bytes of workspace needed by entmax_attn_fwd (is_bwd == 0) or entmax_attn_bwd
  * (is_bwd != 0) for this problem; 0 if the shape or dtype is invalid. */
-size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, int causal, int is_bwd);
+size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, int dtype, int causal, int is_bwd);
 
 /*
  * Forward (Alg. 1): row maximum, histogram and candidate lists (one dense sweep) -> histogram
@@ -103,7 +105,7 @@ size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype, i
  */
 int entmax_attn_fwd(const void* Q, const void* K, const void* V,
                     float* O, float* tau, int32_t* block_mask, int32_t* iters,
-                    int B, int H, int N, int d, ea_dtype dtype, float alpha, int causal,
+                    int B, int H, int N, int d, int dtype, float alpha, int causal,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -121,7 +123,7 @@ int entmax_attn_fwd(const void* Q, const void* K, const void* V,
 int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                     const float* tau, const int32_t* block_mask,
                     float* dQ, float* dK, float* dV,
-                    int B, int H, int N, int d, ea_dtype dtype, float alpha, int causal,
+                    int B, int H, int N, int d, int dtype, float alpha, int causal,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -135,12 +137,12 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
  */
 int entmax_attn_fwd_alpha_per_head(const void* Q, const void* K, const void* V,
                                    float* O, float* tau, int32_t* block_mask, int32_t* iters,
-                                   int B, int H, int N, int d, ea_dtype dtype, const float* alpha_per_head, int causal,
+                                   int B, int H, int N, int d, int dtype, const float* alpha_per_head, int causal,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                                    const float* tau, const int32_t* block_mask,
                                    float* dQ, float* dK, float* dV,
-                                   int B, int H, int N, int d, ea_dtype dtype, const float* alpha_per_head, int causal,
+                                   int B, int H, int N, int d, int dtype, const float* alpha_per_head, int causal,
                                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -161,10 +163,10 @@ int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, 
  * the rows of V in the support.  Conventions, error
  * codes and workspace rules as above; entmax_attn_decode_workspace_bytes returns 0 for a bad shape.
  */
-size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype dtype);
+size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, int dtype);
 int entmax_attn_decode(const void* q, const void* K, const void* V,
                        float* O, float* tau, int32_t* support, int32_t* iters,
-                       int B, int H, int N, int d, ea_dtype dtype, float alpha,
+                       int B, int H, int N, int d, int dtype, float alpha,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
@@ -183,7 +185,7 @@ int entmax_attn_decode(const void* q, const void* K, const void* V,
 size_t entmax_attn_decode_static_max_bytes(void);
 int entmax_attn_decode_static(const void* q, const void* K, const void* V,
                               float* O, float* tau, int32_t* support, int32_t* iters,
-                              int B, int H, int N, int d, ea_dtype dtype, float alpha, void* hip_stream);
+                              int B, int H, int N, int d, int dtype, float alpha, void* hip_stream);
 
 /* Static, human-readable text for a return code. */
 const char* entmax_attn_strerror(int code);

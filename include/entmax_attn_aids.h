@@ -78,7 +78,7 @@ int entmax_attn_histogram_bins(void);
  * Shape arguments as in the forward call; error codes as above.
  */
 int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes,
-                                     int B, int H, int N, int d, ea_dtype dtype,
+                                     int B, int H, int N, int d, int dtype,
                                      float* tau0, float* upper, void* hip_stream);
 
 #ifdef __cplusplus

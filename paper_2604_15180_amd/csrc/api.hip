@@ -44,9 +44,9 @@ struct Layout {
 };
 
 // element size of the stage-2 copies
-inline size_t t_elem(ea_dtype t) { return t == EA_BF16 ? 2 : 4; }
+inline size_t t_elem(int t) { return t == EA_BF16 ? 2 : 4; }
 
-Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
+Layout fwd_layout(int B, int H, int N, int d, int t) {
     Layout L{};
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
@@ -68,7 +68,7 @@ Layout fwd_layout(int B, int H, int N, int d, ea_dtype t) {
     L.total = off;
     return L;
 }
-Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
+Layout bwd_layout(int B, int H, int N, int d, int t) {
     Layout L{};
     const size_t BH = (size_t)B * H, T = N / 64, W = (T + 31) / 32;
     size_t off = 0;
@@ -95,7 +95,7 @@ Layout bwd_layout(int B, int H, int N, int d, ea_dtype t) {
 
 bool alpha_ok(float alpha) { return isfinite(alpha) && alpha > 1.f && alpha <= 2.f; }
 
-int check_common(int B, int H, int N, int d, ea_dtype t, float alpha) {
+int check_common(int B, int H, int N, int d, int t, float alpha) {
     if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
     if (B <= 0 || H <= 0 || N <= 0 || N % 64 != 0 || N > 131072 || (d != 64 && d != 128)) return EA_ERR_SHAPE;
     if ((long)B * H > 65535) return EA_ERR_SHAPE;
@@ -109,7 +109,7 @@ int check_common(int B, int H, int N, int d, ea_dtype t, float alpha) {
         if (e_ != hipSuccess) { g_last_hip_error = (int)e_; return EA_ERR_HIP; } \
     } while (0)
 
-int dispatch(bool is_bwd, ea_dtype t, int d, const Params& p, bool rebuild, void* const copies[4], hipStream_t s) {
+int dispatch(bool is_bwd, int t, int d, const Params& p, bool rebuild, void* const copies[4], hipStream_t s) {
     if (t == EA_BF16) return d == 64 ? run_bf16_d64(is_bwd, p, rebuild, copies, s) : run_bf16_d128(is_bwd, p, rebuild, copies, s);
     return d == 64 ? run_f32_d64(is_bwd, p, rebuild, copies, s) : run_f32_d128(is_bwd, p, rebuild, copies, s);
 }
@@ -138,7 +138,7 @@ __global__ void head_consts_kernel(AlphaChunk chunk, int first, int count, float
     if (i < count) table[first + i] = head_consts_of(chunk.a[i], inv_sqrt_d);
 }
 
-Params base_params(int B, int H, int N, int d, ea_dtype t, float alpha, int causal) {
+Params base_params(int B, int H, int N, int d, int t, float alpha, int causal) {
     Params p{};
     p.BH = B * H; p.N = N; p.T = N / 64; p.W = (p.T + 31) / 32;
     p.causal = causal ? 1 : 0;
@@ -197,7 +197,7 @@ int entmax_attn_mask_tile(void) { return ea::TILE; }
 int entmax_attn_histogram_bins(void) { return NBINS; }
 int entmax_attn_last_hip_error(void) { return g_last_hip_error; }
 
-size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, ea_dtype t, int causal, int is_bwd) {
+size_t entmax_attn_workspace_bytes(int B, int H, int N, int d, int t, int causal, int is_bwd) {
     (void)causal;
     if (check_common(B, H, N, d, t, 1.5f) != EA_OK) return 0;
     return is_bwd ? bwd_layout(B, H, N, d, t).total : fwd_layout(B, H, N, d, t).total;
@@ -229,7 +229,7 @@ int fill_head_table(const float* alpha_h, int H, float inv_sqrt_d, HeadConsts* t
 }
 
 int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
-             int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, const float* alpha_h, int causal,
+             int32_t* iters, int B, int H, int N, int d, int t, float alpha, const float* alpha_h, int causal,
              void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!Q || !K || !V || !O || !tau || !block_mask) return EA_ERR_NULL;
     int rc = check_common(B, H, N, d, t, alpha_h ? 1.5f : alpha);
@@ -266,7 +266,7 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
 
 int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
              const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
-             ea_dtype t, float alpha, const float* alpha_h, int causal, void* workspace, size_t workspace_bytes,
+             int t, float alpha, const float* alpha_h, int causal, void* workspace, size_t workspace_bytes,
              void* hip_stream) {
     if (!Q || !K || !V || !dO || !tau || !dQ || !dK || !dV) return EA_ERR_NULL;
     int rc = check_common(B, H, N, d, t, alpha_h ? 1.5f : alpha);
@@ -312,30 +312,30 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
 extern "C" {
 
 int entmax_attn_fwd(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
-                    int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, int causal,
+                    int32_t* iters, int B, int H, int N, int d, int t, float alpha, int causal,
                     void* workspace, size_t workspace_bytes, void* hip_stream) {
     return fwd_impl(Q, K, V, O, tau, block_mask, iters, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes, hip_stream);
 }
 int entmax_attn_fwd_alpha_per_head(const void* Q, const void* K, const void* V, float* O, float* tau, int32_t* block_mask,
-                                   int32_t* iters, int B, int H, int N, int d, ea_dtype t, const float* alpha_per_head,
+                                   int32_t* iters, int B, int H, int N, int d, int t, const float* alpha_per_head,
                                    int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!alpha_per_head) return EA_ERR_NULL;
     return fwd_impl(Q, K, V, O, tau, block_mask, iters, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
 }
 int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
                     const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
-                    ea_dtype t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                    int t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
     return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes, hip_stream);
 }
 int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                                    const float* tau, const int32_t* block_mask, float* dQ, float* dK, float* dV, int B,
-                                   int H, int N, int d, ea_dtype t, const float* alpha_per_head, int causal,
+                                   int H, int N, int d, int t, const float* alpha_per_head, int causal,
                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!alpha_per_head) return EA_ERR_NULL;
     return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, 0.f, alpha_per_head, causal, workspace, workspace_bytes, hip_stream);
 }
 
-int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d, ea_dtype t,
+int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_bytes, int B, int H, int N, int d, int t,
                                      float* tau0, float* upper, void* hip_stream) {
     if (!workspace || !tau0 || !upper) return EA_ERR_NULL;
     const int rc = check_common(B, H, N, d, t, 1.5f);

@@ -347,7 +347,7 @@ int decode_chunk(int BH, int N) {
 }
 int decode_groups(int BH, int N) { const int ch = decode_chunk(BH, N); return (N + ch - 1) / ch; }
 size_t decode_groups_bytes(int BH, int N) { return align256((size_t)BH * decode_groups(BH, N) * 4); }
-bool decode_shape_ok(int B, int H, int N, int d, ea_dtype t) {
+bool decode_shape_ok(int B, int H, int N, int d, int t) {
     return (t == EA_F32 || t == EA_BF16) && B > 0 && H > 0 && (long)B * H <= 65535 && N > 0 && N <= (1 << 22) && (d == 64 || d == 128);
 }
 
@@ -377,7 +377,7 @@ int decode_scratch_of_current_device(void** out) {
 }
 
 int decode_check(const void* q, const void* K, const void* V, const float* O, const float* tau, int B, int H, int N, int d,
-                 ea_dtype t, float alpha) {
+                 int t, float alpha) {
     if (!q || !K || !V || !O || !tau) return EA_ERR_NULL;
     if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
     if (!decode_shape_ok(B, H, N, d, t)) return EA_ERR_SHAPE;
@@ -388,7 +388,7 @@ int decode_check(const void* q, const void* K, const void* V, const float* O, co
 
 // `workspace`: device memory of at least entmax_attn_decode_workspace_bytes(...) bytes, 256-byte aligned
 int decode_enqueue(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support, int32_t* iters,
-                   int B, int H, int N, int d, ea_dtype t, float alpha, void* workspace, void* hip_stream) {
+                   int B, int H, int N, int d, int t, float alpha, void* workspace, void* hip_stream) {
     using namespace ea;
     DecodeParams p{};
     p.q = q; p.K = K; p.V = V; p.O = O; p.tau = tau; p.support = support; p.iters = iters;
@@ -411,14 +411,14 @@ int decode_enqueue(const void* q, const void* K, const void* V, float* O, float*
 
 extern "C" {
 
-size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, ea_dtype t) {
+size_t entmax_attn_decode_workspace_bytes(int B, int H, int N, int d, int t) {
     if (!decode_shape_ok(B, H, N, d, t)) return 0;
     const int BH = B * H;
     return 2 * decode_groups_bytes(BH, N) + align256((size_t)BH * decode_groups(BH, N) * (size_t)decode_chunk(BH, N) * 8);
 }
 
 int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
-                       int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha,
+                       int32_t* iters, int B, int H, int N, int d, int t, float alpha,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {
     const int rc = decode_check(q, K, V, O, tau, B, H, N, d, t, alpha);
     if (rc) return rc;
@@ -430,7 +430,7 @@ int entmax_attn_decode(const void* q, const void* K, const void* V, float* O, fl
 size_t entmax_attn_decode_static_max_bytes(void) { return DECODE_SCRATCH_BYTES; }
 
 int entmax_attn_decode_static(const void* q, const void* K, const void* V, float* O, float* tau, int32_t* support,
-                              int32_t* iters, int B, int H, int N, int d, ea_dtype t, float alpha, void* hip_stream) {
+                              int32_t* iters, int B, int H, int N, int d, int t, float alpha, void* hip_stream) {
     const int rc = decode_check(q, K, V, O, tau, B, H, N, d, t, alpha);
     if (rc) return rc;
     if (entmax_attn_decode_workspace_bytes(B, H, N, d, t) > DECODE_SCRATCH_BYTES) return EA_ERR_TOO_LARGE;
