@@ -325,9 +325,9 @@ def test_mfma_probe_runs(ea):
         ea.entmax_attn_mfma_probe(data[:100], sink, 4, 3)
 
 
-def test_c2_shape_two_heads(ea):
-    # configs[1]: alpha=1.5 bf16 B=4 H=16 N=4096 d=64 causal sigma=1.5, on 2 of its 64 heads
-    run_case(ea, 1, 2, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
+def test_c2_exact_config(ea):
+    # configs[1] in full: alpha=1.5 bf16 B=4 H=16 N=4096 d=64 causal sigma=1.5, all 64 heads against the oracle
+    run_case(ea, 4, 16, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
 
 
 @pytest.mark.parametrize("alpha", [1.25, 2.0])
