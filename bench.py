@@ -254,7 +254,8 @@ def main():
         for pt in pts:
             O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True,
                                                       workspace=pt["ws_f"])
-            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
+            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"],
+                               fwd_workspace=pt["ws_f"])
 
     def measure_points(pts):
         """Per sigma point, outside any timed region: forward and backward time (events on the stream the
@@ -267,7 +268,8 @@ def main():
             e0.record()
             O, tau, mask, iters = ea.entmax_attn_fwd(pt["Q"], pt["K"], pt["V"], alpha, causal, want_iters=True, workspace=pt["ws_f"])
             e1.record()
-            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"])
+            ea.entmax_attn_bwd(pt["Q"], pt["K"], pt["V"], O, pt["dO"], tau, alpha, causal, block_mask=mask, workspace=pt["ws_b"],
+                               fwd_workspace=pt["ws_f"])
             e2.record()
             torch.cuda.synchronize()
             st = ea.read_stats(pt["ws_f"])

@@ -127,6 +127,27 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * entmax_attn_bwd for a caller that still holds the forward call's workspace.  The forward leaves,
+ * for every row group whose output it formed from listed supports, each row's support (raw score
+ * and key index) at the front of its candidate lists; with them the backward need not find the
+ * supports again (one score sweep over the marked tiles less).  Results as entmax_attn_bwd.
+ *   fwd_workspace  in  the workspace of the entmax_attn_fwd call (same Q, K, V, shape, dtype, alpha,
+ *                      causal) that produced O, tau and block_mask, not written to since; at least
+ *                      entmax_attn_workspace_bytes(..., is_bwd = 0) bytes, 256-byte aligned.  The
+ *                      backward reads it and leaves it as it found it.
+ *   block_mask     in  required here (the forward's).
+ * EA_ERR_NULL if fwd_workspace is NULL, EA_ERR_WORKSPACE if it is misaligned or too small or the mask
+ * is missing.  Handing over a workspace that does not belong to these tensors gives wrong gradients
+ * (or reads of rows that do not exist): the library cannot tell.
+ */
+int entmax_attn_bwd_with_lists(const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                               const float* tau, const int32_t* block_mask,
+                               void* fwd_workspace, size_t fwd_workspace_bytes,
+                               float* dQ, float* dK, float* dV,
+                               int B, int H, int N, int d, int dtype, float alpha, int causal,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * The same two operations with one alpha per head (Sec. 3.2 gives the solver for every alpha in
  * (1, 2]; heads of one layer may use different values).  `alpha_per_head` is a HOST pointer to H
  * floats, each in (1, 2]; it is read before the call returns.  Head h of every batch entry uses

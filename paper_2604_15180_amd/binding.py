@@ -55,6 +55,8 @@ def lib():
         L.entmax_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
         L.entmax_attn_bwd.restype = ci
         L.entmax_attn_bwd.argtypes = [vp] * 10 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+        L.entmax_attn_bwd_with_lists.restype = ci
+        L.entmax_attn_bwd_with_lists.argtypes = [vp] * 8 + [sz] + [vp] * 3 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
         L.entmax_attn_fwd_alpha_per_head.restype = ci
         L.entmax_attn_fwd_alpha_per_head.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, ctypes.POINTER(cf), ci, vp, sz, vp]
         L.entmax_attn_bwd_alpha_per_head.restype = ci
@@ -183,8 +185,10 @@ def entmax_attn_fwd_histogram_bounds(workspace, B, H, N, d, dtype):
     return tau0, upper
 
 
-def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspace=None):
-    """-> (dQ, dK, dV).  block_mask=None makes the library rebuild the mask from tau."""
+def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspace=None, fwd_workspace=None):
+    """-> (dQ, dK, dV).  block_mask=None makes the library rebuild the mask from tau.  fwd_workspace:
+    the forward call's workspace (entmax_attn_bwd_with_lists: the supports the forward listed are
+    used instead of being found again; single alpha only)."""
     B, H, N, d = _prep(Q, K, V, dO)
     dev = Q.device
     dQ = torch.empty((B, H, N, d), dtype=torch.float32, device=dev)
@@ -194,7 +198,14 @@ def entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=None, workspa
     ws = workspace if workspace is not None else _workspace(nbytes, dev)
     stream = torch.cuda.current_stream(dev).cuda_stream
     per_head = _alpha_array(alpha, H)
-    if per_head is None:
+    if fwd_workspace is not None:
+        if per_head is not None:
+            raise ValueError("entmax_attn_bwd: fwd_workspace goes with a single alpha")
+        rc = lib().entmax_attn_bwd_with_lists(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
+                                              _ptr(fwd_workspace), fwd_workspace.numel(), _ptr(dQ), _ptr(dK), _ptr(dV),
+                                              B, H, N, d, _dtype_code(Q.dtype), float(alpha), int(bool(causal)),
+                                              _ptr(ws), ws.numel(), ctypes.c_void_p(stream))
+    elif per_head is None:
         rc = lib().entmax_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(dO), _ptr(tau), _ptr(block_mask),
                                    _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, d, _dtype_code(Q.dtype), float(alpha),
                                    int(bool(causal)), _ptr(ws), ws.numel(), ctypes.c_void_p(stream))

@@ -267,7 +267,7 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
 int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
              const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
              int t, float alpha, const float* alpha_h, int causal, void* workspace, size_t workspace_bytes,
-             void* hip_stream) {
+             void* hip_stream, void* fwd_workspace = nullptr, size_t fwd_workspace_bytes = 0) {
     if (!Q || !K || !V || !dO || !tau || !dQ || !dK || !dV) return EA_ERR_NULL;
     int rc = check_common(B, H, N, d, t, alpha_h ? 1.5f : alpha);
     if (rc) return rc;
@@ -298,6 +298,20 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
     p.nmarked = p.nplain + 1;
     p.klist = ws + L.klist;
     p.defer = (int32_t*)(ws + L.defer);
+    p.list_cap = BWD_LIST_CAP;
+    if (fwd_workspace) {
+        // the forward's candidate lists (supports at the front), their counts and group flags
+        const Layout F = fwd_layout(B, H, N, d, t);
+        if (((uintptr_t)fwd_workspace & 255) || fwd_workspace_bytes < F.total || !block_mask) return EA_ERR_WORKSPACE;
+        if (p.gflag) {
+            char* fw = (char*)fwd_workspace;
+            p.lists = fw + F.lists;
+            p.scnt = (int32_t*)(fw + F.scnt);
+            p.fwd_gflag = (const int32_t*)(fw + F.gflag);
+            p.fwd_scal = (const unsigned int*)(fw + F.stats + STATS_BYTES);
+            p.list_cap = LIST_CAP;
+        }
+    }
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, s, p.stats, EA_STATS_WORDS * EA_STATS_COPIES, p.scal);
     EA_HIP(hipGetLastError());
     if (per_head == 2) {
@@ -326,6 +340,14 @@ int entmax_attn_bwd(const void* Q, const void* K, const void* V, const void* O, 
                     const int32_t* block_mask, float* dQ, float* dK, float* dV, int B, int H, int N, int d,
                     int t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
     return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes, hip_stream);
+}
+int entmax_attn_bwd_with_lists(const void* Q, const void* K, const void* V, const void* O, const void* dO, const float* tau,
+                               const int32_t* block_mask, void* fwd_workspace, size_t fwd_workspace_bytes,
+                               float* dQ, float* dK, float* dV, int B, int H, int N, int d,
+                               int t, float alpha, int causal, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!fwd_workspace) return EA_ERR_NULL;
+    return bwd_impl(Q, K, V, O, dO, tau, block_mask, dQ, dK, dV, B, H, N, d, t, alpha, nullptr, causal, workspace, workspace_bytes,
+                    hip_stream, fwd_workspace, fwd_workspace_bytes);
 }
 int entmax_attn_bwd_alpha_per_head(const void* Q, const void* K, const void* V, const void* O, const void* dO,
                                    const float* tau, const int32_t* block_mask, float* dQ, float* dK, float* dV, int B,

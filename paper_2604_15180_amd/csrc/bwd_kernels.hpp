@@ -798,6 +798,47 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     }
 }
 
+// When the caller hands the forward's workspace to the backward, the supports need not be found
+// again: for the row groups whose output the forward gathered, the front of its candidate lists is
+// the support (raw score, key index), with the counts beside it.  This kernel takes the place of
+// bwd_list_kernel's sweep: per row group of the backward it applies the same rule - at most so many
+// support entries per marked tile, or per row where few tiles are marked - to the forward's counts.
+template <int D, int AM>
+__global__ __launch_bounds__(128) void bwd_decide_kernel(Params p) {
+    __shared__ int gsum[2];
+    const int tid = threadIdx.x;
+    const int N = p.N, T = p.T, W = p.W, BR = p.grows, G = (N + BR - 1) / BR;
+    int bh, I;
+    map_block(blockIdx.x, p.BH, G, bh, I);
+    const int fwd_grows = (int)p.fwd_scal[2];
+    bool gather = (long)*p.nmarked * D >= (long)BWD_MIN_TILES_PER_BLOCK * 128 * p.BH * T && fwd_grows > 0
+                  && p.fwd_gflag[(long)bh * ((N + fwd_grows - 1) / fwd_grows) + (I * BR) / fwd_grows] != 0;
+    if (tid < 2) gsum[tid] = 0;
+    __syncthreads();
+    if (gather) {
+        const int row = I * BR + tid;
+        int ent = 0, marked = 0;
+        if (tid < BR && row < N) ent = p.scnt[((long)bh * N + row) * 2] + p.scnt[((long)bh * N + row) * 2 + 1];
+        const int MR = (BR + 63) / 64;
+        for (int i = tid; i < MR * W; i += 128)
+            if (I * MR + i / W < T) marked += __popc((uint32_t)p.mask[((long)bh * T + (long)I * MR + i / W) * W + (i % W)]);
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) { ent += __shfl_xor(ent, off); marked += __shfl_xor(marked, off); }
+        if ((tid & 63) == 0) { atomicAdd(&gsum[0], ent); atomicAdd(&gsum[1], marked); }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
+        constexpr int PER_ROW_X128 = BWD_ENTRIES_PER_ROW * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
+        const int budget = max(PER_TILE_X128 * gsum[1] / 128,
+                               gsum[1] <= BWD_FEW_TILES ? PER_ROW_X128 * min(BR, N - I * BR) / 128 : 0);
+        gather = gather && gsum[0] <= budget;
+        p.gflag[(long)bh * G + I] = gather;
+        if (!gather) atomicAdd(p.nplain, 1);
+        else atomicAdd(&p.stats[(blockIdx.x & (STATS_COPIES - 1)) * STATS_WORDS + 11], (unsigned long long)min(BR, N - I * BR));
+    }
+}
+
 // Sixteen lanes per row; lane `sub` holds elements [sub * D/16, (sub + 1) * D/16) of the row's
 // vectors.  SCALED: dkdv_kernel works on dO / max|dO|, so the delta handed to it is in those units.
 template <class E, int D, int AM, bool SCALED>
@@ -823,14 +864,15 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
     const elem* Kh = (const elem*)p.K + hoff + sub * EPT;
     const elem* Vh = (const elem*)p.V + hoff + sub * EPT;
     const elem* Gh = (const elem*)p.dO + hoff;
-    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * BWD_LIST_CAP * 8);
+    const int cap8 = p.list_cap * 8;         // bytes of one lane list
+    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (size_t)(2 * cap8);
     const int row_end = min(N, (I + 1) * p.grows);
     for (int row = I * p.grows + rsel; row < row_end; row += 16) {
         const long gi = (long)bh * N + row;
         const float tau = p.tau[gi];
         const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
-        const char* l0 = lists_h + (size_t)row * (2 * BWD_LIST_CAP * 8);     // the second list follows the first
-        auto entry = [&](int i) { return *(const uint2*)(l0 + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8)); };
+        const char* l0 = lists_h + (size_t)row * (size_t)(2 * cap8);     // the second list follows the first
+        auto entry = [&](int i) { return *(const uint2*)(l0 + (i < s0 ? i * 8 : cap8 + (i - s0) * 8)); };
         const vvec gv = *(const vvec*)(Gh + (long)row * D + sub * EPT);
         float g[EPT];
 #pragma unroll
@@ -887,7 +929,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
                     } else {
                         const int i = i0 + u;
                         if (sub == 0)
-                            *(uint32_t*)(const_cast<char*>(l0) + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8) + 4) = e[u].y | 0x80000000u;
+                            *(uint32_t*)(const_cast<char*>(l0) + (i < s0 ? i * 8 : cap8 + (i - s0) * 8) + 4) = e[u].y | 0x80000000u;
                         ++ndefer;
                     }
                 }
@@ -934,19 +976,23 @@ __global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
     const elem* Qh = (const elem*)p.Q + hoff;
     const elem* Vh = (const elem*)p.V + hoff + sub * EPT;
     const elem* Gh = (const elem*)p.dO + hoff;
-    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * BWD_LIST_CAP * 8);
+    const int cap8 = p.list_cap * 8;
+    const char* lists_h = (const char*)p.lists + (size_t)bh * N * (size_t)(2 * cap8);
     const int row_end = min(N, (I + 1) * p.grows);
     for (int row = I * p.grows + rsel; row < row_end; row += 16) {
         const long gi = (long)bh * N + row;
         if (p.defer[gi] == 0) continue;
         const float tau = p.tau[gi], delta = -p.delta[gi] * amax;
         const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
-        const char* l0 = lists_h + (size_t)row * (2 * BWD_LIST_CAP * 8);
+        char* l0 = const_cast<char*>(lists_h) + (size_t)row * (size_t)(2 * cap8);
         const vvec gv = *(const vvec*)(Gh + (long)row * D + sub * EPT);
         for (int i = 0; i < tot; ++i) {
-            const uint2 e = *(const uint2*)(l0 + (i < s0 ? i * 8 : BWD_LIST_CAP * 8 + (i - s0) * 8));
+            char* ep = l0 + (i < s0 ? i * 8 : cap8 + (i - s0) * 8);
+            const uint2 e = *(const uint2*)ep;
             if (!(e.y >> 31)) continue;
             const uint32_t key = e.y & 0x7fffffffu;
+            // the mark comes off again: the lists are left as they were found (they may be the forward's)
+            if (sub == 0) *(uint32_t*)(ep + 4) = key;
             const vvec vv = *(const vvec*)(Vh + (long)key * D);
             float dot = 0.f;
 #pragma unroll

@@ -49,6 +49,10 @@ struct Params {
     int32_t* scnt;        // [BH][N][2] entries at the front of each list that are in the support at the final tau
     int32_t* gflag;       // [BH][ceil(N / grows)] 1 = the rows of this row group get their output by the gather kernel
     int grows;            // rows per row group of the candidate-list kernel
+    // backward: entries per lane list of p.lists (its own lists, or the forward's when the caller hands
+    // them over), and then the forward's group flags and their row-group size
+    int list_cap;
+    const int32_t* fwd_gflag; const unsigned int* fwd_scal;   // (fwd_scal[2] = rows per row group of the forward's flags)
     int32_t* kcnt;        // backward [BH][N]: entries in each key's list
     int32_t* nplain;      // backward: number of row groups that stay with dq_kernel / dkdv_kernel
     int32_t* nmarked;     // backward: set bits of the whole mask
@@ -59,6 +63,7 @@ struct Params {
     // bits of non-negative floats kept in the workspace (atomicMax on the bit patterns):
     // scal[0] = max |dO| rounded up to a power of two (the backward uses dO divided by it: exact)
     // scal[1] = forward: number of row groups left to out_kernel (a plain counter)
+    // scal[2] = forward: rows per row group of its gather flags (for a backward that is handed the forward's lists)
     unsigned int* scal;
     int BH, N, T, W;
     int causal;

@@ -805,6 +805,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
     }
     __syncthreads();
     const bool gather = sparse && gsum[1] <= GATHER_SUP_MAX * nrows;
+    if (blockIdx.x == 0 && tid == 0) p.scal[2] = p.gflag ? (unsigned int)BR : 0u;     // (0: no flags were written)
     if (p.gflag && tid == 0) {
         p.gflag[(long)bh * ((N + BR - 1) / BR) + I] = gather;
         if (!gather) atomicAdd(&p.scal[1], 1u);       // a row group out_kernel will have to serve

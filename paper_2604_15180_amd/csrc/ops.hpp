@@ -130,7 +130,13 @@ struct Ops {
             EA_HIP(hipGetLastError());
             hipLaunchKernelGGL(mask_popcount_kernel, dim3(64), dim3(256), 0, s, p.mask, (long)p.BH * p.T * p.W, p.nmarked);
             EA_HIP(hipGetLastError());
-            rc = launch(bwd_list_kernel<E, D, QBB, AM, NW_BLIST>, groups(p, NW_BLIST, QBB), NW_BLIST * 64, s, po);
+            if (p.fwd_gflag) {
+                // the forward's lists were handed over: no sweep, only the decision per row group
+                static_assert(32 * QBB * NW_BLIST <= 128, "one thread per row of a group");
+                rc = launch(bwd_decide_kernel<D, AM>, groups(p, NW_BLIST, QBB), 128, s, po);
+            } else {
+                rc = launch(bwd_list_kernel<E, D, QBB, AM, NW_BLIST>, groups(p, NW_BLIST, QBB), NW_BLIST * 64, s, po);
+            }
             if (rc) return rc;
         }
         {

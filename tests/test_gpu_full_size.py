@@ -32,7 +32,8 @@ def test_c3_full_size_sampled_heads(ea, sigma, heads):
     wf = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device="cuda")
     wb = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
     O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=wf)
-    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=wb)
+    # (as bench.py calls it: the backward is handed the forward's workspace)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=wb, fwd_workspace=wf)
     torch.cuda.synchronize()
     # which path served the rows, as in the launch configuration bench.py times: at sigma = 4 every
     # row group goes by gather in both passes, at sigma = 1 the backward is split between the gather
