@@ -18,7 +18,7 @@
  *     contiguous [B, H, N, d] with d fastest.  Inputs Q, K, V, dO have the element type
  *     named by `dtype`; O, dQ, dK, dV, tau are always float32.
  *   - N must be a positive multiple of 64 and at most 131072; d must be 64 or 128;
- *     1 < alpha <= 2.  With bf16 inputs, values of magnitude above 65504 are outside the
+ *     1 < alpha <= EA_ALPHA_MAX.  With bf16 inputs, values of magnitude above 65504 are outside the
  *     library's domain (second-stage products run on fp16 copies): they enter those copies as
  *     +-65504 and are counted in EA_STAT_F16_CLAMPED.
  *   - Causal masking: key j is visible to query r iff j <= r.
@@ -44,10 +44,16 @@ extern "C" {
  * with EA_ERR_DTYPE, or a size of 0). */
 typedef enum { EA_F32 = 0, EA_BF16 = 1 } ea_dtype;
 
+/* Largest alpha accepted.  Sec. 3.2 covers every alpha > 1 (secant steps above 2); the bound keeps
+ * the backward's U = P^(2-alpha) = y^(1/(alpha-1) - 1), which grows without limit as a probability
+ * approaches zero once alpha > 2, inside the range of the fp16 operands of the second-stage
+ * products: with alpha <= 3 the exponent is at least -1/2. */
+#define EA_ALPHA_MAX 3.0f
+
 enum {
     EA_OK = 0,
     EA_ERR_NULL = -1,       /* a required pointer is NULL */
-    EA_ERR_ALPHA = -2,      /* alpha not finite or outside (1, 2] */
+    EA_ERR_ALPHA = -2,      /* alpha not finite or outside (1, EA_ALPHA_MAX] */
     EA_ERR_SHAPE = -3,      /* B, H <= 0, N not a positive multiple of 64 or > 131072, d not in {64, 128} */
     EA_ERR_DTYPE = -4,      /* unknown ea_dtype */
     EA_ERR_WORKSPACE = -5,  /* workspace NULL, misaligned or too small */
@@ -148,13 +154,27 @@ int entmax_attn_bwd_with_lists(const void* Q, const void* K, const void* V, cons
                                void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * The same two operations with one alpha per head (Sec. 3.2 gives the solver for every alpha in
- * (1, 2]; heads of one layer may use different values).  `alpha_per_head` is a HOST pointer to H
+ * Right-edge binning (Sec. 3.2, the paragraph after Prop. 1): an approximate forward.  Rounding
+ * every score up to its bin's right edge instead of down to the left one moves the histogram's root
+ * up by one bin width h = 1/63, to tau_h + h >= tau*.  With the switch on, entmax_attn_fwd (and the
+ * per-head variant) takes that root as the threshold and does no refinement: `tau` holds it
+ * (tau* <= tau < tau* + h + 2e-6 (1 + |tau|)), P = [(alpha-1) S - tau]_+^{1/(alpha-1)} has a support
+ * inside the exact one and rows that sum to at most 1, O = P V, `block_mask` is P's.  Sparser and
+ * cheaper than the exact result, not equal to it.  entmax_attn_bwd on these outputs evaluates the
+ * formulas of Sec. 3.3 at that tau; they are the gradient only for the exact threshold.
+ * The switch belongs to the calling host thread (off at its start) and applies to the forward calls
+ * that thread makes after it; entmax_attn_decode is not affected.  Returns EA_OK.
+ */
+int entmax_attn_right_edge_enable(int on);
+
+/*
+ * The same two operations with one alpha per head (Sec. 3.2 gives the solver for every alpha
+ * above 1; heads of one layer may use different values).  `alpha_per_head` is a HOST pointer to H
  * floats, each in (1, 2]; it is read before the call returns.  Head h of every batch entry uses
  * alpha_per_head[h].  When the values differ, all heads run the general-alpha code (power functions
  * through exp2/log2) and a table of per-head constants is written into the workspace first; when
  * they are all equal the call is the single-alpha one.  Everything else as in entmax_attn_fwd /
- * entmax_attn_bwd; EA_ERR_ALPHA if any value is outside (1, 2].
+ * entmax_attn_bwd; EA_ERR_ALPHA if any value is outside (1, EA_ALPHA_MAX].
  */
 int entmax_attn_fwd_alpha_per_head(const void* Q, const void* K, const void* V,
                                    float* O, float* tau, int32_t* block_mask, int32_t* iters,

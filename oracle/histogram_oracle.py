@@ -9,6 +9,7 @@ Follows the paper's steps in its own order and notation:
   objective     f_h(tau) = -1 + sum_k H_k [k/B - tau]_+^{1/(alpha-1)}       (Eq. 9)
   solve         root tau_h of f_h (App. C.3), tau* - 1/B < tau_h <= tau*   (Prop. 1)
   refine        safeguarded hybrid solver on the true scores               (Sec. 3.2)
+  right edge    b(z) = ceil(B z)/B: root >= tau*, the sparser approximation (Sec. 3.2, after Prop. 1)
 and the packed encodings of App. C.2, C.4, C.5 (used as printed-value pins).
 All thresholds in this module are in centred units (z), i.e. tau_z = tau_raw - (m - 1).
 """
@@ -35,6 +36,35 @@ def histogram(z, B):
     """H_k of Eq. 8."""
     k = bin_index(z, B)
     return np.bincount(k[k >= 0], minlength=B).astype(np.int64)
+
+
+def histogram_right_edge(z, B):
+    """Right-edge binning (Sec. 3.2, after Prop. 1): b(z) = ceil(B z) / B, so the counts sit on the
+    B + 1 edges 0, 1/B, ..., 1; z < 0 dropped.  Returns H of length B + 1."""
+    z = np.asarray(z, dtype=np.float64)
+    k = np.ceil(B * z[z >= 0]).astype(np.int64)
+    return np.bincount(np.minimum(k, B), minlength=B + 1).astype(np.int64)
+
+
+def f_h_right_edge(H, alpha, tau):
+    """Eq. 9 with the counts of histogram_right_edge: -1 + sum_k H_k [k/B - tau]_+^{1/(alpha-1)}, k = 0..B."""
+    B = len(H) - 1
+    y = np.arange(B + 1, dtype=np.float64) / B - tau
+    act = y > 0
+    return float(np.sum(np.asarray(H, dtype=np.float64)[act] * y[act] ** (1.0 / (alpha - 1.0))) - 1.0)
+
+
+def solve_histogram_right_edge(H, alpha):
+    """Root of f_h_right_edge by bisection on [-1/B, 1]; tau* <= root < tau* + 1/B."""
+    B = len(H) - 1
+    lo, hi = -1.0 / B, 1.0
+    while hi - lo > 1e-13:
+        mid = 0.5 * (lo + hi)
+        if f_h_right_edge(H, alpha, mid) >= 0:
+            lo = mid
+        else:
+            hi = mid
+    return 0.5 * (lo + hi)
 
 
 def f_true(z, alpha, tau):
@@ -93,13 +123,19 @@ def solve_histogram(H, alpha):
     return 0.5 * (lo + hi)
 
 
-def hybrid_step(z, alpha, tau):
+def hybrid_step(z, alpha, tau, prev=None):
     """f, f', f'' of App. B part (i) on the true centred scores, and the raw update:
-    Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2 (Sec. 3.2)."""
+    Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2, and for alpha > 2, where f' is unbounded,
+    the secant through this iterate and the one before, prev = (tau, f) (Sec. 3.2); no update
+    (infinite) when there is no earlier iterate."""
     r = 1.0 / (alpha - 1.0)
     y = np.asarray(z, dtype=np.float64) - tau
     y = y[y > 0]
     f = float(np.sum(y ** r) - 1.0)
+    if alpha > 2.0:
+        if prev is None or prev[1] == f:
+            return f, float("inf")
+        return f, -f * (tau - prev[0]) / (f - prev[1])
     f1 = float(-r * np.sum(y ** (r - 1.0)))
     if alpha <= 1.5:
         f2 = float(r * (r - 1.0) * np.sum(y ** (r - 2.0)))
@@ -116,12 +152,18 @@ def hybrid_solver(z, alpha, tau0, lo, hi, tol, max_iter=64, trace=None):
 
     One iteration = one evaluation of f (and derivatives) over the true scores followed
     by one update.  A row stops when |f| <= tol or when its update moves tau by less
-    than tol.  Returns (tau, iterations).
+    than tol.  For alpha > 2 a short secant step says nothing about the distance to the root
+    (f rises vertically at every score): while the bracket is wider than tol such a step is
+    lengthened to 2 tol, so the row stops on a short step only once the bracket is that narrow
+    (or its midpoint that near).
+    Returns (tau, iterations).
     """
     tau = float(tau0)
     it = 0
+    prev = None
     while it < max_iter:
-        f, delta = hybrid_step(z, alpha, tau)
+        f, delta = hybrid_step(z, alpha, tau, prev)
+        prev = (tau, f)
         it += 1
         if trace is not None:
             trace.append(tau)
@@ -131,6 +173,8 @@ def hybrid_solver(z, alpha, tau0, lo, hi, tol, max_iter=64, trace=None):
             lo = tau
         else:
             hi = tau
+        if alpha > 2.0 and abs(delta) < tol and hi - lo >= tol:
+            delta = 2 * tol if f > 0 else -2 * tol
         cand = tau + delta
         if not (lo < cand < hi):
             cand = 0.5 * (lo + hi)

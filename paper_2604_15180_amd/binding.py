@@ -65,6 +65,8 @@ def lib():
         L.entmax_attn_timer_enable.argtypes = [ci]
         L.entmax_attn_gather_enable.restype = ci
         L.entmax_attn_gather_enable.argtypes = [ci]
+        L.entmax_attn_right_edge_enable.restype = ci
+        L.entmax_attn_right_edge_enable.argtypes = [ci]
         L.entmax_attn_timer_read.restype = ci
         L.entmax_attn_timer_read.argtypes = [ctypes.POINTER(cf), ctypes.POINTER(ci), ci]
         L.entmax_attn_decode_workspace_bytes.restype = sz
@@ -276,6 +278,11 @@ def entmax_attn_mfma_probe(data, sink, groups, iters):
     _check(lib().entmax_attn_mfma_probe(_ptr(data), _ptr(sink), int(groups), int(iters),
                                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
     return float(groups) * 4 * iters * 32 * 32768.0
+
+
+def entmax_attn_right_edge_enable(on):
+    """Approximate forward from right-edge binning, no refinement (this thread's later forward calls)."""
+    _check(lib().entmax_attn_right_edge_enable(int(bool(on))))
 
 
 def entmax_attn_gather_enable(on):

@@ -38,6 +38,7 @@ constexpr size_t STATS_BYTES = (size_t)EA_STATS_WORDS * EA_STATS_COPIES * 8;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 thread_local bool g_gather_enabled = true;      // the gather switch of the calling host thread
+thread_local bool g_right_edge = false;         // right-edge binning without refinement (approximate forward), same scope
 
 struct Layout {
     size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, rs_t0, rs_up0, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
@@ -93,7 +94,7 @@ Layout bwd_layout(int B, int H, int N, int d, int t) {
     return L;
 }
 
-bool alpha_ok(float alpha) { return isfinite(alpha) && alpha > 1.f && alpha <= 2.f; }
+bool alpha_ok(float alpha) { return isfinite(alpha) && alpha > 1.f && alpha <= EA_ALPHA_MAX; }
 
 int check_common(int B, int H, int N, int d, int t, float alpha) {
     if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
@@ -251,6 +252,7 @@ int fwd_impl(const void* Q, const void* K, const void* V, float* O, float* tau, 
     p.oflag = (int32_t*)(ws + L.oflag);
     p.scnt = (int32_t*)(ws + L.scnt);
     p.gflag = g_gather_enabled ? (int32_t*)(ws + L.gflag) : nullptr;
+    p.right_edge = g_right_edge ? 1 : 0;
     p.rs_lo = (float*)(ws + L.rs_lo); p.rs_hi = (float*)(ws + L.rs_hi); p.rs_f1 = (float*)(ws + L.rs_f1); p.rs_state = (int*)(ws + L.rs_state);
     p.rs_t0 = (float*)(ws + L.rs_t0); p.rs_up0 = (float*)(ws + L.rs_up0);
     p.scal = (unsigned int*)(ws + L.stats + STATS_BYTES);
@@ -367,6 +369,11 @@ int entmax_attn_fwd_histogram_bounds(const void* workspace, size_t workspace_byt
     const size_t bytes = (size_t)B * H * N * sizeof(float);
     EA_HIP(hipMemcpyAsync(tau0, (const char*)workspace + L.rs_t0, bytes, hipMemcpyDeviceToDevice, (hipStream_t)hip_stream));
     EA_HIP(hipMemcpyAsync(upper, (const char*)workspace + L.rs_up0, bytes, hipMemcpyDeviceToDevice, (hipStream_t)hip_stream));
+    return EA_OK;
+}
+
+int entmax_attn_right_edge_enable(int on) {
+    g_right_edge = on != 0;
     return EA_OK;
 }
 

@@ -51,6 +51,7 @@ struct Params {
     int grows;            // rows per row group of the candidate-list kernel
     // backward: entries per lane list of p.lists (its own lists, or the forward's when the caller hands
     // them over), and then the forward's group flags and their row-group size
+    int right_edge;      // forward: thresholds are the right-edge histogram roots, no refinement (Sec. 3.2)
     int list_cap;
     const int32_t* fwd_gflag; const unsigned int* fwd_scal;   // (fwd_scal[2] = rows per row group of the forward's flags)
     int32_t* kcnt;        // backward [BH][N]: entries in each key's list
@@ -96,10 +97,14 @@ template <int AM> EA_DEV float pow_r(float y, float r) {
     else if constexpr (AM == ALPHA_20) return y;
     else return __builtin_amdgcn_exp2f(r * __builtin_amdgcn_logf(y));
 }
+// (alpha > 2: the exponent r - 1 is negative, at least -1/2 for alpha <= 3, and y^(r-1) grows
+// without limit as y falls to zero.  y is held at or above 1e-6, about the accuracy to which an fp32
+// score difference is known anyway, so that the result stays below 1e3 and its products with dP - delta
+// inside the range of the fp16 operands of the backward's second-stage products.)
 template <int AM> EA_DEV float pow_r1(float y, float r) {
     if constexpr (AM == ALPHA_15) return y;
     else if constexpr (AM == ALPHA_20) return 1.f;
-    else return __builtin_amdgcn_exp2f((r - 1.f) * __builtin_amdgcn_logf(y));
+    else return __builtin_amdgcn_exp2f((r - 1.f) * __builtin_amdgcn_logf(r < 1.f ? fmaxf(y, 1e-6f) : y));
 }
 template <int AM> EA_DEV float pow_r2(float y, float r) {
     if constexpr (AM == ALPHA_15) return 1.f;

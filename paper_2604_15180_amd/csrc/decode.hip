@@ -245,6 +245,7 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
     };
     // refinement (Sec. 3.2): f, f', f'' over the candidates, hybrid step, until the step or f is below tol
     int iters = 0;
+    SecantPrev prev;
     for (int it = 0; it < p.max_iters; ++it) {
         float F = 0.f, G = 0.f, Hs = 0.f;
         auto term = [&](float x) {
@@ -264,7 +265,7 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
         ++iters;
         const float f = F - 1.f;
         if (fabsf(f) <= p.tol) break;
-        const float cand = hybrid_step(thr, f, G, Hs, r, p.alpha, blo, bhi);
+        const float cand = hybrid_step<AM>(thr, f, G, Hs, r, p.alpha, blo, bhi, prev, p.tol);
         const bool small = fabsf(cand - thr) < p.tol;
         thr = cand;
         if (small) break;
@@ -381,7 +382,7 @@ int decode_check(const void* q, const void* K, const void* V, const float* O, co
     if (!q || !K || !V || !O || !tau) return EA_ERR_NULL;
     if (t != EA_F32 && t != EA_BF16) return EA_ERR_DTYPE;
     if (!decode_shape_ok(B, H, N, d, t)) return EA_ERR_SHAPE;
-    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > 2.f) return EA_ERR_ALPHA;
+    if (!isfinite(alpha) || !(alpha > 1.f) || alpha > EA_ALPHA_MAX) return EA_ERR_ALPHA;
     if (decode_groups(B * H, N) > 1024) return EA_ERR_SHAPE;      // decode_entmax_kernel indexes the groups by thread
     return EA_OK;
 }
@@ -402,7 +403,7 @@ int decode_enqueue(const void* q, const void* K, const void* V, float* O, float*
     p.alpha = alpha; p.r = 1.f / (alpha - 1.f);
     p.tol = (t == EA_BF16) ? 1e-4f : 1e-6f;
     p.zwin = p.r * (1.f + 1e-5f);
-    p.max_iters = 16;
+    p.max_iters = alpha > 2.f ? 32 : 16;      // (alpha > 2: a logit within the tolerance of the root makes the solver bisect)
     hipStream_t s = (hipStream_t)hip_stream;
     if (t == EA_BF16) return d == 64 ? decode_run<Bf16, 64>(p, s) : decode_run<Bf16, 128>(p, s);
     return d == 64 ? decode_run<F32, 64>(p, s) : decode_run<F32, 128>(p, s);

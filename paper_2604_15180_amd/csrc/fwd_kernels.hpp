@@ -47,8 +47,10 @@ EA_DEV float solve_histogram(const uint32_t* H, int rot, int shift, float h, flo
         const float mean = B1 / B0;
         return mean - sqrtf(fmaxf(mean * mean - (B2 - 1.f) / B0, 0.f));
     } else {
-        // general alpha: bisection of f_h on [-h, (SLOTS-1) h], then Newton from the left end
-        // (f_h is convex and decreasing for alpha <= 2, so Newton from the left is monotone)
+        // general alpha: bisection of f_h on [-h, (SLOTS-1) h]; for alpha <= 2 then Newton from the
+        // left end (f_h is convex and decreasing there, so Newton from the left is monotone and
+        // stays at or below the root); for alpha > 2 f_h is not convex, so the bisection is run
+        // further instead and its left end, where f_h >= 0, is returned
         auto eval = [&](float tau, float& f1) {
             float f = -1.f; f1 = 0.f;
             for (int k = SLOTS - 1; k >= 0; --k) {
@@ -63,12 +65,13 @@ EA_DEV float solve_histogram(const uint32_t* H, int rot, int shift, float h, flo
             return f;
         };
         float lo = -h, hi = (SLOTS - 1) * h, d1;
-        for (int i = 0; i < 12; ++i) {
+        const int nbis = r < 1.f ? 22 : 12;
+        for (int i = 0; i < nbis; ++i) {
             const float mid = 0.5f * (lo + hi);
             if (eval(mid, d1) >= 0.f) lo = mid; else hi = mid;
         }
         float tau = lo;
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4 && !(r < 1.f); ++i) {
             const float f = eval(tau, d1);
             if (d1 >= 0.f) break;
             const float nt = tau - f / d1;
@@ -122,10 +125,19 @@ EA_DEV bool eval_scores(const f32x16 (&C)[2][QB], const float (&thr)[QB], float 
     return hit;
 }
 
+// The iterate before the current one and its f, for the secant steps of alpha > 2; t is NaN while
+// there is none (at the start of a kernel: the state is not carried from one kernel to the next).
+struct SecantPrev { float t = __builtin_nanf(""), f = 0.f; };
+
 // One safeguarded hybrid step from (tau, f = F - 1) with G = sum y^(r-1), Hs = sum y^(r-2):
-// Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2, the bracket's midpoint whenever the
-// proposed point leaves (lo, hi).  Updates the bracket; returns the proposed threshold.
-EA_DEV float hybrid_step(float tau, float f, float G, float Hs, float r, float alpha, float& lo, float& hi) {
+// Halley for alpha <= 1.5, Newton for 1.5 < alpha <= 2, and for alpha > 2, where f' is unbounded
+// next to every score (Prop. 2), a secant step through the last two iterates; the bracket's
+// midpoint whenever the proposed point leaves (lo, hi) or does not exist (no earlier iterate, or
+// f unchanged).  Updates the bracket; returns the proposed threshold.  tol: the callers' stopping
+// length, used by the secant branch only.
+template <int AM>
+EA_DEV float hybrid_step(float tau, float f, float G, float Hs, float r, float alpha, float& lo, float& hi,
+                         SecantPrev& prev, float tol) {
     if (f > 0.f) lo = tau; else hi = tau;
     const float f1 = -r * G;
     float delta;
@@ -134,6 +146,19 @@ EA_DEV float hybrid_step(float tau, float f, float G, float Hs, float r, float a
         delta = -2.f * f * f1 / (2.f * f1 * f1 - f * f2);
     } else {
         delta = -f / f1;
+    }
+    if constexpr (AM == ALPHA_GEN) {
+        if (alpha > 2.f) {
+            delta = -f * (tau - prev.t) / (f - prev.f);      // NaN or inf when there is no usable secant
+            prev.t = tau; prev.f = f;
+            // Callers stop when the step is shorter than tol.  Here a short step is no sign of
+            // convergence (f rises vertically at every score, so a secant taken on its flat side
+            // can be short far from the root): while the bracket is wider than tol such a step is
+            // lengthened to 2 tol - either f changes sign, and the bracket is then no wider than
+            // that, or the iterate has moved on by as much.  A step shorter than tol is then left
+            // only inside a bracket narrower than tol, or as the half of one narrower than 2 tol.
+            if (fabsf(delta) < tol && hi - lo >= tol) delta = f > 0.f ? 2.f * tol : -2.f * tol;
+        }
     }
     float cand = tau + delta;
     if (!(cand > lo && cand < hi)) cand = 0.5f * (lo + hi);
@@ -316,10 +341,13 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             thr[qb] = mine ? my_t0 : o_t0;
             blo[qb] = thr[qb];
             bhi[qb] = mine ? my_hi : o_hi;
+            // right-edge binning moves every bin, and with it the root, up by one bin width: that
+            // root, tau_h + h >= tau*, is the bracket's upper end, and it stands as the threshold
             if (active && h == 0) {
                 p.rs_t0[(long)bh * N + qw0 + 32 * qb + n] = thr[qb];
                 p.rs_up0[(long)bh * N + qw0 + 32 * qb + n] = bhi[qb];
             }
+            if (p.right_edge) thr[qb] = bhi[qb];
         }
     }
     // candidate tiles of this wave's rows: those holding a score above tau_0.  64 tiles per
@@ -383,10 +411,11 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             if constexpr (AM == ALPHA_15) Hs[qb] = (float)cnt[qb];
             if constexpr (AM == ALPHA_20) G[qb] = (float)cnt[qb];
             const float f = xhalf_sum(F[qb]) - 1.f, g = xhalf_sum(G[qb]), hs = xhalf_sum(Hs[qb]);
-            bool done = fabsf(f) <= p.tol;
+            bool done = fabsf(f) <= p.tol || p.right_edge;
             float tau = thr[qb];
             if (!done) {
-                const float cand_tau = hybrid_step(tau, f, g, hs, r, hc.alpha, blo[qb], bhi[qb]);
+                SecantPrev none;
+                const float cand_tau = hybrid_step<AM>(tau, f, g, hs, r, hc.alpha, blo[qb], bhi[qb], none, p.tol);
                 done = fabsf(cand_tau - tau) < p.tol;
                 tau = cand_tau;
             }
@@ -681,12 +710,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
             mycnt[qb] = min(cnt[qb], LIST_CAP);
             nmax = max(nmax, mycnt[qb]);
             blo[qb] = thr[qb]; iters[qb] = 0; done[qb] = 0; f1_last[qb] = -1.f;
+            if (p.right_edge) thr[qb] = bhi[qb];      // tau_h + h >= tau*: the right-edge root, taken as it is
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) nmax = max(nmax, __shfl_xor(nmax, off));
         // refinement (Sec. 3.2): evaluations of f, f', f'' over the listed scores; each lane walks
         // its own lists, sixteen entries per row block at a time with all loads in flight together
-        for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
+        SecantPrev prev[QB];
+        // (alpha > 2: a row with a score within the tolerance of its root ends up bisecting, since f
+        // rises vertically there; the sweeps over the lists are cheap, those of the output kernel
+        // are not, so the limit is doubled here)
+        const int nsweeps = r < 1.f ? 2 * p.max_sweeps : p.max_sweeps;
+        for (int sweep = 0; sweep < nsweeps; ++sweep) {
             float F[QB], G[QB], Hs[QB];
             uint32_t lastj[QB];
 #pragma unroll
@@ -726,9 +761,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
                 if (!done[qb]) {
                     iters[qb] += 1;
                     f1_last[qb] = -r * g;
-                    if (fabsf(f) <= p.tol) done[qb] = 1;
+                    if (fabsf(f) <= p.tol || p.right_edge) done[qb] = 1;
                     else {
-                        const float cand_tau = hybrid_step(thr[qb], f, g, hs, r, hc.alpha, blo[qb], bhi[qb]);
+                        const float cand_tau = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, blo[qb], bhi[qb], prev[qb], p.tol);
                         if (fabsf(cand_tau - thr[qb]) < p.tol) done[qb] = 1;
                         thr[qb] = cand_tau;
                     }
@@ -911,9 +946,9 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
     auto issue_k = [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)tl[it] * 64, wave, lane); };
 
     // Phase 4 doubles as the next evaluation of f: the row sums of P are f(tau) + 1.  A row is
-    // finished when |f| <= tol, or when the step -f / f' (with f' from its previous evaluation: a
-    // chord step) is shorter than tol; it then takes that step, and O, computed less than tol away
-    // in tau, stands.  Only when some row fails both, a scores-only sweep gathers f', f'' at the
+    // finished when |f| <= tol, or (alpha <= 2, where f' is bounded) when the step -f / f' (with f'
+    // from its previous evaluation: a chord step) is shorter than tol; it then takes that step, and
+    // O, computed less than tol away in tau, stands.  Only when some row fails both, a scores-only sweep gathers f', f'' at the
     // same tau, the hybrid step moves those rows, and Phase 4 runs again.
     auto pv_pass = [&](float (&rowsum)[QB]) {
 #pragma unroll
@@ -963,7 +998,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                 iters[qb] += 1;
                 const float chord = -fval[qb] / f1_prev[qb];
                 if (fabsf(fval[qb]) <= p.tol) done[qb] = 1;
-                else if (fabsf(chord) < p.tol && f1_prev[qb] < 0.f) {
+                else if (fabsf(chord) < p.tol && f1_prev[qb] < 0.f && hc.alpha <= 2.f) {
                     thr[qb] = fminf(fmaxf(thr[qb] + chord, lo[qb]), hi[qb]);
                     done[qb] = 1;
                 } else need = 1;
@@ -971,8 +1006,12 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
         }
         if (__syncthreads_count(need) != 0) {
             // rare: finish those rows with scores-only sweeps over the tiles that held some P > 0
-            // (a superset of the support at any larger tau), then form O once more
+            // (a superset of the support at any larger tau), then form O once more.  For alpha > 2
+            // the iterates come from both sides of the root, so the next tau may lie below this
+            // one: the sweeps then walk the whole working mask, which was taken at tau_0 <= tau*.
+            const bool below = hc.alpha > 2.f;
             bool have_f = true;          // the first sweep runs at the tau whose f is already known
+            SecantPrev prev[QB];
             for (int sweep = 0; sweep < p.max_sweeps; ++sweep) {
                 float F[QB], G[QB], Hs[QB];
                 int cnt[QB];
@@ -980,7 +1019,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                 for (int qb = 0; qb < QB; ++qb) { F[qb] = G[qb] = Hs[qb] = 0.f; cnt[qb] = 0; }
                 stream_tiles<NBUF>(*tl_count, set0, NBUF == 2 ? set1 : set0, issue_k, [&](int it, const char* buf) {
                     const int j = tl[it];
-                    if (!mask_bit(fm, W, myrow, j)) return;
+                    if (!mask_bit(below ? wm : fm, W, myrow, j)) return;
                     stage1<E, D, QB>(C, buf, qf, lane);
                     if (p.causal && (long)j * 64 + 63 > qw0) causal_hide<QB, true>(C, j * 64, (int)qw0, lane);
                     ++nstat_done;
@@ -997,7 +1036,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                         if (!have_f) iters[qb] += 1;
                         if (!have_f && fabsf(f) <= p.tol) done[qb] = 1;
                         else {
-                            const float cand = hybrid_step(thr[qb], f, g, hs, r, hc.alpha, lo[qb], hi[qb]);
+                            const float cand = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, lo[qb], hi[qb], prev[qb], p.tol);
                             if (fabsf(cand - thr[qb]) < p.tol) done[qb] = 1;
                             thr[qb] = cand;
                         }

@@ -33,7 +33,7 @@ int main() {
     const float alphas_bad[2] = {1.5f, 0.5f};
     CHECK(entmax_attn_fwd_alpha_per_head(x, x, x, x, x, m, nullptr, 1, 2, 64, 64, EA_F32, alphas_bad, 0, ws, sizeof ws, nullptr) == EA_ERR_ALPHA);
     CHECK(entmax_attn_fwd_alpha_per_head(x, x, x, x, x, m, nullptr, 1, 2, 64, 64, EA_F32, nullptr, 0, ws, sizeof ws, nullptr) == EA_ERR_NULL);
-    CHECK(entmax_attn_decode(x, x, x, x, x, m, m, 1, 1, 8, 64, EA_F32, 2.5f, ws, sizeof ws, nullptr) == EA_ERR_ALPHA);
+    CHECK(entmax_attn_decode(x, x, x, x, x, m, m, 1, 1, 8, 64, EA_F32, 3.5f, ws, sizeof ws, nullptr) == EA_ERR_ALPHA);
     CHECK(entmax_attn_decode(x, x, x, x, x, m, m, 1, 1, 8, 64, EA_F32, 1.5f, ws, 0, nullptr) == EA_ERR_WORKSPACE);
     CHECK(entmax_attn_decode_static(x, x, x, x, x, m, m, 1, 64, 131072, 64, EA_BF16, 1.5f, nullptr) == EA_ERR_TOO_LARGE);
     CHECK(entmax_attn_fwd_histogram_bounds(nullptr, 0, 1, 1, 64, 64, EA_F32, x, x, nullptr) == EA_ERR_NULL);

@@ -79,7 +79,7 @@ def test_forward_argument_errors(L):
     assert call_fwd(L, [0] + ok[1:]) == -1
     assert call_fwd(L, ok[:5] + [0]) == -1
     assert call_fwd(L, ok, alpha=1.0) == -2
-    assert call_fwd(L, ok, alpha=2.5) == -2
+    assert call_fwd(L, ok, alpha=3.5) == -2
     assert call_fwd(L, ok, alpha=float("nan")) == -2
     assert call_fwd(L, ok, N=96) == -3
     assert call_fwd(L, ok, d=32) == -3

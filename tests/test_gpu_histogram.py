@@ -141,3 +141,55 @@ def test_permuting_key_tiles(ea):
     assert ((dV2 - dV[:, :, idx_c]).abs() / (1 + dV2.abs())).max().item() <= 5e-5
     bits, bits2 = parity.unpack_mask(mask, T), parity.unpack_mask(mask2, T)
     assert (bits2 != bits[..., perm.numpy()]).sum() <= 2
+
+
+@pytest.mark.parametrize("dtype,d,alpha,sigma,causal,N", [("bf16", 128, 1.5, 2.0, True, 1024), ("bf16", 64, 2.0, 2.0, False, 640),
+                                                       ("f32", 64, 1.25, 1.0, True, 320), ("bf16", 64, 3.0, 2.0, True, 640),
+                                                       ("bf16", 64, 1.5, 0.3, True, 2048), ("bf16", 128, 1.5, 4.0, True, 1024)])
+def test_right_edge_binning_gives_a_sparser_approximation(ea, dtype, d, alpha, sigma, causal, N):
+    # The approximate forward (Sec. 3.2, binning strategies): thresholds are the right-edge histogram
+    # roots, unrefined.  Asserted: what defines the mode - tau* <= tau < tau* + h + slack against the
+    # oracle's tau*, one evaluation per row, rows of P summing to at most 1, and O = P(tau) V for
+    # the tau returned (float64, from the same inputs).  Its distance from the exact result is
+    # printed, not asserted: the mode is not meant to reach it.  sigma = 0.3 overflows the candidate
+    # lists (the sweep-based kernel), sigma = 4 takes the gather path.
+    from oracle import entmax_oracle as eo
+    B, H = 1, 2
+    print(f"right-edge case N={N} d={d} {dtype} alpha={alpha} sigma={sigma} causal={causal}", flush=True)
+    q, k, v, _ = workloads.gaussian_qkv(B, H, N, d, dtype, sigma, seed=77)
+    Q, K, V = (t.cuda() for t in (q, k, v))
+    ea.entmax_attn_right_edge_enable(True)
+    try:
+        O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
+        torch.cuda.synchronize()
+    finally:
+        ea.entmax_attn_right_edge_enable(False)
+    O2, tau2, mask2 = ea.entmax_attn_fwd(Q, K, V, alpha, causal)          # and the switch is off again
+    torch.cuda.synchronize()
+    ref = eo.attn_fwd(*(parity.to_np64(t) for t in (q, k, v)), alpha, causal, tile=64)
+    parity.check_forward(q, k, v, alpha, causal, O2, tau2, mask2, ref=ref, label="exact mode after the approximate one")
+    h = 1.0 / ea.entmax_attn_histogram_bins()
+    t, ts = parity.to_np64(tau), ref["tau"]
+    slack = 2e-6 * (1 + np.abs(ts))
+    assert (t >= ts - slack).all() and (t <= ts + h + 2 * slack).all(), ((t - ts).min(), (t - ts).max())
+    assert (iters.cpu().numpy() == 1).all()
+    Qn, Kn, Vn = (parity.to_np64(x) for x in (q, k, v))
+    r = 1.0 / (alpha - 1.0)
+    worst_o, sums = 0.0, []
+    for hh in range(H):
+        X = (alpha - 1.0) * Qn[0, hh] @ Kn[0, hh].T / np.sqrt(d)
+        if causal:
+            X = np.where(np.tril(np.ones((N, N), bool)), X, -np.inf)
+        P = np.maximum(X - t[0, hh][:, None], 0.0) ** r
+        sums.append(P.sum(-1))
+        worst_o = max(worst_o, np.abs(P @ Vn[0, hh] - parity.to_np64(O)[0, hh]).max())
+    sums = np.concatenate(sums)
+    assert sums.max() <= 1 + 1e-3
+    assert worst_o <= parity.TOL[q.dtype]["O"], worst_o
+    # block mask: every tile it marks is marked in the exact result (support inside the true one)
+    T = N // 64
+    got, exact = parity.unpack_mask(mask, T), parity.unpack_mask(mask2, T)
+    assert not (got & ~exact).any()
+    print("  right edge:", dict(tau_above=float((t - ts).mean()), row_sum_mean=float(sums.mean()), row_sum_min=float(sums.min()),
+                               dO_vs_exact=float(np.abs(parity.to_np64(O) - ref["O"]).max()),
+                               tiles=int(got.sum()), tiles_exact=int(exact.sum())), flush=True)

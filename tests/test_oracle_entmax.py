@@ -12,7 +12,7 @@ from scipy import optimize
 from oracle import entmax_oracle as eo
 
 RNG = np.random.default_rng(1234)
-ALPHAS = [1.25, 1.5, 1.75, 2.0, 1.1]
+ALPHAS = [1.25, 1.5, 1.75, 2.0, 1.1, 2.5, 3.0]
 
 
 def tsallis_objective(p, s, alpha):
@@ -21,7 +21,7 @@ def tsallis_objective(p, s, alpha):
     return -(p @ s + np.sum(p - p ** alpha) / (alpha * (alpha - 1.0)))
 
 
-@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0, 1.8])
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0, 1.8, 2.5, 3.0])
 def test_matches_variational_definition(alpha):
     # generic constrained optimiser on the simplex, tiny n
     for n in (3, 5, 7):
@@ -63,6 +63,20 @@ def test_entmax15_two_element_closed_form():
             t = (xa + xb) / 2 - math.sqrt(0.5 - (xa - xb) ** 2 / 4)
             assert abs(tau - t) < 1e-14
             assert np.allclose(p, [(xa - t) ** 2, (xb - t) ** 2], atol=1e-14)
+
+
+def test_alpha3_two_element_closed_form():
+    # alpha = 3, x = 2 s: sqrt(x_a - tau) + sqrt(x_b - tau) = 1 when both are active; with
+    # u = sqrt(x_a - tau): x_a - x_b = u^2 - (1 - u)^2 = 2u - 1, so p = ((1 + D)/2, (1 - D)/2), D = x_a - x_b < 1
+    for a, b in [(0.3, -0.1), (0.2, 0.2), (1.0, 0.6), (3.0, 0.5), (0.45, 0.0)]:
+        xa, xb = 2 * a, 2 * b
+        p, tau = eo.entmax(np.array([a, b]), 3.0)
+        if xa - xb >= 1:
+            assert np.allclose(p, [1.0, 0.0], atol=1e-12) and abs(tau - (xa - 1)) < 1e-12
+        else:
+            u = (1 + xa - xb) / 2
+            assert np.allclose(p, [u, 1 - u], atol=1e-11)
+            assert abs(tau - (xa - u * u)) < 1e-11
 
 
 def sparsemax_textbook(s):

@@ -71,6 +71,35 @@ def test_prop1_lower_bound_and_sandwich(alpha, B):
         assert np.all((z > max(tau_h, 0)) | ~(z > tau_star))
 
 
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0, 3.0])
+@pytest.mark.parametrize("B", [8, 63])
+def test_right_edge_binning_bounds_the_threshold_from_above(alpha, B):
+    # the mirror image of Prop. 1: tau* <= tau_h < tau* + h; every bin moves up by h against
+    # left-edge binning, so the root does too; the support it leaves lies inside the true one
+    h = 1.0 / B
+    for n, scale in [(1, 1.0), (7, 1.0), (300, 0.5), (4096, 1.0), (4096, 6.0)]:
+        x = (alpha - 1) * RNG.normal(size=n) * scale
+        z, shift = ho.centre(x)
+        tau_star = eo.tau_row(x, alpha) - shift
+        HR = ho.histogram_right_edge(z, B)
+        assert HR.sum() == int((z >= 0).sum()) and HR[B] >= 1          # the maximum sits on the last edge
+        tau_r = ho.solve_histogram_right_edge(HR, alpha)
+        assert abs(ho.f_h_right_edge(HR, alpha, tau_r)) < 1e-8
+        assert tau_star - 1e-11 <= tau_r < tau_star + h + 1e-11
+        for t in np.linspace(0.0, 1.0, 23):
+            assert ho.f_h_right_edge(HR, alpha, t) >= ho.f_true(z, alpha, t) - 1e-10
+        assert np.all(~(z > tau_r) | (z > tau_star - 1e-12))
+        if alpha in (1.5, 2.0) or n > 1:
+            tau_l = ho.solve_histogram(ho.histogram(z, B), alpha)
+            assert abs(tau_r - (tau_l + h)) < 1e-9
+
+
+def test_right_edge_binning_rule():
+    B = 8
+    z = np.array([-0.01, 0.0, 0.1249, 0.125, 0.1251, 0.99, 1.0])
+    assert list(ho.histogram_right_edge(z, B)) == [1, 2, 1, 0, 0, 0, 0, 0, 2]
+
+
 @pytest.mark.parametrize("alpha", [1.5, 2.0])
 def test_closed_form_scan_agrees_with_generic_root(alpha):
     for B in (8, 32):
@@ -86,7 +115,7 @@ def test_closed_form_scan_agrees_with_generic_root(alpha):
             assert abs(t - lo) < 1e-10
 
 
-@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0, 2.5, 3.0])
 def test_hybrid_solver_reaches_exact_threshold(alpha):
     for n, scale in [(1, 1.0), (50, 1.0), (4096, 1.0), (4096, 8.0)]:
         x = (alpha - 1) * RNG.normal(size=n) * scale
@@ -94,7 +123,35 @@ def test_hybrid_solver_reaches_exact_threshold(alpha):
         for B, tol in [(8, 1e-6), (64, 1e-4), (64, 1e-6)]:
             tau, it, tau0 = ho.tau_from_histogram(x, alpha, B, tol)
             assert abs(tau - exact) < 20 * tol
-            assert it <= 6
+            # secant steps (alpha > 2) come down to bisection when a score sits on the root
+            assert it <= (6 if alpha <= 2 else 30)
+
+
+def test_secant_does_not_stop_on_a_short_step_far_from_the_root():
+    # alpha = 3 and a score that sits almost on the root: f rises vertically just below it, and a
+    # secant taken on the flat side proposes a step shorter than tol while still 5e-4 away.  A
+    # solver that stops on that step misses the root by more than tol; the rule that lengthens
+    # short steps while the bracket is wide does not.
+    alpha, tol = 3.0, 1e-4
+    x = np.array([15.42228769, 14.42482779, 14.41279519, 14.33566045, 14.29362637, 12.97043358, 12.05384912, 11.99181098])
+    exact = eo.tau_row(x, alpha)
+    tau, it, _ = ho.tau_from_histogram(x, alpha, 63, tol)
+    assert abs(tau - exact) <= tol and it <= 30
+    z, shift = ho.centre(x)
+    tau_h = ho.solve_histogram(ho.histogram(z, 63), alpha)
+    lo, hi, t, prev, naive = max(tau_h, 0.0), tau_h + 1 / 63, max(tau_h, 0.0), None, None
+    for _ in range(30):                      # the same iteration without that rule
+        f, delta = ho.hybrid_step(z, alpha, t, prev)
+        prev = (t, f)
+        if abs(f) <= tol:
+            break
+        lo, hi = (t, hi) if f > 0 else (lo, t)
+        cand = t + delta if lo < t + delta < hi else 0.5 * (lo + hi)
+        short = abs(cand - t) < tol
+        t = cand
+        if short:
+            break
+    assert abs(t + shift - exact) > 3 * tol
 
 
 def test_solver_study_shape():
