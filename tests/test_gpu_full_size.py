@@ -138,3 +138,25 @@ def test_maximum_sequence_length(ea, recipe):
     T = N // 64
     sparsity = 1.0 - (ref["margin"] > 0).sum() / (T * (T + 1) / 2)
     print("  block sparsity", sparsity, info, ginfo, "mean iters", iters.float().mean().item(), flush=True)
+
+
+def test_flat_attention_at_65536_tokens(ea):
+    # From 65536 keys on a histogram bin can hold more keys than a 16-bit counter, so the sweep-based
+    # threshold kernel switches to its variant with 32-bit counters; the list kernel's shared 16-bit
+    # counters only ever count listed candidates (at most 512 per row).  Tiny scores put every
+    # visible key within one unit of the row's maximum: all but the first rows overflow their
+    # lists, are redone by the sweep-based kernel, and have thousands of keys in the support.
+    B, H, N, d, alpha, causal = 1, 1, 65536, 64, 1.5, True
+    print("case flat attention N=65536", flush=True)
+    q, k, v, _ = workloads.gaussian_qkv(B, H, N, d, "bf16", 0.3, seed=4100)
+    Q, K, V = (t.cuda() for t in (q, k, v))
+    ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device="cuda")
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True, workspace=ws)
+    torch.cuda.synchronize()
+    st = ea.read_stats(ws)
+    print("  stats", {k_: st[k_] for k_ in ("list_overflow_blocks", "tau_subtiles")}, "oracle", flush=True)
+    assert st["list_overflow_blocks"] > 0.9 * (N // 64)
+    assert iters.max().item() <= 12
+    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="flat N=65536")
+    support = ((alpha - 1) * 0 + (ref["margin"] > 0)).sum()
+    print("  flat N=65536", info, "marked tiles", int(support), "mean iters", iters.float().mean().item(), flush=True)
