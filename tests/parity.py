@@ -38,9 +38,10 @@ def y_accuracy(X, dtype):
 
 
 def output_slack(Q, K, V, alpha, causal, tau_ref):
-    """For alpha > 2, where P = y_+^r with r = 1/(alpha-1) < 1 has an unbounded slope at the edge of
-    the support (a score 1e-6 above the threshold already has P = 1e-3 at alpha = 3): what a
-    perturbation of y within y_accuracy can change in O, per element, worst case:
+    """What a perturbation of y within y_accuracy can change in O, per element, worst case.  Needed
+    for alpha > 2, where P = y_+^r with r = 1/(alpha-1) < 1 has an unbounded slope at the edge of
+    the support (a score 1e-6 above the threshold already has P = 1e-3 at alpha = 3), and where fp32
+    inputs are compared at a score scale whose own rounding exceeds the 1e-5 bar:
         bP = max |P(y +- eta) - P(y)|,   O moves by at most  bP |V|."""
     Qn, Kn, Vn = (to_np64(t) for t in (Q, K, V))
     B, H, N, d = Qn.shape

@@ -250,10 +250,14 @@ def test_sparse_row_groups_gather_their_gradients(ea, dtype, d, alpha, sigma, ma
     print("  ", ginfo, flush=True)
 
 
-@pytest.mark.parametrize("dtype,d,sigma,otol,gtol", [("bf16", 128, 3.0, 2e-3, 1e-2), ("f32", 128, 2.5, 2e-4, 4e-4)])
-def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma, otol, gtol):
-    # the same call with the gather paths switched off: every row group on the matrix kernels
-    # (fp32 inputs at a score scale where fp32 scores themselves limit both paths to about 1e-4)
+@pytest.mark.parametrize("dtype,d,sigma", [("bf16", 128, 3.0), ("f32", 128, 2.5)])
+def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma):
+    # the same call with the gather paths switched off: every row group on the matrix kernels.
+    # Each path is within `allowed` of the oracle - the tolerance plus what the accuracy of
+    # y = (alpha-1) s - tau itself leaves open (parity.output_slack, parity.conditioning_slack; for
+    # fp32 inputs at this score scale that is about 1e-4, ten times the plain bar) - so the two may
+    # differ by twice that, element by element, and no more
+    from oracle import entmax_oracle as eo
     B, H, N, alpha, causal = 1, 2, 3072, 1.5, False
     q, k, v, do = workloads.gaussian_qkv(B, H, N, d, dtype, sigma, seed=93)
     Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
@@ -287,11 +291,21 @@ def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma, otol, gtol):
     assert res[False][7] == 0 and res[False][8] == 0
     # tau, mask and iteration counts come from the list kernel either way
     assert torch.equal(res[True][1], res[False][1]) and torch.equal(res[True][2], res[False][2]) and torch.equal(res[True][3], res[False][3])
-    for i, name, tol in ((0, "O", otol), (4, "dQ", gtol), (5, "dK", gtol), (6, "dV", gtol)):
-        a, b = res[True][i].double(), res[False][i].double()
-        err = ((a - b).abs() / (1 + b.abs())).max().item()
-        print(f"  {name}: gather vs matrix {err:.3e}", flush=True)
-        assert err <= tol
+    qn, kn, vn, gn = (parity.to_np64(t) for t in (q, k, v, do))
+    ref = eo.attn_fwd(qn, kn, vn, alpha, causal, want_margin=False)
+    gref = eo.attn_bwd(qn, kn, vn, gn, alpha, causal)
+    tol = parity.TOL[q.dtype]
+    slack = parity.conditioning_slack(q, k, v, do, alpha, causal, ref["tau"])
+    allowed = {"O": tol["O"] + parity.output_slack(q, k, v, alpha, causal, ref["tau"])}
+    for name in ("dQ", "dK", "dV"):
+        allowed[name] = tol["grad"] * (1 + np.abs(gref[name])) + slack[name]
+    for i, name in ((0, "O"), (4, "dQ"), (5, "dK"), (6, "dV")):
+        a, b = parity.to_np64(res[True][i]), parity.to_np64(res[False][i])
+        oracle = ref["O"] if name == "O" else gref[name]
+        worst = (np.abs(a - b) / (2 * allowed[name])).max()
+        print(f"  {name}: gather vs matrix {np.abs(a - b).max():.3e}, {worst:.3f} of what is allowed; against the oracle "
+              f"{(np.abs(a - oracle) / allowed[name]).max():.3f} / {(np.abs(b - oracle) / allowed[name]).max():.3f}", flush=True)
+        assert worst <= 1.0 and (np.abs(a - oracle) <= allowed[name]).all() and (np.abs(b - oracle) <= allowed[name]).all()
 
 
 @pytest.mark.parametrize("dtype,d,N,sigma,causal,hubs", [("bf16", 128, 3072, 3.0, False, (5, 1777)),
@@ -387,7 +401,7 @@ def test_c2_exact_config(ea):
     run_case(ea, 4, 16, 4096, 64, "bf16", True, 1.5, 1.5, seed=2000)
 
 
-@pytest.mark.parametrize("alpha", [1.25, 2.0])
+@pytest.mark.parametrize("alpha", [1.25, 1.5, 2.0])
 def test_c5_shape_one_head(ea, alpha):
     # configs[4]: alpha sweep, bf16, N=8192, d=64, causal, Q,K ~ N(0,4); one head
     run_case(ea, 1, 1, 8192, 64, "bf16", True, alpha, 2.0, seed=5000)
