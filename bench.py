@@ -73,6 +73,33 @@ def sustained_mfma_tflops(ea, dev):
     return out
 
 
+def valu_under_mfma(ea, dev):
+    """The library's co-issue probe: four waves per SIMD, each round 16 MFMAs 32x32x16 and n
+    independent v_add_u32 per wave; ns per round with the MFMAs alone, the additions alone, and
+    both, and the share of the matrix pipe's time under which the additions disappeared.  This is
+    what bounds a kernel that handles every score with vector instructions from below."""
+    sink = torch.empty(512 * 512, dtype=torch.float32, device=dev)
+    iters = 20000
+
+    def timed(nv, mf):
+        ea.entmax_attn_coissue_probe(sink, 200, nv, mf)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ea.entmax_attn_coissue_probe(sink, iters, nv, mf)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e6 / iters
+
+    mfma = timed(0, True)
+    out = {"waves_per_simd": 4, "mfma_per_round_per_simd": 64, "mfma_only_ns": round(mfma, 1), "points": []}
+    for nv in (64, 128, 256):
+        alone, both = timed(nv, False), timed(nv, True)
+        out["points"].append({"v_add_per_round_per_simd": 4 * nv, "valu_only_ns": round(alone, 1), "both_ns": round(both, 1),
+                              "hidden_share_of_mfma_time": round(max(0.0, mfma + alone - both) / mfma, 3)})
+    return out
+
+
 def block_sparsity(mask, T, causal):
     m = mask.cpu().numpy().view(np.uint32)
     set_bits = int(np.unpackbits(m.view(np.uint8)).sum())
@@ -355,6 +382,7 @@ def main():
     # the same matrix cores without any of the kernels' other work, for context: Gaussian operands,
     # sustained; `peak` above stays the published figure
     roofline["sustained_mfma_tflops_measured"] = sustained_mfma_tflops(ea, dev)
+    roofline["valu_under_mfma_measured"] = valu_under_mfma(ea, dev)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:

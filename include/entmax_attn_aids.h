@@ -63,6 +63,17 @@ int entmax_attn_gather_enable(int on);
  */
 int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters, void* hip_stream);
 
+/*
+ * Co-issue probe (measurement aid: how much vector-ALU work hides under the matrix pipe, the figure
+ * behind the distance of the score-handling kernels from the matrix roofline).  Launches 512
+ * work-groups of 8 wavefronts (four per SIMD of an MI355X); every wavefront runs `iters` rounds of
+ * 16 MFMAs 32x32x16 bf16 (if with_mfma) followed by valu_per_round independent v_add_u32
+ * (0 only with with_mfma; else 64, 128 or 256), registers only.  `sink`: device pointer to
+ * 512 * 512 floats.  The caller times the launch; time / iters is the time of one round on every
+ * SIMD (64 MFMAs and 4 * valu_per_round additions).  EA_ERR_SHAPE for other counts.
+ */
+int entmax_attn_coissue_probe(float* sink, int iters, int valu_per_round, int with_mfma, void* hip_stream);
+
 /* Histogram bins B per unit of (alpha-1) s used by the threshold kernels (introspection for tests
  * and the benchmark report): the bracket after the histogram solve is 1/B wide (Prop. 1). */
 int entmax_attn_histogram_bins(void);

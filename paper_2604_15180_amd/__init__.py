@@ -7,5 +7,5 @@ from .binding import (  # noqa: F401
     read_stats, STAT_NAMES, entmax_attn_timer_enable, entmax_attn_timer_read, entmax_attn_mfma_probe,
     entmax_attn_decode, entmax_attn_decode_workspace_bytes, entmax_attn_gather_enable,
     entmax_attn_decode_static, entmax_attn_decode_static_max_bytes, entmax_attn_fwd_histogram_bounds,
-    entmax_attn_right_edge_enable,
+    entmax_attn_right_edge_enable, entmax_attn_coissue_probe,
 )

@@ -81,6 +81,8 @@ def lib():
         L.entmax_attn_fwd_histogram_bounds.argtypes = [vp, sz, ci, ci, ci, ci, ci, vp, vp, vp]
         L.entmax_attn_mfma_probe.restype = ci
         L.entmax_attn_mfma_probe.argtypes = [vp, vp, ci, ci, vp]
+        L.entmax_attn_coissue_probe.restype = ci
+        L.entmax_attn_coissue_probe.argtypes = [vp, ci, ci, ci, vp]
         L.entmax_attn_strerror.restype = ctypes.c_char_p
         L.entmax_attn_strerror.argtypes = [ci]
         _lib = L
@@ -278,6 +280,14 @@ def entmax_attn_mfma_probe(data, sink, groups, iters):
     _check(lib().entmax_attn_mfma_probe(_ptr(data), _ptr(sink), int(groups), int(iters),
                                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
     return float(groups) * 4 * iters * 32 * 32768.0
+
+
+def entmax_attn_coissue_probe(sink, iters, valu_per_round, with_mfma):
+    """Enqueue the co-issue probe on the current stream (sink: >= 512 * 512 floats on the GPU)."""
+    if not (sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= 512 * 512):
+        raise ValueError("entmax_attn_coissue_probe: sink = 512 * 512 floats on the GPU")
+    _check(lib().entmax_attn_coissue_probe(_ptr(sink), int(iters), int(valu_per_round), int(bool(with_mfma)),
+                                            ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)))
 
 
 def entmax_attn_right_edge_enable(on):

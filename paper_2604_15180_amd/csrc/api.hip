@@ -177,6 +177,36 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const f16x8* data, floa
     sink[blockIdx.x * 256 + threadIdx.x] = t;
 }
 
+// How much vector-ALU work hides under the matrix pipe: every wave runs `iters` rounds of 16
+// dependent-in-pairs 32x32x16 bf16 MFMAs (MF) followed by NV independent v_add_u32; 8 waves per
+// group, and the fixed grid of 512 groups puts four waves on every SIMD of an MI355X, so one
+// wave's additions can run while another's MFMAs do.  Registers only, no memory traffic.
+template <int NV, bool MF>
+__global__ __launch_bounds__(512) void coissue_probe_kernel(float* sink, int iters, float seed) {
+    f32x16 c0, c1;
+    for (int v = 0; v < 16; ++v) { c0[v] = 0.f; c1[v] = 0.f; }
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) { a[i] = (__bf16)(seed + threadIdx.x * 0.001f + i); b[i] = (__bf16)(seed * 0.5f + i); }
+    unsigned x0 = threadIdx.x, x1 = 1, x2 = 2, x3 = 3;
+    for (int it = 0; it < iters; ++it) {
+        if constexpr (MF) {
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c0) : "v"(a), "v"(b));
+                asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c1) : "v"(a), "v"(b));
+            }
+        }
+#pragma unroll
+        for (int n = 0; n < NV / 2; ++n) {
+            asm volatile("v_add_u32 %0, %0, %1" : "+v"(x0) : "v"(x1));
+            asm volatile("v_add_u32 %0, %0, %1" : "+v"(x2) : "v"(x3));
+        }
+    }
+    float t = (float)(x0 + x2);
+    for (int v = 0; v < 16; ++v) t += c0[v] + c1[v];
+    sink[blockIdx.x * 512 + threadIdx.x] = t;
+}
+
 namespace ea {
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 void timer_begin() { timer_begin_call(); }
@@ -413,11 +443,31 @@ int entmax_attn_mfma_probe(const void* data, float* sink, int groups, int iters,
     return EA_OK;
 }
 
+int entmax_attn_coissue_probe(float* sink, int iters, int valu_per_round, int with_mfma, void* hip_stream) {
+    if (!sink) return EA_ERR_NULL;
+    if (iters <= 0) return EA_ERR_SHAPE;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const dim3 grid(512), block(512);
+    const int key = valu_per_round * 2 + (with_mfma ? 1 : 0);
+    switch (key) {
+        case 1: hipLaunchKernelGGL((coissue_probe_kernel<0, true>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 64 * 2: hipLaunchKernelGGL((coissue_probe_kernel<64, false>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 64 * 2 + 1: hipLaunchKernelGGL((coissue_probe_kernel<64, true>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 128 * 2: hipLaunchKernelGGL((coissue_probe_kernel<128, false>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 128 * 2 + 1: hipLaunchKernelGGL((coissue_probe_kernel<128, true>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 256 * 2: hipLaunchKernelGGL((coissue_probe_kernel<256, false>), grid, block, 0, s, sink, iters, 1.f); break;
+        case 256 * 2 + 1: hipLaunchKernelGGL((coissue_probe_kernel<256, true>), grid, block, 0, s, sink, iters, 1.f); break;
+        default: return EA_ERR_SHAPE;
+    }
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
 const char* entmax_attn_strerror(int code) {
     switch (code) {
         case EA_OK: return "ok";
         case EA_ERR_NULL: return "a required pointer is NULL";
-        case EA_ERR_ALPHA: return "alpha must be finite and in (1, 2]";
+        case EA_ERR_ALPHA: return "alpha must be finite and in (1, 3]";
         case EA_ERR_SHAPE: return "bad shape: need B,H > 0, N a positive multiple of 64 (<= 131072), d in {64, 128}";
         case EA_ERR_DTYPE: return "unknown dtype";
         case EA_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";

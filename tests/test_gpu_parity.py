@@ -394,6 +394,18 @@ def test_mfma_probe_runs(ea):
     assert torch.all(sink == 3 * 8 * 16 * 64).item()
     with pytest.raises(ValueError):
         ea.entmax_attn_mfma_probe(data[:100], sink, 4, 3)
+    # the co-issue probe: each lane ends with x0 + x2 = tid + 2 + 2 n (n = rounds x additions / 2)
+    # plus its 32 accumulator entries; without MFMAs those are zero
+    sink2 = torch.full((512 * 512,), float("nan"), device="cuda")
+    ea.entmax_attn_coissue_probe(sink2, 3, 64, False)
+    torch.cuda.synchronize()
+    tid = torch.arange(512, device="cuda", dtype=torch.float32).repeat(512)
+    assert torch.equal(sink2, tid + 2 + 3 * 32 * (1 + 3))
+    ea.entmax_attn_coissue_probe(sink2, 2, 0, True)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink2).all().item()
+    with pytest.raises(ea.EntmaxAttnError):
+        ea.entmax_attn_coissue_probe(sink2, 2, 100, True)
 
 
 def test_c2_exact_config(ea):
