@@ -584,12 +584,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    gm[qb][g] = C[g >> 1][qb][8 * (g & 1)];
-#pragma unroll
-                    for (int v = 1; v < 8; ++v) gm[qb][g] = fmaxf(gm[qb][g], C[g >> 1][qb][8 * (g & 1) + v]);
-                }
-                lm[qb] = fmaxf(fmaxf(gm[qb][0], gm[qb][1]), fmaxf(gm[qb][2], gm[qb][3]));
+                for (int g = 0; g < 4; ++g) gm[qb][g] = max8_raw(C[g >> 1][qb], 8 * (g & 1));
+                lm[qb] = max2_raw(max3_raw(gm[qb][0], gm[qb][1], gm[qb][2]), gm[qb][3]);
             }
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) tm[qb] = xhalf_max(lm[qb]);

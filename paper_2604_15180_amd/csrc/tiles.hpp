@@ -447,7 +447,19 @@ EA_DEV void xhalf_both(float v, float& lo, float& hi) {
     const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     lo = __uint_as_float(r[0]); hi = __uint_as_float(r[1]);
 }
-EA_DEV float xhalf_max(float v) { float a, b; xhalf_both(v, a, b); return fmaxf(a, b); }
+// Maxima as bare instructions: before an IEEE fmaxf the compiler first copies each operand through
+// v_max_f32 x, x (to quiet a signalling NaN), which in the maximum tree of a score tile is a third
+// of the instructions.
+EA_DEV float max3_raw(float a, float b, float c) { float r; asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c)); return r; }
+EA_DEV float max2_raw(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+// maximum of registers off .. off+7 of an accumulator
+EA_DEV float max8_raw(const f32x16& C, int off) {
+    float m = max3_raw(C[off], C[off + 1], C[off + 2]);
+    m = max3_raw(m, C[off + 3], C[off + 4]);
+    m = max3_raw(m, C[off + 5], C[off + 6]);
+    return max2_raw(m, C[off + 7]);
+}
+EA_DEV float xhalf_max(float v) { float a, b; xhalf_both(v, a, b); return max2_raw(a, b); }
 EA_DEV float xhalf_sum(float v) { float a, b; xhalf_both(v, a, b); return a + b; }
 // the value the other lane of the row holds
 EA_DEV float xhalf_other(float v, int h) { float a, b; xhalf_both(v, a, b); return h ? a : b; }
