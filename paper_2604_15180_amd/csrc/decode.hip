@@ -265,8 +265,9 @@ __global__ __launch_bounds__(1024) void decode_entmax_kernel(DecodeParams p) {
         ++iters;
         const float f = F - 1.f;
         if (fabsf(f) <= p.tol) break;
-        const float cand = hybrid_step<AM>(thr, f, G, Hs, r, p.alpha, blo, bhi, prev, p.tol);
-        const bool small = fabsf(cand - thr) < p.tol;
+        const float stol = step_tol(p.tol, thr);
+        const float cand = hybrid_step<AM>(thr, f, G, Hs, r, p.alpha, blo, bhi, prev, stol);
+        const bool small = fabsf(cand - thr) < stol;
         thr = cand;
         if (small) break;
     }

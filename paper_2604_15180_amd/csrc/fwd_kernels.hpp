@@ -125,6 +125,11 @@ EA_DEV bool eval_scores(const f32x16 (&C)[2][QB], const float (&thr)[QB], float 
     return hit;
 }
 
+// Stopping length of the refinement at threshold tau: the caller's tolerance, but no less than four
+// units in the last place of tau - fp32 thresholds of large scores (|tau| > 2 at tol = 1e-6) cannot
+// move by less, and a row would otherwise iterate until its bracket has collapsed.
+EA_DEV float step_tol(float tol, float tau) { return fmaxf(tol, 4.8e-7f * fabsf(tau)); }
+
 // The iterate before the current one and its f, for the secant steps of alpha > 2; t is NaN while
 // there is none (at the start of a kernel: the state is not carried from one kernel to the next).
 struct SecantPrev { float t = __builtin_nanf(""), f = 0.f; };
@@ -415,8 +420,9 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
             float tau = thr[qb];
             if (!done) {
                 SecantPrev none;
-                const float cand_tau = hybrid_step<AM>(tau, f, g, hs, r, hc.alpha, blo[qb], bhi[qb], none, p.tol);
-                done = fabsf(cand_tau - tau) < p.tol;
+                const float stol = step_tol(p.tol, tau);
+                const float cand_tau = hybrid_step<AM>(tau, f, g, hs, r, hc.alpha, blo[qb], bhi[qb], none, stol);
+                done = fabsf(cand_tau - tau) < stol;
                 tau = cand_tau;
             }
             if (active && h == 0) {
@@ -759,8 +765,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
                     f1_last[qb] = -r * g;
                     if (fabsf(f) <= p.tol || p.right_edge) done[qb] = 1;
                     else {
-                        const float cand_tau = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, blo[qb], bhi[qb], prev[qb], p.tol);
-                        if (fabsf(cand_tau - thr[qb]) < p.tol) done[qb] = 1;
+                        const float stol = step_tol(p.tol, thr[qb]);
+                        const float cand_tau = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, blo[qb], bhi[qb], prev[qb], stol);
+                        if (fabsf(cand_tau - thr[qb]) < stol) done[qb] = 1;
                         thr[qb] = cand_tau;
                     }
                     pending |= !done[qb];
@@ -994,7 +1001,7 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                 iters[qb] += 1;
                 const float chord = -fval[qb] / f1_prev[qb];
                 if (fabsf(fval[qb]) <= p.tol) done[qb] = 1;
-                else if (fabsf(chord) < p.tol && f1_prev[qb] < 0.f && hc.alpha <= 2.f) {
+                else if (fabsf(chord) < step_tol(p.tol, thr[qb]) && f1_prev[qb] < 0.f && hc.alpha <= 2.f) {
                     thr[qb] = fminf(fmaxf(thr[qb] + chord, lo[qb]), hi[qb]);
                     done[qb] = 1;
                 } else need = 1;
@@ -1032,8 +1039,9 @@ __global__ __launch_bounds__(NW * 64) void out_kernel(Params p) {
                         if (!have_f) iters[qb] += 1;
                         if (!have_f && fabsf(f) <= p.tol) done[qb] = 1;
                         else {
-                            const float cand = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, lo[qb], hi[qb], prev[qb], p.tol);
-                            if (fabsf(cand - thr[qb]) < p.tol) done[qb] = 1;
+                            const float stol = step_tol(p.tol, thr[qb]);
+                            const float cand = hybrid_step<AM>(thr[qb], f, g, hs, r, hc.alpha, lo[qb], hi[qb], prev[qb], stol);
+                            if (fabsf(cand - thr[qb]) < stol) done[qb] = 1;
                             thr[qb] = cand;
                         }
                         pending |= !done[qb];
