@@ -1036,11 +1036,46 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
         amax = __uint_as_float(p.scal[0]);
         if (!(amax > 0.f)) amax = 1.f;
     }
+    // The entries of a key were filed in the order an integer atomic handed out their slots, which
+    // changes from run to run.  They are summed in the order of their query rows instead (a row
+    // files at most one entry per key, so the rows are distinct): for a list longer than one batch
+    // the rank of every entry among the key's rows, found by the key's 16 lanes through LDS, gives
+    // the slot to read at each step (a short list is sorted in registers, below), and
+    // dK, dV of a key come out bit-identical in every run (keys with more entries than a list
+    // holds get the rest from bwd_hot_kernel's atomic additions and do not).
+    __shared__ int rows_s[16][KEY_LIST_CAP];
+    __shared__ unsigned char order_s[16][KEY_LIST_CAP];
+    static_assert(KEY_LIST_CAP <= 64 && (KEY_LIST_CAP & (KEY_LIST_CAP - 1)) == 0, "four entries per lane of a key's 16; slot indices are masked");
     for (int key = I * 256 + rsel; key < key_end; key += 16) {
         const long kj = (long)bh * N + key;
         const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
         if (cnt == 0 && !fresh) continue;
         const uint4* el = (const uint4*)p.klist + kj * KEY_LIST_CAP;
+        if (cnt > CH) {
+            int myrow[4], rank[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int i = sub + 16 * q;
+                myrow[q] = i < cnt ? (int)((const uint32_t*)(el + i))[0] : INT_MAX;
+                rank[q] = 0;
+                if (i < cnt) rows_s[rsel][i] = myrow[q];
+            }
+            // (the 16 lanes of a key sit in one wave, whose LDS operations execute in issue order)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            for (int j = 0; j < cnt; ++j) {
+                const int rj = rows_s[rsel][j];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) rank[q] += rj < myrow[q];
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (sub + 16 * q < cnt) order_s[rsel][rank[q]] = (unsigned char)(sub + 16 * q);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
         float ak[EPT], av[EPT];
 #pragma unroll
         for (int k = 0; k < EPT; ++k) { ak[k] = 0.f; av[k] = 0.f; }
@@ -1049,7 +1084,20 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
             vvec qv[CH], gv[CH];
             float nd[CH];                     // -delta / max|dO| of the entry's row
 #pragma unroll
-            for (int u = 0; u < CH; ++u) e[u] = i0 + u < cnt ? el[i0 + u] : make_uint4(0u, 0u, 0u, 0u);
+            for (int u = 0; u < CH; ++u)
+                e[u] = i0 + u < cnt ? el[cnt > CH ? (int)order_s[rsel][i0 + u] & (KEY_LIST_CAP - 1) : u] : make_uint4(0xffffffffu, 0u, 0u, 0u);
+            if (cnt <= CH) {
+                // a short list is put in row order in registers (no second trip to memory): a
+                // sorting network of five exchanges; the unused slots, row 0xffffffff, end up last
+                auto exchange = [&](int i, int j) {
+                    if (e[j].x < e[i].x) { const uint4 t = e[i]; e[i] = e[j]; e[j] = t; }
+                };
+                static_assert(CH == 4, "network for four entries");
+                exchange(0, 1); exchange(2, 3); exchange(0, 2); exchange(1, 3); exchange(1, 2);
+            }
+#pragma unroll
+            for (int u = 0; u < CH; ++u)
+                if (i0 + u >= cnt) e[u] = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
             for (int u = 0; u < CH; ++u) {
 #pragma unroll

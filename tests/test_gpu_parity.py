@@ -279,13 +279,11 @@ def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma):
     g3 = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=wb, fwd_workspace=wf)
     torch.cuda.synchronize()
     sb3 = ea.read_stats(wb)
-    # (only the row groups whose output the forward gathered have their supports in its lists: with
-    # fp32 inputs at this scale the forward gathers none, and the backward then stays on the matrix kernels)
-    assert sb3["bwd_list_subtiles"] == 0 and sb3["bwd_gather_rows"] == (res[True][8] if res[True][7] > 0 else 0)
-    for name, a, b in zip(("dQ", "dK", "dV"), g3, res[True][4:7] if res[True][7] > 0 else res[False][4:7]):
-        err = ((a.double() - b.double()).abs() / (1 + b.double().abs())).max().item()
-        print(f"  {name}: supports from the forward's lists vs found again {err:.3e}", flush=True)
-        assert err <= 1e-5
+    # (only the row groups whose output the forward gathered have their supports in its lists; the
+    # others stay on the matrix kernels, so the third run may mix both routes; it is compared with
+    # the oracle below like the other two)
+    assert sb3["bwd_list_subtiles"] == 0 and sb3["bwd_gather_rows"] <= min(res[True][7], res[True][8])
+    assert sb3["bwd_gather_rows"] > 0 or res[True][7] == 0
     print("  rows by gather: forward", res[True][7], "backward", res[True][8], "of", B * H * N, flush=True)
     assert res[True][8] > B * H * N // 2 and (res[True][7] > B * H * N // 2 or dtype == "f32")
     assert res[False][7] == 0 and res[False][8] == 0
@@ -306,6 +304,11 @@ def test_gather_and_matrix_paths_agree(ea, dtype, d, sigma):
         print(f"  {name}: gather vs matrix {np.abs(a - b).max():.3e}, {worst:.3f} of what is allowed; against the oracle "
               f"{(np.abs(a - oracle) / allowed[name]).max():.3f} / {(np.abs(b - oracle) / allowed[name]).max():.3f}", flush=True)
         assert worst <= 1.0 and (np.abs(a - oracle) <= allowed[name]).all() and (np.abs(b - oracle) <= allowed[name]).all()
+        if name != "O":
+            c = parity.to_np64(g3[("dQ", "dK", "dV").index(name)])
+            print(f"  {name}: supports from the forward's lists ({sb3['bwd_gather_rows']} rows by gather): "
+                  f"{(np.abs(c - oracle) / allowed[name]).max():.3f} of what is allowed", flush=True)
+            assert (np.abs(c - oracle) <= allowed[name]).all() and (np.abs(c - a) <= 2 * allowed[name]).all()
 
 
 @pytest.mark.parametrize("dtype,d,N,sigma,causal,hubs", [("bf16", 128, 3072, 3.0, False, (5, 1777)),
@@ -433,20 +436,24 @@ def test_c4_shape_planted_keys(ea):
     assert sparsity > 0.5
 
 
-def test_backward_twice_gives_the_same_gradients(ea):
+@pytest.mark.parametrize("hub", [False, True])
+def test_backward_twice_gives_the_same_gradients(ea, hub):
     # run-to-run stability.  The matrix kernels accumulate in a fixed order: bit-identical.  On the
-    # gather path a key's entries are filed in the order an integer atomic hands out slots and the
-    # entries of overfull keys arrive as fp32 atomic additions, so dK, dV may differ in the last bits
-    # between runs; dQ is formed row by row in list order and must not.
+    # gather path a key's entries are filed in the order an integer atomic hands out slots, but
+    # summed in the order of their query rows: bit-identical too - except for a key that more rows
+    # attend to than its list holds (the hub), whose remaining entries arrive as fp32 atomic
+    # additions: its dK, dV may differ in the last bits between runs.  dQ is formed row by row in
+    # list order and must not.
     B, H, N, d, alpha, causal, sigma = 1, 2, 3072, 128, 1.5, False, 3.0
     q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sigma, seed=97)
-    g = torch.Generator().manual_seed(98)
-    dirn = torch.randn(d, generator=g)
-    dirn = dirn / dirn.norm()
-    amp = (sigma * sigma * 3.5 * d ** 0.5) ** 0.5
-    q = (q.float() + amp * dirn).to(q.dtype)
-    k = k.clone()
-    k[:, :, 11] = (k[:, :, 11].float() + amp * dirn).to(k.dtype)        # one hub key: more entries than its list holds
+    if hub:
+        g = torch.Generator().manual_seed(98)
+        dirn = torch.randn(d, generator=g)
+        dirn = dirn / dirn.norm()
+        amp = (sigma * sigma * 3.5 * d ** 0.5) ** 0.5
+        q = (q.float() + amp * dirn).to(q.dtype)
+        k = k.clone()
+        k[:, :, 11] = (k[:, :, 11].float() + amp * dirn).to(k.dtype)        # one hub key: more entries than its list holds
     Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
     O, tau, mask = ea.entmax_attn_fwd(Q, K, V, alpha, causal)
     try:
@@ -462,8 +469,13 @@ def test_backward_twice_gives_the_same_gradients(ea):
             print(f"  gather paths {'on' if on else 'off'}: rows by gather {rows}, spread between two runs {spread}", flush=True)
             assert (rows > 0) == on
             assert spread["dQ"] == 0.0
-            if on:
-                assert spread["dK"] <= 1e-4 and spread["dV"] <= 1e-4          # fp32 sums in another order: far inside the 1e-2 bar
+            if on and hub:
+                assert spread["dK"] <= 1e-4 and spread["dV"] <= 1e-4          # fp32 atomics in another order: far inside the 1e-2 bar
+                # the hub, and the few keys whose own component along the hub's direction makes hundreds
+                # of rows attend to them too; every other key repeats exactly
+                moved = ((runs[0][1] != runs[1][1]).any(-1) | (runs[0][2] != runs[1][2]).any(-1))
+                print("  keys that differ between the runs:", int(moved.sum().item()), "of", moved.numel(), flush=True)
+                assert moved[:, :, 11].all().item() and moved.float().mean().item() < 0.02
             else:
                 assert spread["dK"] == 0.0 and spread["dV"] == 0.0
     finally:
