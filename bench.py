@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused alpha-entmax attention hot path on one MI355X.
 
-Workload (configs[2] of the benchmark spec, the one its metric is quoted on): alpha = 1.5, bf16,
+Workload (the long-context sparsity sweep the headline metric is quoted on): alpha = 1.5, bf16,
 B = 2, H = 16, N = 16384, d = 128, causal, Q,K ~ N(0, sigma^2) with sigma swept over
 {1, 2, 3, 4}, V, dO ~ N(0, 1); seeded synthetic tensors, resident in HBM before timing.
 One step = forward + backward over each of the four sigma batches.  `value` is the
