@@ -1045,16 +1045,17 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     // holds get the rest from bwd_hot_kernel's atomic additions and do not).
     __shared__ int rows_s[16][KEY_LIST_CAP];
     __shared__ unsigned char order_s[16][KEY_LIST_CAP];
-    static_assert(KEY_LIST_CAP <= 64 && (KEY_LIST_CAP & (KEY_LIST_CAP - 1)) == 0, "four entries per lane of a key's 16; slot indices are masked");
+    constexpr int PER_LANE = KEY_LIST_CAP / 16;      // entries of a key's list per lane of its 16
+    static_assert(KEY_LIST_CAP <= 256 && (KEY_LIST_CAP & (KEY_LIST_CAP - 1)) == 0 && KEY_LIST_CAP >= 16, "slot indices are bytes, and masked");
     for (int key = I * 256 + rsel; key < key_end; key += 16) {
         const long kj = (long)bh * N + key;
         const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
         if (cnt == 0 && !fresh) continue;
         const uint4* el = (const uint4*)p.klist + kj * KEY_LIST_CAP;
         if (cnt > CH) {
-            int myrow[4], rank[4];
+            int myrow[PER_LANE], rank[PER_LANE];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < PER_LANE; ++q) {
                 const int i = sub + 16 * q;
                 myrow[q] = i < cnt ? (int)((const uint32_t*)(el + i))[0] : INT_MAX;
                 rank[q] = 0;
@@ -1067,10 +1068,10 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
             for (int j = 0; j < cnt; ++j) {
                 const int rj = rows_s[rsel][j];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) rank[q] += rj < myrow[q];
+                for (int q = 0; q < PER_LANE; ++q) rank[q] += rj < myrow[q];
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
+            for (int q = 0; q < PER_LANE; ++q)
                 if (sub + 16 * q < cnt) order_s[rsel][rank[q]] = (unsigned char)(sub + 16 * q);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
