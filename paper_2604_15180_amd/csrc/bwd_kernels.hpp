@@ -690,7 +690,7 @@ __global__ __launch_bounds__(NW * 64) void bwd_list_kernel(Params p) {
     // head - still has one entry or more per row, and is cheap either way: it goes with the rest,
     // so that the matrix kernels' input copies are not made for its sake alone)
     // (the matrix kernels' time per tile goes with D, the gather's time per entry hardly does -
-    // measured break-even: about 21 entries per tile at D = 128, 5 at D = 64; the power functions
+    // measured break-even: about 32 entries per tile at D = 128, 8 at D = 64; the power functions
     // of general alpha weigh on every entry)
     constexpr int PER_TILE_X128 = BWD_ENTRIES_PER_TILE * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);
     constexpr int PER_ROW_X128 = BWD_ENTRIES_PER_ROW * D * D / 128 / (AM == ALPHA_GEN ? 2 : 1);

@@ -12,7 +12,7 @@ constexpr int MAX_W = 64;       // mask words per row
 constexpr int GATHER_LIST_MAX = 320, GATHER_SUP_MAX = 48;
 // Backward: support entries per lane list (two lists per row), entries per key in the lists by key,
 // and the non-zeros per marked 64 x 64 tile up to which a row group takes the gather path.
-constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 128, BWD_ENTRIES_PER_TILE = 21, BWD_ENTRIES_PER_ROW = 6, BWD_FEW_TILES = 40;
+constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 128, BWD_ENTRIES_PER_TILE = 32, BWD_ENTRIES_PER_ROW = 6, BWD_FEW_TILES = 40;
 // The gather kernels' fixed cost is a few passes over dK and dV; below this many marked tiles per
 // 64-row block (at head dim 128; twice as many at 64) the matrix kernels' whole time is less.
 constexpr int BWD_MIN_TILES_PER_BLOCK = 16;
