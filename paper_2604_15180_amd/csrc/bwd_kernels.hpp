@@ -848,9 +848,13 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
-    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    // a work-group takes GATHER_ROWS rows of a row group (one or a few per 16 lanes): the rows are
+    // chains of dependent loads, so many short work-groups hide their latency better than few long ones
+    const int N = p.N, G = (N + p.grows - 1) / p.grows, parts = p.grows / GATHER_ROWS;
     int bh, I;
-    map_block(blockIdx.x, p.BH, G, bh, I);
+    map_block(blockIdx.x, p.BH, G * parts, bh, I);
+    const int part = I % parts;
+    I /= parts;
     if (!p.gflag[(long)bh * G + I]) return;
     const HeadConsts hc = head_consts(p, bh);
     const float c = hc.c, r = hc.r;
@@ -866,8 +870,8 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(Params p) {
     const elem* Gh = (const elem*)p.dO + hoff;
     const int cap8 = p.list_cap * 8;         // bytes of one lane list
     const char* lists_h = (const char*)p.lists + (size_t)bh * N * (size_t)(2 * cap8);
-    const int row_end = min(N, (I + 1) * p.grows);
-    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+    const int row_end = min(N, I * p.grows + (part + 1) * GATHER_ROWS);
+    for (int row = I * p.grows + part * GATHER_ROWS + rsel; row < row_end; row += 16) {
         const long gi = (long)bh * N + row;
         const float tau = p.tau[gi];
         const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];
@@ -961,9 +965,13 @@ __global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
     constexpr int EPT = D / 16;
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
-    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    // a work-group takes GATHER_ROWS rows of a row group (one or a few per 16 lanes): the rows are
+    // chains of dependent loads, so many short work-groups hide their latency better than few long ones
+    const int N = p.N, G = (N + p.grows - 1) / p.grows, parts = p.grows / GATHER_ROWS;
     int bh, I;
-    map_block(blockIdx.x, p.BH, G, bh, I);
+    map_block(blockIdx.x, p.BH, G * parts, bh, I);
+    const int part = I % parts;
+    I /= parts;
     if (!p.gflag[(long)bh * G + I]) return;
     const HeadConsts hc = head_consts(p, bh);
     const float c = hc.c, r = hc.r;
@@ -978,8 +986,8 @@ __global__ __launch_bounds__(256) void bwd_hot_kernel(Params p) {
     const elem* Gh = (const elem*)p.dO + hoff;
     const int cap8 = p.list_cap * 8;
     const char* lists_h = (const char*)p.lists + (size_t)bh * N * (size_t)(2 * cap8);
-    const int row_end = min(N, (I + 1) * p.grows);
-    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+    const int row_end = min(N, I * p.grows + (part + 1) * GATHER_ROWS);
+    for (int row = I * p.grows + part * GATHER_ROWS + rsel; row < row_end; row += 16) {
         const long gi = (long)bh * N + row;
         if (p.defer[gi] == 0) continue;
         const float tau = p.tau[gi], delta = -p.delta[gi] * amax;
@@ -1023,13 +1031,13 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
-    const int N = p.N, G = (N + 255) / 256;
+    const int N = p.N, G = (N + BWD_COLS_KEYS - 1) / BWD_COLS_KEYS;
     int bh, I;
     map_block(blockIdx.x, p.BH, G, bh, I);
     const long hoff = (long)bh * N * D;
     const elem* Qh = (const elem*)p.Q + hoff + sub * EPT;
     const elem* Gh = (const elem*)p.dO + hoff + sub * EPT;
-    const int key_end = min(N, (I + 1) * 256);
+    const int key_end = min(N, (I + 1) * BWD_COLS_KEYS);
     const bool fresh = *p.nplain == 0;
     float amax = 1.f;                        // the stored deltas are in units of max|dO| (see bwd_rows_kernel)
     if constexpr (SCALED) {
@@ -1047,7 +1055,7 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
     __shared__ unsigned char order_s[16][KEY_LIST_CAP];
     constexpr int PER_LANE = KEY_LIST_CAP / 16;      // entries of a key's list per lane of its 16
     static_assert(KEY_LIST_CAP <= 256 && (KEY_LIST_CAP & (KEY_LIST_CAP - 1)) == 0 && KEY_LIST_CAP >= 16, "slot indices are bytes, and masked");
-    for (int key = I * 256 + rsel; key < key_end; key += 16) {
+    for (int key = I * BWD_COLS_KEYS + rsel; key < key_end; key += 16) {
         const long kj = (long)bh * N + key;
         const int cnt = min(p.kcnt[kj], KEY_LIST_CAP);
         if (cnt == 0 && !fresh) continue;

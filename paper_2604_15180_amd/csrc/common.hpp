@@ -12,6 +12,11 @@ constexpr int MAX_W = 64;       // mask words per row
 constexpr int GATHER_LIST_MAX = 320, GATHER_SUP_MAX = 48;
 // Backward: support entries per lane list (two lists per row), entries per key in the lists by key,
 // and the non-zeros per marked 64 x 64 tile up to which a row group takes the gather path.
+// Work-group sizes of the gather kernels: each 16 lanes take one row (or key) at a time, a chain of
+// dependent loads; 16 rows or keys per work-group (one per 16 lanes) measured 10 - 20 % faster than
+// 128 - 256 per work-group, whose lanes walked 8 - 16 such chains one after the other.
+constexpr int GATHER_ROWS = 16;          // rows per work-group of gather_out / bwd_rows / bwd_hot
+constexpr int BWD_COLS_KEYS = 16;        // keys per work-group of bwd_cols_kernel
 constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 128, BWD_ENTRIES_PER_TILE = 32, BWD_ENTRIES_PER_ROW = 6, BWD_FEW_TILES = 40;
 // The gather kernels' fixed cost is a few passes over dK and dV; below this many marked tiles per
 // 64-row block (at head dim 128; twice as many at 64) the matrix kernels' whole time is less.

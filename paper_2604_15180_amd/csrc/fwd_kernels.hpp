@@ -1091,16 +1091,20 @@ __global__ __launch_bounds__(256) void gather_out_kernel(Params p) {
     typedef elem vvec __attribute__((ext_vector_type(EPT)));
     typedef float ovec __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, sub = tid & 15, rsel = tid >> 4;
-    const int N = p.N, G = (N + p.grows - 1) / p.grows;
+    // a work-group takes GATHER_ROWS rows of a row group (one or a few per 16 lanes): the rows are
+    // chains of dependent loads, so many short work-groups hide their latency better than few long ones
+    const int N = p.N, G = (N + p.grows - 1) / p.grows, parts = p.grows / GATHER_ROWS;
     int bh, I;
-    map_block(blockIdx.x, p.BH, G, bh, I);
+    map_block(blockIdx.x, p.BH, G * parts, bh, I);
+    const int part = I % parts;
+    I /= parts;
     if (!p.gflag[(long)bh * G + I]) return;
     const HeadConsts hc = head_consts(p, bh);
     const float c = hc.c, r = hc.r;
     const elem* Vh = (const elem*)p.V + (long)bh * N * D + sub * EPT;
     const char* lists_h = (const char*)p.lists + (size_t)bh * N * (2 * LIST_CAP * 8);
-    const int row_end = min(N, (I + 1) * p.grows);
-    for (int row = I * p.grows + rsel; row < row_end; row += 16) {
+    const int row_end = min(N, I * p.grows + (part + 1) * GATHER_ROWS);
+    for (int row = I * p.grows + part * GATHER_ROWS + rsel; row < row_end; row += 16) {
         const long gi = (long)bh * N + row;
         const float tau = p.tau[gi];
         const int s0 = p.scnt[gi * 2], tot = s0 + p.scnt[gi * 2 + 1];

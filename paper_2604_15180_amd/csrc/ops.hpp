@@ -97,7 +97,7 @@ struct Ops {
         ScopedKernelTime t(EA_TIMER_OUT, s);
         // sparse row groups: a gather over each row's support; all others: block-sparse matrix products
         if (p.gflag) {
-            rc = launch(gather_out_kernel<E, D, AM>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, p);
+            rc = launch(gather_out_kernel<E, D, AM>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows) * (p.grows / GATHER_ROWS)), 256, s, p);
             if (rc) return rc;
         }
         return launch(out_kernel<E, E2, D, QB, AM, false, NW_OUT, NBUF_OUT>, groups(p, NW_OUT), NW_OUT * 64, s, p);
@@ -169,11 +169,11 @@ struct Ops {
         if (p.gflag) {
             // after dkdv_kernel has stored dK, dV: the listed row groups add their share
             ScopedKernelTime t(EA_TIMER_BWD_GATHER, s);
-            rc = launch(bwd_rows_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
+            rc = launch(bwd_rows_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows) * (p.grows / GATHER_ROWS)), 256, s, po);
             if (rc) return rc;
-            rc = launch(bwd_cols_kernel<E, D, E2::SCALED>, dim3(p.BH * ((p.N + 255) / 256)), 256, s, po);
+            rc = launch(bwd_cols_kernel<E, D, E2::SCALED>, dim3(p.BH * ((p.N + BWD_COLS_KEYS - 1) / BWD_COLS_KEYS)), 256, s, po);
             if (rc) return rc;
-            rc = launch(bwd_hot_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows)), 256, s, po);
+            rc = launch(bwd_hot_kernel<E, D, AM, E2::SCALED>, dim3(p.BH * ((p.N + p.grows - 1) / p.grows) * (p.grows / GATHER_ROWS)), 256, s, po);
             if (rc) return rc;
         }
         return EA_OK;
