@@ -1101,8 +1101,9 @@ __global__ __launch_bounds__(256) void bwd_cols_kernel(Params p) {
                 auto exchange = [&](int i, int j) {
                     if (e[j].x < e[i].x) { const uint4 t = e[i]; e[i] = e[j]; e[j] = t; }
                 };
-                static_assert(CH == 4, "network for four entries");
-                exchange(0, 1); exchange(2, 3); exchange(0, 2); exchange(1, 3); exchange(1, 2);
+                static_assert(CH == 4 || CH == 2, "networks for two and for four entries");
+                if constexpr (CH == 4) { exchange(0, 1); exchange(2, 3); exchange(0, 2); exchange(1, 3); exchange(1, 2); }
+                else exchange(0, 1);
             }
 #pragma unroll
             for (int u = 0; u < CH; ++u)
