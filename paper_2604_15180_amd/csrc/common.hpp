@@ -199,9 +199,7 @@ EA_DEV void stream_tiles_ring(int n, char* ring, int tile_bytes, IssueF issue, C
         if (NB >= 4 && ahead == 2) wait_vm_at_most<2 * LPW>();
         else if (NB >= 3 && ahead == 1) wait_vm_at_most<LPW>();
         else wait_vm_at_most<0>();
-#if !defined(EA_SKEL) || EA_SKEL != 3
         __syncthreads();     // tile `it` has landed for every wave; everyone is done with tile it-1
-#endif
         if (it + NB - 1 < n) issue(it + NB - 1, ring + ((it + NB - 1) % NB) * tile_bytes);
         compute(it, ring + (it % NB) * tile_bytes);
     }

@@ -595,9 +595,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
             }
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) tm[qb] = xhalf_max(lm[qb]);
-#if defined(EA_SKEL) && EA_SKEL != 4
-            { for (int qb = 0; qb < QB; ++qb) run[qb] = fmaxf(run[qb], tm[qb]); return; }
-#endif
             bool rise_any = false;
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) rise_any |= tm[qb] > run[qb];
@@ -684,14 +681,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(PAIR ? 
             }
     };
     stream_tiles_ring<NBUF, KT::NINST / NW>(njt, kring, KT::BYTES,
-        [&](int it, char* buf) {
-#if !defined(EA_SKEL) || EA_SKEL != 2
-            issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane);
-#endif
-        }, sweep_tile);
-#if defined(EA_SKEL) && (EA_SKEL == 4 || EA_SKEL == 5)
-    if (p.N > 0) { if (run[0] == 12345.f) p.tau[tid] = run[0]; return; }
-#endif
+        [&](int it, char* buf) { issue_rows<E, D, NW>(buf, Kh, (long)it * 64, wave, lane); }, sweep_tile);
     for (int i = tid; i < MR * W; i += THREADS) { wm[i] = 0u; fmk[i] = 0u; }   // (the walk ended with a barrier: the ring is free)
     if (tid < MR) over_s[tid] = 0;
     if (tid < 4) gsum[tid] = 0;
