@@ -362,7 +362,9 @@ __global__ __launch_bounds__(NW * 64) void tau_kernel(Params p) {
         float t0[QB];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) t0[qb] = thr[qb];
-        __threadfence();
+        // (the tile maxima read below were stored by lanes of this same wave and are read here for
+        // the first time: waiting for the wave's stores is enough, see tau_list_kernel)
+        wait_loads();
         for (int j0 = 0; j0 < wjt; j0 += 64) {
             _Float16 tm[32][QB];
 #pragma unroll
