@@ -30,7 +30,7 @@ sys.path.insert(0, ROOT)
 MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix peak (published)
 # HBM bytes per launch (fetched + written) on the default workload, from the FETCH_SIZE / WRITE_SIZE
 # passes summarised in profiles/bench_c3_n16k_counters.md (scaled by the library's own copy kernel)
-HBM_TRAFFIC_BYTES = {"tau": 1.80e9, "dq": 0.11e9, "dkdv": 0.23e9}
+HBM_TRAFFIC_BYTES = {"tau": 1.90e9, "dq": 0.05e9, "dkdv": 0.22e9}
 KERNEL_OF_TIMER = {"tau": "tau_list_kernel", "out": "out_kernel", "dq": "dq_kernel", "dkdv": "dkdv_kernel", "bwd_list": "bwd_list_kernel"}
 METRIC = "effective fwd+bwd TFLOP/s vs block sparsity at N=16k; mean τ iterations/row"
 
