@@ -41,7 +41,7 @@ thread_local bool g_gather_enabled = true;      // the gather switch of the call
 thread_local bool g_right_edge = false;         // right-edge binning without refinement (approximate forward), same scope
 
 struct Layout {
-    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, rs_t0, rs_up0, lists, oflag, scnt, gflag, kcnt, klist, defer, total;
+    size_t stats, hc, a, b, c, d, delta, ntau, mask, wmask, tmax, rs_lo, rs_hi, rs_f1, rs_state, rs_t0, rs_up0, lists, oflag, scnt, gflag, kcnt, klist, defer, colcnt, total;
 };
 
 // element size of the stage-2 copies
@@ -90,6 +90,7 @@ Layout bwd_layout(int B, int H, int N, int d, int t) {
     L.kcnt = off; off += align256(BH * N * 4 + 8);               // and two counters: row groups on the matrix path, set mask bits
     L.klist = off; off += align256(BH * N * (size_t)(KEY_LIST_CAP * 16));
     L.defer = off; off += align256(BH * N * 4);
+    L.colcnt = off; off += align256(BH * T * 4);                 // query tiles per key tile's mask column (dkdv_kernel's parts)
     L.total = off;
     return L;
 }
@@ -330,6 +331,7 @@ int bwd_impl(const void* Q, const void* K, const void* V, const void* O, const v
     p.nmarked = p.nplain + 1;
     p.klist = ws + L.klist;
     p.defer = (int32_t*)(ws + L.defer);
+    p.colcnt = (int32_t*)(ws + L.colcnt);
     p.list_cap = BWD_LIST_CAP;
     if (fwd_workspace) {
         // the forward's candidate lists (supports at the front), their counts and group flags

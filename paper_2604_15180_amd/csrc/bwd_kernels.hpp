@@ -460,10 +460,13 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     const int n = lane & 31, h = lane >> 5;
     const int N = p.N, T = p.T, W = p.W;
     int bh, J;
-    map_block(blockIdx.x, p.BH, (N + BC - 1) / BC, bh, J);
-    J = (N + BC - 1) / BC - 1 - J;            // causal: the first key tiles have the longest columns
+    const int GC = (N + BC - 1) / BC, part = p.col_part0 ? 1 + (int)blockIdx.x / (p.BH * GC) : 0;
+    map_block(p.col_part0 ? (int)blockIdx.x % (p.BH * GC) : (int)blockIdx.x, p.BH, GC, bh, J);
+    J = GC - 1 - J;                           // causal: the first key tiles have the longest columns
     // every row group went by gather: bwd_cols_kernel writes dK, dV itself
     if (p.gflag && *p.nplain == 0) return;
+    // a later part of a column that ended before it (the first part's launch left the length)
+    if (part > 0 && p.colcnt[(long)bh * GC + J] <= part * p.col_part_len) return;
     const long k0 = (long)J * BC, kw0 = k0 + wave * 32 * QB;
     const bool active = kw0 < N;
     const long hoff = (long)bh * N * D;
@@ -512,7 +515,25 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         }
         __syncthreads();
     }
-    const int ntl = wcnt[8];
+    int ntl = wcnt[8];
+    if (p.col_part_len > 0) {
+        // Long columns (a key that every later query tile attends to walks up to T tiles while most
+        // columns hold a few) are cut into parts of col_part_len tiles, each worked off by a group
+        // of its own: this one keeps its part of the list, moved to the front.
+        if (part == 0 && tid == 0) p.colcnt[(long)bh * GC + J] = ntl;
+        const int lo = part * p.col_part_len, len = max(0, min(ntl - lo, p.col_part_len));
+        if (part > 0) {
+            int keep[(MAX_T + THREADS - 1) / THREADS];
+#pragma unroll
+            for (int q = 0; q < (MAX_T + THREADS - 1) / THREADS; ++q) keep[q] = q * THREADS + tid < len ? tl[lo + q * THREADS + tid] : 0;
+            __syncthreads();
+#pragma unroll
+            for (int q = 0; q < (MAX_T + THREADS - 1) / THREADS; ++q)
+                if (q * THREADS + tid < len) tl[q * THREADS + tid] = keep[q];
+            __syncthreads();
+        }
+        ntl = len;
+    }
 
     Owned<E, D, QB> kf, vf;
     load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, active ? kw0 : 0, lane);
@@ -606,8 +627,13 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) { settle_acc(XV[db][qb]); settle_acc(XK[db][qb]); }
     if (active) {
-        store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * hc.rho_p, lane);
-        store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * hc.rho_u, lane);
+        if (part == 0) {
+            store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * hc.rho_p, lane);
+            store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * hc.rho_u, lane);
+        } else {
+            add_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * hc.rho_p, lane);
+            add_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * hc.rho_u, lane);
+        }
     }
     {
         const int slot[1] = {4};

@@ -410,6 +410,22 @@ EA_DEV void store_owned_T(float* g, long row0, const f32x16 (&X)[D / 32][QB], co
     }
 }
 
+// The same, added to what is there with fp32 atomics (several work-groups share the rows).
+template <int D, int QB>
+EA_DEV void add_owned_T(float* g, long row0, const f32x16 (&X)[D / 32][QB], float scale, int lane) {
+    const int n = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        float* rowp = g + (row0 + 32 * qb + n) * (long)D;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) atomicAdd(rowp + 32 * db + 8 * a + 4 * h + c, X[db][qb][4 * a + c] * scale);
+    }
+}
+
 template <int D, int QB>
 EA_DEV void store_owned_T(float* g, long row0, const f32x16 (&X)[D / 32][QB], float scale, int lane) {
     float scales[QB];
