@@ -434,6 +434,51 @@ EA_DEV void dkdv_tile_staggered(const char* qbuf, const char* gbuf, const float*
     }
 }
 
+// Which of the MC mask columns jc0.. hold query tile i of head bh (bit c: column jc0 + c); none for
+// query tiles of row groups whose supports were listed (those are left to bwd_cols_kernel).
+template <int MC>
+EA_DEV int column_flags(const Params& p, int bh, int i, int jc0) {
+    if (p.gflag && p.gflag[(long)bh * ((p.N + p.grows - 1) / p.grows) + (i * 64) / p.grows]) return 0;
+    int flags = 0;
+#pragma unroll
+    for (int cidx = 0; cidx < MC; ++cidx) {
+        const int j = jc0 + cidx;
+        if (j >= p.T) continue;
+        const uint32_t w = (uint32_t)p.mask[((long)bh * p.T + i) * p.W + (j >> 5)];
+        flags |= (int)((w >> (j & 31)) & 1u) << cidx;
+    }
+    return flags;
+}
+
+// Length of every key block's mask column, for dkdv_kernel's launch in parts; a column of more than
+// one part has its rows of dK, dV cleared here, since all its parts add to them.
+template <int D, int BC>
+__global__ __launch_bounds__(128) void col_count_kernel(Params p) {
+    constexpr int MC = (BC + 63) / 64;
+    __shared__ int total;
+    const int tid = threadIdx.x;
+    const int GC = (p.N + BC - 1) / BC;
+    int bh, J;
+    map_block(blockIdx.x, p.BH, GC, bh, J);
+    if (p.gflag && *p.nplain == 0) return;
+    if (tid == 0) total = 0;
+    __syncthreads();
+    const int jc0 = J * MC;
+    int mine = 0;
+    for (int i = (p.causal ? jc0 : 0) + tid; i < p.T; i += 128) mine += column_flags<MC>(p, bh, i, jc0) != 0;
+    if (mine) atomicAdd(&total, mine);
+    __syncthreads();
+    const int cnt = total;
+    if (tid == 0) p.colcnt[(long)bh * GC + J] = cnt;
+    if (cnt > p.col_part_len) {
+        const long k0 = (long)J * BC, nk = min((long)BC, p.N - k0);
+        f32x4* const dk = (f32x4*)(p.dK + ((long)bh * p.N + k0) * D);
+        f32x4* const dv = (f32x4*)(p.dV + ((long)bh * p.N + k0) * D);
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        for (long e = tid; e < nk * (D / 4); e += 128) { dk[e] = zero; dv[e] = zero; }
+    }
+}
+
 template <class E, class E2, int D, int QB, int NW, int NBUF>
 struct DkdvSmem {
     static constexpr int BC = 32 * QB * NW;
@@ -460,12 +505,14 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     const int n = lane & 31, h = lane >> 5;
     const int N = p.N, T = p.T, W = p.W;
     int bh, J;
-    const int GC = (N + BC - 1) / BC, part = p.col_part0 ? 1 + (int)blockIdx.x / (p.BH * GC) : 0;
-    map_block(p.col_part0 ? (int)blockIdx.x % (p.BH * GC) : (int)blockIdx.x, p.BH, GC, bh, J);
+    const int GC = (N + BC - 1) / BC, part = (int)blockIdx.x / (p.BH * GC);
+    map_block((int)blockIdx.x % (p.BH * GC), p.BH, GC, bh, J);
     J = GC - 1 - J;                           // causal: the first key tiles have the longest columns
     // every row group went by gather: bwd_cols_kernel writes dK, dV itself
     if (p.gflag && *p.nplain == 0) return;
-    // a later part of a column that ended before it (the first part's launch left the length)
+    // launched in parts (col_part_len > 0): a part past the column's end has nothing to do; all
+    // parts of a column that has several add to rows that col_count_kernel cleared
+    const bool shared_out = p.col_part_len > 0 && p.colcnt[(long)bh * GC + J] > p.col_part_len;
     if (part > 0 && p.colcnt[(long)bh * GC + J] <= part * p.col_part_len) return;
     const long k0 = (long)J * BC, kw0 = k0 + wave * 32 * QB;
     const bool active = kw0 < N;
@@ -489,17 +536,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
     __syncthreads();
     for (int base = i_min; base < T; base += THREADS) {
         const int i = base + tid;
-        int flags = 0;
-        // (query tiles of row groups whose supports were listed are left to bwd_cols_kernel)
-        if (i < T && !(p.gflag && p.gflag[(long)bh * ((N + p.grows - 1) / p.grows) + (i * 64) / p.grows])) {
-#pragma unroll
-            for (int cidx = 0; cidx < MC; ++cidx) {
-                const int j = jc0 + cidx;
-                if (j >= T) continue;
-                const uint32_t w = (uint32_t)p.mask[((long)bh * T + i) * W + (j >> 5)];
-                flags |= (int)((w >> (j & 31)) & 1u) << cidx;
-            }
-        }
+        const int flags = i < T ? column_flags<MC>(p, bh, i, jc0) : 0;
         const unsigned long long bal = __ballot(flags != 0);
         if (lane == 0) wcnt[wave] = __popcll(bal);
         __syncthreads();
@@ -520,7 +557,6 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         // Long columns (a key that every later query tile attends to walks up to T tiles while most
         // columns hold a few) are cut into parts of col_part_len tiles, each worked off by a group
         // of its own: this one keeps its part of the list, moved to the front.
-        if (part == 0 && tid == 0) p.colcnt[(long)bh * GC + J] = ntl;
         const int lo = part * p.col_part_len, len = max(0, min(ntl - lo, p.col_part_len));
         if (part > 0) {
             int keep[(MAX_T + THREADS - 1) / THREADS];
@@ -627,7 +663,7 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) { settle_acc(XV[db][qb]); settle_acc(XK[db][qb]); }
     if (active) {
-        if (part == 0) {
+        if (!shared_out) {
             store_owned_T<D, QB>(p.dV + hoff, kw0, XV, go_amax * hc.rho_p, lane);
             store_owned_T<D, QB>(p.dK + hoff, kw0, XK, p.inv_sqrt_d * go_amax * hc.rho_u, lane);
         } else {

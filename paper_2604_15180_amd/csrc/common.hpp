@@ -15,7 +15,10 @@ constexpr int GATHER_LIST_MAX = 320, GATHER_SUP_MAX = 48;
 // Work-group sizes of the gather kernels: each 16 lanes take one row (or key) at a time, a chain of
 // dependent loads; 16 rows or keys per work-group (one per 16 lanes) measured 10 - 20 % faster than
 // 128 - 256 per work-group, whose lanes walked 8 - 16 such chains one after the other.
-constexpr int COL_PART = 128;            // query tiles per part of a mask column in dkdv_kernel (columns of more than two parts are shared out)
+// Query tiles per part of a mask column in dkdv_kernel from 65536 tokens on (half that below;
+// every part pays the column walk, the owned K, V fragments and atomic adds of its results, and an
+// empty part a work-group's launch: parts of 32 or 16 tiles measured slower at every length).
+constexpr int COL_PART = 128;
 constexpr int GATHER_ROWS = 16;          // rows per work-group of gather_out / bwd_rows / bwd_hot
 constexpr int BWD_COLS_KEYS = 16;        // keys per work-group of bwd_cols_kernel
 constexpr int BWD_LIST_CAP = 64, KEY_LIST_CAP = 128, BWD_ENTRIES_PER_TILE = 32, BWD_ENTRIES_PER_ROW = 6, BWD_FEW_TILES = 40;
@@ -59,11 +62,11 @@ struct Params {
     // them over), and then the forward's group flags and their row-group size
     int right_edge;      // forward: thresholds are the right-edge histogram roots, no refinement (Sec. 3.2)
     // dkdv_kernel: a key block's mask column (its list of query tiles) is worked off in parts of
-    // col_part_len tiles; this launch takes part col_part0 (0: one work-group per key block, stores
-    // dK, dV and the list's length in colcnt) or parts 1.. (col_part0 = 1: work-groups past the
-    // first BH * key blocks take part 1 + blockIdx / that, leave at once where colcnt says the list
-    // ends before their part, and add to dK, dV atomically).  col_part_len = 0: whole columns.
-    int col_part_len, col_part0;
+    // col_part_len tiles: work-group blockIdx takes part blockIdx / (BH * key blocks), leaves at
+    // once where colcnt (the columns' lengths, from col_count_kernel) says the list ends before its
+    // part, and adds to dK, dV atomically where the column has several parts (col_count_kernel
+    // cleared those rows).  col_part_len = 0: whole columns, one work-group each, no counts.
+    int col_part_len;
     int32_t* colcnt;
     int list_cap;
     const int32_t* fwd_gflag; const unsigned int* fwd_scal;   // (fwd_scal[2] = rows per row group of the forward's flags)

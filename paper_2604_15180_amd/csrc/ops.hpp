@@ -163,18 +163,19 @@ struct Ops {
         {
             ScopedKernelTime t(EA_TIMER_DKDV, s);
             constexpr int NB2 = (E2::EPL == 8) ? NBUF_DKDV : 1;     // fp32 tiles are twice as large
-            // mask columns longer than COL_PART query tiles are shared out: a second launch takes
-            // the parts after the first (most of its work-groups leave at once)
-            const int col_parts = p.T > 2 * COL_PART ? (p.T + COL_PART - 1) / COL_PART : 1;
-            p.col_part_len = col_parts > 1 ? COL_PART : 0;
-            p.col_part0 = 0;
-            rc = launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, groups(p, NW_DKDV), NW_DKDV * 64, s, p);
-            if (rc) return rc;
+            // long mask columns are worked off in parts of `len` query tiles when a column can hold
+            // more than four (at 256 tiles the extra work-groups cost more than they gain as soon as
+            // most row groups go by gather): a small kernel counts every column first, then one
+            // launch holds all parts of all columns (most work-groups past the first part leave at once)
+            const int len = p.T >= 8 * COL_PART ? COL_PART : COL_PART / 2;
+            const int col_parts = p.T > 4 * len ? (p.T + len - 1) / len : 1;
+            p.col_part_len = col_parts > 1 ? len : 0;
             if (col_parts > 1) {
-                p.col_part0 = 1;
-                rc = launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, dim3(groups(p, NW_DKDV).x * (col_parts - 1)), NW_DKDV * 64, s, p);
+                rc = launch(col_count_kernel<D, 32 * QB * NW_DKDV>, groups(p, NW_DKDV), 128, s, p);
                 if (rc) return rc;
             }
+            rc = launch(dkdv_kernel<E2, E2, D, QB, AM, NW_DKDV, NB2>, dim3(groups(p, NW_DKDV).x * col_parts), NW_DKDV * 64, s, p);
+            if (rc) return rc;
         }
         if (p.gflag) {
             // after dkdv_kernel has stored dK, dV: the listed row groups add their share

@@ -94,11 +94,12 @@ def test_c4_full_size_one_head(ea):
     print("  ", info, ginfo, flush=True)
 
 
-@pytest.mark.parametrize("N", [4096, 65536])
+@pytest.mark.parametrize("N", [4096, 32768, 65536])
 def test_context_scaling_recipe(ea, N):
     # the second workload's inputs (planted keys, d = 64, sigma = 3; `bench.py --workload context`
     # and the `context` rows of the default line), one head per length against the oracle; the
-    # longest length is the planted case of test_maximum_sequence_length
+    # longest length is the planted case of test_maximum_sequence_length (32768 and 65536 tokens:
+    # the two part lengths of the dK, dV kernel's long mask columns)
     B, H, d, alpha, causal = 1, 1, 64, 1.5, True
     print(f"case context scaling N={N}", flush=True)
     q, k, v, do = workloads.planted_qkv(B, H, N, d, "bf16", 3.0, seed=7000 + N // 4096)
