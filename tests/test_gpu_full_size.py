@@ -161,3 +161,36 @@ def test_flat_attention_at_65536_tokens(ea):
     ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="flat N=65536")
     support = ((alpha - 1) * 0 + (ref["margin"] > 0)).sum()
     print("  flat N=65536", info, "marked tiles", int(support), "mean iters", iters.float().mean().item(), flush=True)
+
+
+def test_long_mask_columns_without_a_causal_mask(ea):
+    # Past 16384 tokens the dK, dV kernel works a key block's mask column off in parts that add their
+    # results with atomics (the causal cases above have a few such columns: planted keys).  Here
+    # there is no causal mask and the gather paths are off, so every key block's column holds most
+    # of the 272 query tiles and every dK, dV row is the sum of five parts; also run twice, which
+    # must agree to rounding (the parts add in any order).
+    B, H, N, d, alpha, causal = 1, 1, 17408, 64, 1.5, False
+    print("case long columns, no causal mask, N=17408", flush=True)
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", 2.0, seed=515)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    try:
+        ea.entmax_attn_gather_enable(False)
+        O, tau, mask = ea.entmax_attn_fwd(Q, K, V, alpha, causal)
+        ws = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
+        dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws)
+        again = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=ws)
+        torch.cuda.synchronize()
+        assert ea.read_stats(ws)["bwd_gather_rows"] == 0
+    finally:
+        ea.entmax_attn_gather_enable(True)
+    T = N // 64
+    bits = torch.tensor([bin(int(w) & 0xffffffff).count("1") for w in mask[0].reshape(-1).tolist()]).sum().item()
+    print(f"  marked tiles {bits} of {T * T}", flush=True)
+    assert bits > T * T // 2
+    spread = {n_: ((a - b).abs() / (1 + a.abs())).max().item() for n_, a, b in zip(("dQ", "dK", "dV"), (dQ, dK, dV), again)}
+    print("  spread between two runs", spread, flush=True)
+    assert spread["dQ"] == 0.0 and spread["dK"] <= 1e-4 and spread["dV"] <= 1e-4
+    print("  oracle", flush=True)
+    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="long columns")
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="long columns")
+    print("  ", info, ginfo, flush=True)
