@@ -1198,6 +1198,61 @@ __global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* 
     }
 }
 
+// The backward's fp16 copies, limited to the rows its matrix kernels will read: one work-group per
+// 64 rows of a head.  QUERY_SIDE (Q, dO): the rows of row groups that are not served by the gather
+// kernels (gflag = 0).  Otherwise (K, V): every row such a group can see - with a causal mask the
+// rows up to the head's last such group, else all rows when the head has one.  gflag null: all rows.
+template <class Ein, class Eout, int D, bool QUERY_SIDE>
+__global__ __launch_bounds__(256) void convert_rows_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
+                                                           const unsigned int* amax_bits, const int32_t* needed,
+                                                           const int32_t* gflag, int grows, int causal,
+                                                           unsigned long long* clamped) {
+    if (needed && *needed == 0) return;     // nobody will read the copy
+    __shared__ int last_plain;
+    const int tiles = N / 64, bh = blockIdx.x / tiles, rt = blockIdx.x % tiles;
+    if (gflag) {
+        const int ng = (N + grows - 1) / grows;
+        const int32_t* gf = gflag + (long)bh * ng;
+        if constexpr (QUERY_SIDE) {
+            if (gf[(rt * 64) / grows]) return;
+        } else {
+            if (threadIdx.x == 0) last_plain = -1;
+            __syncthreads();
+            int mine = -1;
+            for (int g = threadIdx.x; g < ng; g += 256)
+                if (!gf[g]) mine = g;
+            if (mine >= 0) atomicMax(&last_plain, mine);
+            __syncthreads();
+            if (last_plain < 0 || (causal && rt * 64 >= (last_plain + 1) * grows)) return;
+        }
+    }
+    float mul = 1.f;
+    if (amax_bits) {
+        const float a = __uint_as_float(*amax_bits);
+        if (a > 0.f) mul = 1.f / a;
+    }
+    constexpr bool NARROW = std::is_same<Eout, F16>::value && !std::is_same<Ein, F16>::value;
+    int nclamped = 0;
+    const long base = ((long)bh * N + (long)rt * 64) * D;
+    for (int i = threadIdx.x * 8; i < 64 * D; i += 256 * 8) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float x = (float)in[base + i + e] * mul;
+            if constexpr (NARROW) {
+                if (fabsf(x) > 65504.f) { x = copysignf(65504.f, x); ++nclamped; }     // (NaN compares false and stays NaN)
+            }
+            out[base + i + e] = Eout::from_float(x);
+        }
+    }
+    if constexpr (NARROW) {
+        if (__any(nclamped != 0)) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) nclamped += __shfl_xor(nclamped, off);
+            if ((threadIdx.x & 63) == 0 && clamped) atomicAdd(clamped, (unsigned long long)nclamped);
+        }
+    }
+}
+
 static __global__ void zero_stats_kernel(unsigned long long* stats, int n, unsigned int* scal) {
     for (int i = threadIdx.x; i < n; i += blockDim.x) stats[i] = 0ull;
     if (scal && threadIdx.x < 4) scal[threadIdx.x] = 0u;

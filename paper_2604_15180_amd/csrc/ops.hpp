@@ -53,6 +53,16 @@ int launch_convert(const void* in, void* out, long n, const unsigned int* amax_b
     return EA_OK;
 }
 
+template <class Ein, class Eout, int D, bool QUERY_SIDE>
+int launch_convert_rows(const void* in, void* out, const Params& p, const unsigned int* amax_bits, const int32_t* needed,
+                        hipStream_t s) {
+    hipLaunchKernelGGL((convert_rows_kernel<Ein, Eout, D, QUERY_SIDE>), dim3(p.BH * (p.N / 64)), dim3(256), 0, s,
+                       (const typename Ein::elem*)in, (typename Eout::elem*)out, p.N, amax_bits, needed,
+                       (const int32_t*)p.gflag, p.grows, p.causal, p.stats + EA_STAT_F16_CLAMPED);
+    EA_HIP(hipGetLastError());
+    return EA_OK;
+}
+
 // E: input element type; E2: element type of every second-stage product and of the whole backward
 // (for bf16 inputs: fp16; the copies are made by convert_kernel)
 template <class E, class E2, int D, int AM>
@@ -147,11 +157,12 @@ struct Ops {
                 EA_HIP(hipGetLastError());
             }
             if (COPY) {
-                const long n = (long)p.BH * p.N * D;
-                if ((rc = launch_convert<E, E2>(p.K, copies[0], n, nullptr, needed, p.stats, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.Q, copies[1], n, nullptr, needed, p.stats, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.V, copies[2], n, nullptr, needed, p.stats, s))) return rc;
-                if ((rc = launch_convert<E, E2>(p.dO, copies[3], n, E2::SCALED ? p.scal : nullptr, needed, p.stats, s))) return rc;
+                // (only the rows the matrix kernels will read: those of the row groups left to them, and
+                // the keys such a group can see)
+                if ((rc = launch_convert_rows<E, E2, D, false>(p.K, copies[0], p, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert_rows<E, E2, D, true>(p.Q, copies[1], p, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert_rows<E, E2, D, false>(p.V, copies[2], p, nullptr, needed, s))) return rc;
+                if ((rc = launch_convert_rows<E, E2, D, true>(p.dO, copies[3], p, E2::SCALED ? p.scal : nullptr, needed, s))) return rc;
                 p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
             }
         }
