@@ -570,6 +570,17 @@ __global__ __launch_bounds__(NW * 64) void dkdv_kernel(Params p) {
         }
         ntl = len;
     }
+    if (ntl == 0) {
+        // no query tile for these keys (none attends to them, or all that do went by gather): their
+        // dK, dV are zero, and a part of a shared column has nothing to add
+        if (active && !shared_out) {
+            f32x4* const dk = (f32x4*)(p.dK + hoff + kw0 * D);
+            f32x4* const dv = (f32x4*)(p.dV + hoff + kw0 * D);
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            for (int e = lane; e < 32 * QB * D / 4; e += 64) { dk[e] = zero; dv[e] = zero; }
+        }
+        return;
+    }
 
     Owned<E, D, QB> kf, vf;
     load_owned<E, D, QB>(kf, (const elem*)p.K + hoff, active ? kw0 : 0, lane);
