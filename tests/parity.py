@@ -61,9 +61,11 @@ def output_slack(Q, K, V, alpha, causal, tau_ref):
     return out
 
 
-def check_forward(Q, K, V, alpha, causal, O, tau, mask, ref=None, label=""):
+def check_forward(Q, K, V, alpha, causal, O, tau, mask, ref=None, label="", rounding_slack=False):
     """Compare a GPU forward result with the oracle. Returns the oracle result for reuse.
-    alpha > 2: the bound of output_slack is added to the tolerance of O, element by element."""
+    alpha > 2, or rounding_slack (fp32 inputs whose rows attend to dozens of keys: each P carries the
+    rounding of its fp32 score, a few 1e-7 times the score, and O sums them over the support): the
+    bound of output_slack is added to the tolerance of O, element by element."""
     tol = TOL[Q.dtype]
     if ref is None:
         ref = eo.attn_fwd(to_np64(Q), to_np64(K), to_np64(V), alpha, causal, tile=64)
@@ -71,7 +73,7 @@ def check_forward(Q, K, V, alpha, causal, O, tau, mask, ref=None, label=""):
     diffO = np.abs(to_np64(O) - ref["O"])
     dO = diffO.max()
     assert dtau <= tol["tau"], f"{label}: |dtau| = {dtau:.3e} > {tol['tau']}"
-    if alpha > 2.0:
+    if alpha > 2.0 or rounding_slack:
         allowed = tol["O"] + output_slack(Q, K, V, alpha, causal, ref["tau"])
         worst = (diffO / allowed).max()
         assert worst <= 1.0, f"{label}: O error is {worst:.3f} of what is allowed (|dO| = {dO:.3e})"

@@ -67,6 +67,33 @@ def test_fp32_alpha_sweep(ea, alpha):
     run_case(ea, 1, 2, 256, 64, "f32", True, alpha, 1.0, seed=11)
 
 
+@pytest.mark.parametrize("N,d,causal", [(2560, 128, False), (6144, 64, True)])
+def test_fp32_rows_with_large_supports(ea, N, d, causal):
+    # fp32 inputs at alpha = 2, sigma = 1, beyond the size of configs[0]: a row attends to dozens of
+    # keys, P = y passes the rounding of every fp32 score (d products, a few 1e-7 times |s|) straight
+    # into O, and the sum over the support reaches the 1e-5 bar by itself (a randomized sweep met
+    # 1.0e-5 .. 1.3e-5 on such inputs, on both output paths).  O is held to 1e-5 plus the bound that
+    # follows from that rounding and the solver's 1e-6 (parity.output_slack); tau, the mask and the
+    # gradients to their usual bars.
+    alpha = 2.0
+    print(f"case fp32 large supports N={N} d={d} causal={causal}", flush=True)
+    q, k, v, do = workloads.gaussian_qkv(1, 1, N, d, "f32", 1.0, seed=4400 + N)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    O, tau, mask, iters = ea.entmax_attn_fwd(Q, K, V, alpha, causal, want_iters=True)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask)
+    torch.cuda.synchronize()
+    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="fp32 large supports", rounding_slack=True)
+    slack = parity.output_slack(q, k, v, alpha, causal, ref["tau"])
+    support = ((alpha - 1.0) * (parity.to_np64(q)[0, 0] @ parity.to_np64(k)[0, 0].T) / np.sqrt(d) > ref["tau"][0, 0][:, None])
+    if causal:
+        support &= np.tril(np.ones((N, N), bool))
+    print("  fwd", info, "largest slack", slack.max(), "mean support", support.sum(1).mean(), "max iters", iters.max().item(), flush=True)
+    # the bound stays of the order of the bar it is added to
+    assert slack.max() <= 1e-4 and info["dO"] <= 3e-5
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="fp32 large supports", tau_ref=ref["tau"])
+    print("  bwd", ginfo, flush=True)
+
+
 def test_fp32_head_dim_128(ea):
     run_case(ea, 1, 1, 192, 128, "f32", True, 1.5, 1.0, seed=5)
 
