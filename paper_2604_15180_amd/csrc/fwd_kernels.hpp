@@ -1199,21 +1199,27 @@ __global__ __launch_bounds__(256) void convert_kernel(const typename Ein::elem* 
 }
 
 // The backward's fp16 copies, limited to the rows its matrix kernels will read: one work-group per
-// 64 rows of a head.  QUERY_SIDE (Q, dO): the rows of row groups that are not served by the gather
-// kernels (gflag = 0).  Otherwise (K, V): every row such a group can see - with a causal mask the
-// rows up to the head's last such group, else all rows when the head has one.  gflag null: all rows.
-template <class Ein, class Eout, int D, bool QUERY_SIDE>
-__global__ __launch_bounds__(256) void convert_rows_kernel(const typename Ein::elem* in, typename Eout::elem* out, int N,
-                                                           const unsigned int* amax_bits, const int32_t* needed,
+// 64 rows of a head and tensor (blockIdx.y picks the tensor).  Query side (Q, dO): the rows of row
+// groups that are not served by the gather kernels (gflag = 0).  Key side (K, V): every row such a
+// group can see - with a causal mask the rows up to the head's last such group, else all rows when
+// the head has one.  gflag null: all rows.
+struct ConvertJob { const void* in; void* out; const unsigned int* amax_bits; int query_side; };
+struct ConvertJobs { ConvertJob j[4]; };
+template <class Ein, class Eout, int D>
+__global__ __launch_bounds__(256) void convert_rows_kernel(ConvertJobs jobs, int N, const int32_t* needed,
                                                            const int32_t* gflag, int grows, int causal,
                                                            unsigned long long* clamped) {
-    if (needed && *needed == 0) return;     // nobody will read the copy
+    if (needed && *needed == 0) return;     // nobody will read the copies
     __shared__ int last_plain;
+    const ConvertJob job = jobs.j[blockIdx.y];
+    const typename Ein::elem* in = (const typename Ein::elem*)job.in;
+    typename Eout::elem* out = (typename Eout::elem*)job.out;
+    const unsigned int* amax_bits = job.amax_bits;
     const int tiles = N / 64, bh = blockIdx.x / tiles, rt = blockIdx.x % tiles;
     if (gflag) {
         const int ng = (N + grows - 1) / grows;
         const int32_t* gf = gflag + (long)bh * ng;
-        if constexpr (QUERY_SIDE) {
+        if (job.query_side) {
             if (gf[(rt * 64) / grows]) return;
         } else {
             if (threadIdx.x == 0) last_plain = -1;

@@ -53,11 +53,16 @@ int launch_convert(const void* in, void* out, long n, const unsigned int* amax_b
     return EA_OK;
 }
 
-template <class Ein, class Eout, int D, bool QUERY_SIDE>
-int launch_convert_rows(const void* in, void* out, const Params& p, const unsigned int* amax_bits, const int32_t* needed,
+// fp16 copies of K, Q, V, dO (in this order in `copies`) in one launch; dO is divided by max|dO|
+template <class Ein, class Eout, int D>
+int launch_convert_rows(const Params& p, void* const copies[4], const unsigned int* dO_amax_bits, const int32_t* needed,
                         hipStream_t s) {
-    hipLaunchKernelGGL((convert_rows_kernel<Ein, Eout, D, QUERY_SIDE>), dim3(p.BH * (p.N / 64)), dim3(256), 0, s,
-                       (const typename Ein::elem*)in, (typename Eout::elem*)out, p.N, amax_bits, needed,
+    ConvertJobs jobs;
+    jobs.j[0] = ConvertJob{p.K, copies[0], nullptr, 0};
+    jobs.j[1] = ConvertJob{p.Q, copies[1], nullptr, 1};
+    jobs.j[2] = ConvertJob{p.V, copies[2], nullptr, 0};
+    jobs.j[3] = ConvertJob{p.dO, copies[3], dO_amax_bits, 1};
+    hipLaunchKernelGGL((convert_rows_kernel<Ein, Eout, D>), dim3(p.BH * (p.N / 64), 4), dim3(256), 0, s, jobs, p.N, needed,
                        (const int32_t*)p.gflag, p.grows, p.causal, p.stats + EA_STAT_F16_CLAMPED);
     EA_HIP(hipGetLastError());
     return EA_OK;
@@ -159,10 +164,7 @@ struct Ops {
             if (COPY) {
                 // (only the rows the matrix kernels will read: those of the row groups left to them, and
                 // the keys such a group can see)
-                if ((rc = launch_convert_rows<E, E2, D, false>(p.K, copies[0], p, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert_rows<E, E2, D, true>(p.Q, copies[1], p, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert_rows<E, E2, D, false>(p.V, copies[2], p, nullptr, needed, s))) return rc;
-                if ((rc = launch_convert_rows<E, E2, D, true>(p.dO, copies[3], p, E2::SCALED ? p.scal : nullptr, needed, s))) return rc;
+                if ((rc = launch_convert_rows<E, E2, D>(p, copies, E2::SCALED ? p.scal : nullptr, needed, s))) return rc;
                 p.K = copies[0]; p.Q = copies[1]; p.V = copies[2]; p.dO = copies[3];
             }
         }
