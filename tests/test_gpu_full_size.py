@@ -194,3 +194,35 @@ def test_long_mask_columns_without_a_causal_mask(ea):
     ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="long columns")
     _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="long columns")
     print("  ", info, ginfo, flush=True)
+
+
+@pytest.mark.parametrize("d,hub", [(64, False), (128, True)])
+def test_gather_and_matrix_rows_together_at_32768_tokens(ea, d, hub):
+    # i.i.d. inputs at sigma = 1, one head of 32768 tokens: about half (d = 64) or most (d = 128) of
+    # the row groups go by the gather kernels, the early ones stay on the matrix kernels, whose key
+    # blocks then see mask columns long enough to be worked off in parts; the backward takes the
+    # supports from the forward's lists.  With hub keys three keys are attended by most later rows.
+    B, H, N, alpha, causal, sigma = 1, 1, 32768, 1.5, True, 1.0
+    print(f"case both routes N={N} d={d} hub={hub}", flush=True)
+    q, k, v, do = workloads.gaussian_qkv(B, H, N, d, "bf16", sigma, seed=777 + d)
+    if hub:
+        g = torch.Generator().manual_seed(5)
+        dirn = torch.randn(d, generator=g)
+        dirn = dirn / dirn.norm()
+        amp = (sigma * sigma * 3.5 * d ** 0.5) ** 0.5
+        q = (q.float() + amp * dirn).to(q.dtype)
+        k = k.clone()
+        for j in (100, 5000, 20000):
+            k[:, :, j] = (k[:, :, j].float() + amp * dirn).to(k.dtype)
+    Q, K, V, dO = (t.cuda() for t in (q, k, v, do))
+    wf = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, False), dtype=torch.uint8, device="cuda")
+    wb = torch.empty(ea.entmax_attn_workspace_bytes(B, H, N, d, "bf16", causal, True), dtype=torch.uint8, device="cuda")
+    O, tau, mask = ea.entmax_attn_fwd(Q, K, V, alpha, causal, workspace=wf)
+    dQ, dK, dV = ea.entmax_attn_bwd(Q, K, V, O, dO, tau, alpha, causal, block_mask=mask, workspace=wb, fwd_workspace=wf)
+    torch.cuda.synchronize()
+    rows = ea.read_stats(wb)["bwd_gather_rows"]
+    print(f"  rows by gather {rows} of {N}", flush=True)
+    assert N // 4 < rows < N
+    ref, info = parity.check_forward(q, k, v, alpha, causal, O, tau, mask, label="both routes")
+    _, ginfo = parity.check_backward(q, k, v, do, alpha, causal, dQ, dK, dV, label="both routes", tau_ref=ref["tau"])
+    print("  ", info, ginfo, flush=True)
